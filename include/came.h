@@ -1,0 +1,202 @@
+/*
+ * came.h -- C ABI of the MI355X (gfx950) CAME optimizer-step library.
+ *
+ * One call, came_step, applies one step of the CAME optimizer (Luo et al.,
+ * "CAME: Confidence-guided Adaptive Memory Efficient Optimization",
+ * Algorithm 2) to every tensor of a parameter list on one GPU.  For an n x m
+ * weight matrix theta with gradient g (Section 3.1 notation; n = rows,
+ * m = columns, row-major contiguous):
+ *
+ *   r <- beta2 r + (1-beta2) rowsum(g^2 + eps1)        c <- ... colsum(...)
+ *   v  = r c^T / sum(r)                                u  = g / sqrt(v)
+ *   u^ = u / max(1, RMS(u)/d)                          (Eq. 1)
+ *   M <- beta1 M + (1-beta1) u^
+ *   U  = (u^ - M)^2
+ *   R <- beta3 R + (1-beta3) rowsum(U + eps2)          C <- ... colsum(...)
+ *   S  = R C^T / sum(R)                                theta <- theta - eta M / sqrt(S)
+ *
+ * Row/column reductions are sums (as printed), RMS is over the n*m entries of
+ * that tensor, all state starts at zero, and the step counter never enters
+ * the arithmetic (no bias correction in Algorithm 2).  A 1-D parameter of
+ * length n is treated as the n x 1 special case of Algorithm 2, which
+ * degenerates to the unfactored update: v (length n) replaces r c^T / sum r and
+ * s (length n) replaces R C^T / sum R.
+ *
+ * Memory and ownership.  ALL device memory belongs to the caller: the
+ * parameter tensors, the gradient tensors, one `state` blob and one `scratch`
+ * blob whose sizes came_state_size reports.  The library never allocates or
+ * frees device memory.  came_ctx is a host object owned by the library from
+ * came_init_state until came_destroy.  Pointers marked "device" must be
+ * device-accessible addresses on the GPU that is current when the call is
+ * made; pointers marked "host" are ordinary process memory.
+ *
+ * Threading / ordering.  came_step only enqueues kernels (and, when the
+ * parameter/gradient addresses differ from the previous call, one small
+ * host-to-device copy) on the given HIP stream and returns without
+ * synchronising.  Calls on one context must be issued from one thread at a
+ * time and on streams ordered with respect to each other.
+ *
+ * Errors.  Every function returning int gives 0 (CAME_OK) or a negative
+ * came_status.  No exceptions cross this boundary.  On error nothing has been
+ * enqueued unless the code is CAME_EHIP (a HIP runtime call failed part-way).
+ */
+#ifndef CAME_H
+#define CAME_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CAME_OK = 0,
+    CAME_EINVAL = -1, /* null pointer, count <= 0, rows/cols <= 0, ndim not 1 or 2, bad dtype,
+                         beta outside [0,1), eps < 0, clip_d <= 0, non-finite lr, step < 1,
+                         option out of range */
+    CAME_ESIZE = -2,  /* state or scratch blob smaller than came_state_size reports */
+    CAME_EALIGN = -3, /* a device pointer is not aligned as documented */
+    CAME_EHIP = -4,   /* a HIP runtime call failed; see came_last_hip_error */
+    CAME_ENOMEM = -5  /* host allocation failed */
+} came_status;
+
+typedef enum {
+    CAME_GRAD_F32 = 0, /* gradient stored as IEEE binary32 */
+    CAME_GRAD_BF16 = 1 /* gradient stored as bfloat16 (upper 16 bits of binary32); widened exactly */
+} came_grad_dtype;
+
+typedef enum {
+    CAME_ALGO_CAME = 0,     /* Algorithm 2 */
+    CAME_ALGO_ADAFACTOR = 1 /* Algorithm 1 (Adafactor with momentum): Algorithm 2 without the
+                               instability/confidence lines, theta <- theta - eta M; R, C stay zero */
+} came_algo;
+
+/* One parameter tensor.  ndim == 2: rows x cols matrix (factored statistics).
+ * ndim == 1: vector of `rows` entries, cols must be 1 (unfactored statistics).
+ * Parameters (theta) and all optimizer state are binary32; only the gradient
+ * dtype varies. */
+typedef struct {
+    int64_t rows;
+    int64_t cols;
+    int32_t ndim;
+    int32_t grad_dtype; /* came_grad_dtype */
+} came_tensor_desc;
+
+/* Hyper-parameters of Algorithm 2's input list, passed per call so that the
+ * caller can schedule them.  Doubles, so that 1-beta is formed without first
+ * rounding beta to binary32 (1-0.9999f is off by 1e-3 relative). */
+typedef struct {
+    double beta1;  /* EMA coefficient of the momentum M,          [0,1) */
+    double beta2;  /* EMA coefficient of r, c (second moment),    [0,1) */
+    double beta3;  /* EMA coefficient of R, C (confidence),       [0,1) */
+    double eps1;   /* added to g^2 inside the row/column sums,    >= 0  */
+    double eps2;   /* added to U inside the row/column sums,      >= 0  */
+    double clip_d; /* RMS clipping threshold d of Eq. 1,          > 0   */
+} came_hyper;
+
+/* Planner knobs; pass NULL for defaults.  Zero in a field means "default". */
+typedef struct {
+    int32_t tile_rows;       /* rows of a matrix one workgroup sweeps per tile: multiple of 4,
+                                4..4096; 0 = chosen from the list so the launch fills the GPU */
+    int32_t algo;            /* came_algo */
+    int64_t group_elements;  /* 0 = all tensors in one launch group; otherwise consecutive
+                                tensors are packed into groups of at most about this many
+                                elements and the phases run group after group, so that a
+                                group's gradient and momentum can stay in the on-package cache
+                                between phases */
+    int32_t reserved[4];     /* must be zero */
+} came_options;
+
+/* Device addresses of one tensor's state inside the caller's state blob.
+ * Matrix: m = M (rows*cols), r, R (rows), c, C (cols).
+ * Vector: m = M, r = v, R = s (rows each); c = C = NULL.   All binary32. */
+typedef struct {
+    void *m, *r, *c, *R, *C;
+} came_state_view;
+
+typedef struct came_ctx came_ctx;
+
+/*
+ * Bytes the caller must provide for the optimizer state (Algorithm 2's M, r,
+ * c, R, C for every tensor: rows*cols + 2(rows+cols) floats per matrix, 3*rows
+ * per vector, each array padded to 256 B) and for the library's scratch
+ * (tile/descriptor tables, per-tile partial sums, per-tensor scalars).
+ * Host-only: touches no device.  descs: host, `count` entries.
+ */
+int came_state_size(const came_tensor_desc *descs, int32_t count, const came_options *opts,
+                    size_t *state_bytes, size_t *scratch_bytes);
+
+/*
+ * Creates a context for the tensor list, uploads the launch plan into
+ * `scratch_dev` and zero-fills `state_dev` (M_0 = r_0 = c_0 = 0 from
+ * Algorithm 2's input list; R_0 = C_0 = 0 likewise) on `hip_stream`
+ * (a hipStream_t, or NULL for the default stream).  state_dev / scratch_dev:
+ * device, 256-byte aligned, at least the sizes came_state_size reports; they
+ * must stay valid and untouched by others (except through came_state_view)
+ * until came_destroy.  *out receives the context.
+ */
+int came_init_state(came_ctx **out, const came_tensor_desc *descs, int32_t count,
+                    const came_options *opts, void *state_dev, size_t state_bytes,
+                    void *scratch_dev, size_t scratch_bytes, void *hip_stream);
+
+/*
+ * One optimizer step over the whole list (Algorithm 2, one iteration of the
+ * loop; Algorithm 1 if the context was created with CAME_ALGO_ADAFACTOR).
+ * theta_dev / grad_dev: host arrays of `count` device pointers, one per
+ * tensor in descriptor order; theta[i] (binary32, updated in place) and
+ * grad[i] (dtype of the descriptor, read only) are contiguous, 16-byte
+ * aligned, and alias neither each other nor the state/scratch blobs.
+ * lr is the learning rate eta; step is the 1-based iteration number t, which
+ * is validated (must be >= 1) and recorded but, as in Algorithm 2, never used
+ * in the arithmetic.  Asynchronous on hip_stream.
+ */
+int came_step(came_ctx *ctx, void *const *theta_dev, const void *const *grad_dev,
+              const came_hyper *hyper, double lr, int64_t step, void *hip_stream);
+
+/* Device addresses of tensor i's state arrays (for checkpointing and tests). */
+int came_state_view_get(const came_ctx *ctx, int32_t i, came_state_view *view);
+
+/*
+ * Plan introspection (host only, no device): fills out[0..7] with
+ * { tile_rows chosen, tile_cols, number of sweep work items per phase,
+ *   number of finalize workgroups per phase, number of launch groups,
+ *   number of matrices, number of vectors, total elements }.
+ */
+int came_plan_query(const came_tensor_desc *descs, int32_t count, const came_options *opts,
+                    int64_t out[8]);
+
+/*
+ * Algorithmic HBM bytes per parameter of the shipped three-sweep design for a
+ * gradient element of `grad_bytes` bytes: sweep 1 reads g; sweep 2 reads g and
+ * M; sweep 3 reads g, M, theta and writes M, theta  ->  20 + 3*grad_bytes.
+ * which: 0 = whole step, 1/2/3 = that sweep alone.
+ */
+double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which);
+
+/*
+ * Built-in phase timer.  While enabled, came_step brackets each of its five
+ * launches per group with HIP events on the step's stream.  came_profile_read
+ * waits for the recorded events, adds the elapsed milliseconds and launch
+ * counts per phase { sweep 1, finalize 1, sweep 2, finalize 2, sweep 3 } since
+ * the previous read into phase_ms[5] / phase_launches[5], and forgets them.
+ * At most 65536 launches are kept between reads; further ones go untimed.
+ */
+int came_profile_enable(came_ctx *ctx, int32_t on);
+int came_profile_read(came_ctx *ctx, double phase_ms[5], int64_t phase_launches[5]);
+
+/* hipError_t of the last failed HIP call on this context (0 if none). */
+int came_last_hip_error(const came_ctx *ctx);
+
+/* Releases the host context.  Does not touch or free any device memory and
+ * does not synchronise: the caller must keep the blobs alive until work
+ * already enqueued has finished. */
+void came_destroy(came_ctx *ctx);
+
+/* Static, never NULL. */
+const char *came_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAME_H */

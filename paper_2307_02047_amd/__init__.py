@@ -1,0 +1,8 @@
+"""MI355X-native CAME optimizer step: a C-ABI HIP library plus this thin binding.
+
+The arithmetic of the step runs entirely in the gfx950 kernels of
+libcame_hip.so; Python only marshals arguments.  PyTorch is used for device
+memory and streams.
+"""
+from .binding import (CameHyper, CameStep, GRAD_BF16, GRAD_F32, ALGO_CAME, ALGO_ADAFACTOR,  # noqa: F401
+                      CameError, algorithmic_bytes_per_param, load_library, plan_query, state_size)

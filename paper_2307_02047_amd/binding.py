@@ -1,0 +1,260 @@
+"""ctypes binding of include/came.h.  Same names, argument marshalling only.
+
+There is no CPU fallback: if libcame_hip.so is missing the import of the
+library fails loudly (build it with `python -m paper_2307_02047_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libcame_hip.so")
+
+GRAD_F32, GRAD_BF16 = 0, 1
+ALGO_CAME, ALGO_ADAFACTOR = 0, 1
+
+EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_state_view_get",
+           "came_plan_query", "came_algorithmic_bytes_per_param", "came_profile_enable",
+           "came_profile_read", "came_last_hip_error",
+           "came_destroy", "came_strerror")
+
+
+class CameError(RuntimeError):
+    def __init__(self, status: int, what: str, hip_error: int = 0):
+        self.status, self.hip_error = status, hip_error
+        extra = f" (hipError_t {hip_error})" if hip_error else ""
+        super().__init__(f"{what}: status {status}{extra}")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("ndim", ctypes.c_int32),
+                ("grad_dtype", ctypes.c_int32)]
+
+
+class _Hyper(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_double) for k in ("beta1", "beta2", "beta3", "eps1", "eps2", "clip_d")]
+
+
+class _Options(ctypes.Structure):
+    _fields_ = [("tile_rows", ctypes.c_int32), ("algo", ctypes.c_int32),
+                ("group_elements", ctypes.c_int64), ("reserved", ctypes.c_int32 * 4)]
+
+
+class _View(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_void_p) for k in ("m", "r", "c", "R", "C")]
+
+
+@dataclass
+class CameHyper:
+    """Algorithm 2's hyper-parameters (defaults: Section 3.3 / Section 4.1)."""
+    beta1: float = 0.9
+    beta2: float = 0.999
+    beta3: float = 0.9999
+    eps1: float = 1e-30
+    eps2: float = 1e-16
+    clip_d: float = 1.0
+
+    def _c(self) -> _Hyper:
+        return _Hyper(self.beta1, self.beta2, self.beta3, self.eps1, self.eps2, self.clip_d)
+
+
+_lib = None
+
+
+def load_library(path: str | None = None) -> ctypes.CDLL:
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or _LIB_PATH
+    if not os.path.exists(p):
+        raise ImportError(f"{p} not found: build it with `python -m paper_2307_02047_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = ctypes.CDLL(p)
+    vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    lib.came_state_size.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), szp, szp]
+    lib.came_state_size.restype = ctypes.c_int
+    lib.came_init_state.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options),
+                                    vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+    lib.came_init_state.restype = ctypes.c_int
+    lib.came_step.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(_Hyper), dbl, i64, vp]
+    lib.came_step.restype = ctypes.c_int
+    lib.came_state_view_get.argtypes = [vp, i32, ctypes.POINTER(_View)]
+    lib.came_state_view_get.restype = ctypes.c_int
+    lib.came_plan_query.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), ctypes.POINTER(i64)]
+    lib.came_plan_query.restype = ctypes.c_int
+    lib.came_algorithmic_bytes_per_param.argtypes = [i32, i32]
+    lib.came_algorithmic_bytes_per_param.restype = dbl
+    lib.came_profile_enable.argtypes = [vp, i32]
+    lib.came_profile_enable.restype = ctypes.c_int
+    lib.came_profile_read.argtypes = [vp, ctypes.POINTER(dbl), ctypes.POINTER(i64)]
+    lib.came_profile_read.restype = ctypes.c_int
+    lib.came_last_hip_error.argtypes = [vp]
+    lib.came_last_hip_error.restype = ctypes.c_int
+    lib.came_destroy.argtypes = [vp]
+    lib.came_destroy.restype = None
+    lib.came_strerror.argtypes = [ctypes.c_int]
+    lib.came_strerror.restype = ctypes.c_char_p
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _descs(shapes: Sequence[Sequence[int]], grad_dtypes: Sequence[int]):
+    arr = (_Desc * len(shapes))()
+    for i, (s, d) in enumerate(zip(shapes, grad_dtypes)):
+        s = tuple(int(x) for x in s)
+        if len(s) == 2:
+            arr[i] = _Desc(s[0], s[1], 2, int(d))
+        elif len(s) == 1:
+            arr[i] = _Desc(s[0], 1, 1, int(d))
+        else:
+            raise ValueError(f"tensor {i}: only 1-D and 2-D parameters are supported, got shape {s}")
+    return arr
+
+
+def _options(tile_rows: int = 0, algo: int = ALGO_CAME, group_elements: int = 0):
+    o = _Options()
+    o.tile_rows, o.algo, o.group_elements = int(tile_rows), int(algo), int(group_elements)
+    return o
+
+
+def _check(lib, status: int, what: str, ctx=None):
+    if status != 0:
+        msg = lib.came_strerror(status).decode()
+        hip = lib.came_last_hip_error(ctx) if ctx else 0
+        raise CameError(status, f"{what}: {msg}", hip)
+
+
+def state_size(shapes, grad_dtypes, **opts) -> tuple[int, int]:
+    """came_state_size: (state_bytes, scratch_bytes).  Host only."""
+    lib = load_library()
+    d, o = _descs(shapes, grad_dtypes), _options(**opts)
+    sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib, lib.came_state_size(d, len(shapes), ctypes.byref(o), ctypes.byref(sb), ctypes.byref(wb)),
+           "came_state_size")
+    return sb.value, wb.value
+
+
+def plan_query(shapes, grad_dtypes, **opts) -> dict:
+    """came_plan_query as a dict.  Host only."""
+    lib = load_library()
+    d, o = _descs(shapes, grad_dtypes), _options(**opts)
+    out = (ctypes.c_int64 * 8)()
+    _check(lib, lib.came_plan_query(d, len(shapes), ctypes.byref(o), out), "came_plan_query")
+    keys = ("tile_rows", "tile_cols", "sweep_items", "finalize_items", "groups", "matrices", "vectors",
+            "elements")
+    return dict(zip(keys, [int(x) for x in out]))
+
+
+def algorithmic_bytes_per_param(grad_bytes: int, which: int = 0) -> float:
+    return float(load_library().came_algorithmic_bytes_per_param(int(grad_bytes), int(which)))
+
+
+class CameStep:
+    """came_init_state / came_step / came_state_view_get / came_destroy for one tensor list.
+
+    The state and scratch blobs are torch uint8 tensors on `device` (PyTorch is the
+    device-memory allocator); everything else happens inside the library.
+    """
+
+    def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
+                 group_elements: int = 0):
+        import torch
+        self._torch = torch
+        self.lib = load_library()
+        self.shapes = [tuple(int(x) for x in s) for s in shapes]
+        self.grad_dtypes = [int(d) for d in grad_dtypes]
+        self.device = torch.device(device)
+        self._d = _descs(self.shapes, self.grad_dtypes)
+        self._o = _options(tile_rows, algo, group_elements)
+        n = len(self.shapes)
+        sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
+        _check(self.lib, self.lib.came_state_size(self._d, n, ctypes.byref(self._o), ctypes.byref(sb),
+                                                  ctypes.byref(wb)), "came_state_size")
+        self.state_bytes, self.scratch_bytes = sb.value, wb.value
+        with torch.cuda.device(self.device):
+            self.state = torch.empty(self.state_bytes, dtype=torch.uint8, device=self.device)
+            self.scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=self.device)
+            self._ctx = ctypes.c_void_p()
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            st = self.lib.came_init_state(ctypes.byref(self._ctx), self._d, n, ctypes.byref(self._o),
+                                          self.state.data_ptr(), self.state_bytes,
+                                          self.scratch.data_ptr(), self.scratch_bytes, stream)
+        _check(self.lib, st, "came_init_state")
+        self._theta_arr = (ctypes.c_void_p * n)()
+        self._grad_arr = (ctypes.c_void_p * n)()
+
+    def step(self, thetas, grads, hyper: CameHyper, lr: float, step: int, stream=None) -> None:
+        torch = self._torch
+        n = len(self.shapes)
+        assert len(thetas) == n and len(grads) == n
+        for i in range(n):
+            self._theta_arr[i] = thetas[i].data_ptr()
+            self._grad_arr[i] = grads[i].data_ptr()
+        h = hyper._c()
+        with torch.cuda.device(self.device):
+            s = stream if stream is not None else torch.cuda.current_stream(self.device).cuda_stream
+            st = self.lib.came_step(self._ctx, self._theta_arr, self._grad_arr, ctypes.byref(h), float(lr),
+                                    int(step), s)
+        _check(self.lib, st, "came_step", self._ctx)
+
+    def check_tensors(self, thetas, grads) -> None:
+        """Host-side shape/dtype check of what step() will hand to the kernels."""
+        torch = self._torch
+        for i, (s, d) in enumerate(zip(self.shapes, self.grad_dtypes)):
+            want = torch.bfloat16 if d == GRAD_BF16 else torch.float32
+            t, g = thetas[i], grads[i]
+            if tuple(t.shape) != s or tuple(g.shape) != s:
+                raise ValueError(f"tensor {i}: shapes {tuple(t.shape)}/{tuple(g.shape)} do not match plan {s}")
+            if t.dtype != torch.float32 or g.dtype != want:
+                raise ValueError(f"tensor {i}: dtypes {t.dtype}/{g.dtype}, expected float32/{want}")
+            if not (t.is_contiguous() and g.is_contiguous()):
+                raise ValueError(f"tensor {i}: tensors must be contiguous")
+            if t.device != self.device or g.device != self.device:
+                raise ValueError(f"tensor {i}: tensors must live on {self.device}")
+
+    def state_view(self, i: int) -> dict:
+        """came_state_view_get as float32 torch views into the state blob."""
+        v = _View()
+        _check(self.lib, self.lib.came_state_view_get(self._ctx, int(i), ctypes.byref(v)), "came_state_view_get")
+        base = self.state.data_ptr()
+        f = self.state.view(self._torch.float32)
+        s = self.shapes[i]
+        n, m = (s[0], s[1]) if len(s) == 2 else (s[0], 1)
+
+        def sl(ptr, count, shape):
+            if not ptr:
+                return None
+            off = (ptr - base) // 4
+            return f[off:off + count].view(shape)
+
+        return {"M": sl(v.m, n * m, s), "r": sl(v.r, n, (n,)), "c": sl(v.c, m, (m,)),
+                "R": sl(v.R, n, (n,)), "C": sl(v.C, m, (m,))}
+
+    PHASES = ("sweep1", "finalize1", "sweep2", "finalize2", "sweep3")
+
+    def profile_enable(self, on: bool = True) -> None:
+        _check(self.lib, self.lib.came_profile_enable(self._ctx, 1 if on else 0), "came_profile_enable")
+
+    def profile_read(self) -> dict:
+        """came_profile_read: {phase: (total_ms, launches)} since the previous read."""
+        ms = (ctypes.c_double * 5)()
+        cnt = (ctypes.c_int64 * 5)()
+        _check(self.lib, self.lib.came_profile_read(self._ctx, ms, cnt), "came_profile_read", self._ctx)
+        return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(self.PHASES)}
+
+    def close(self) -> None:
+        if getattr(self, "_ctx", None) and self._ctx.value:
+            self._torch.cuda.synchronize(self.device)
+            self.lib.came_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,338 @@
+// C ABI of the library (declared in include/came.h): validation, plan upload,
+// per-step pointer table and the launch sequence.  Host code only; the kernels
+// are in came_kernels.hip.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "came.h"
+#include "came_kernels.h"
+#include "came_plan.h"
+
+using namespace came;
+
+struct came_ctx {
+    Plan plan;
+    char* scratch = nullptr;  // caller's scratch blob (device)
+    float* state = nullptr;   // caller's state blob (device)
+    // pinned host staging for the per-step pointer table, one region per slot
+    char* pinned = nullptr;
+    hipEvent_t slot_event[kPtrSlots] = {};
+    bool slot_used[kPtrSlots] = {};
+    int slot = -1;
+    std::vector<const void*> cached;  // theta[count] then grad[count] of the current slot
+    int last_hip = 0;
+    int64_t last_step = 0;
+    // phase timer
+    bool profiling = false;
+    struct Timed { hipEvent_t start, stop; int phase; };
+    std::vector<Timed> timed;
+};
+
+namespace {
+
+inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int hip_fail(came_ctx* ctx, hipError_t e)
+{
+    if (ctx) ctx->last_hip = static_cast<int>(e);
+    return CAME_EHIP;
+}
+
+constexpr size_t kMaxTimed = 65536;
+
+// Runs `launch` on stream s, bracketed by timing events when the phase timer is on.
+template <class F>
+hipError_t timed_launch(came_ctx* ctx, int phase, hipStream_t s, F launch)
+{
+    if (!ctx->profiling || ctx->timed.size() >= kMaxTimed) return launch();
+    came_ctx::Timed t{};
+    t.phase = phase;
+    hipError_t e = hipEventCreate(&t.start);
+    if (e != hipSuccess) return e;
+    e = hipEventCreate(&t.stop);
+    if (e != hipSuccess) { (void)hipEventDestroy(t.start); return e; }
+    e = hipEventRecord(t.start, s);
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(t.stop, s);
+    if (e != hipSuccess) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); return e; }
+    ctx->timed.push_back(t);
+    return hipSuccess;
+}
+
+DeviceTables tables_for(const came_ctx* ctx, int slot)
+{
+    const Plan& p = ctx->plan;
+    DeviceTables t{};
+    t.metas = reinterpret_cast<const TensorMeta*>(ctx->scratch + p.off_metas);
+    t.items = reinterpret_cast<const WorkItem*>(ctx->scratch + p.off_items);
+    t.fins = reinterpret_cast<const FinalizeItem*>(ctx->scratch + p.off_fins);
+    t.scalars = reinterpret_cast<TensorScalars*>(ctx->scratch + p.off_scalars);
+    char* slot_base = ctx->scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot);
+    t.theta = reinterpret_cast<void* const*>(slot_base);
+    t.grad = reinterpret_cast<const void* const*>(slot_base + sizeof(void*) * p.descs.size());
+    t.state = ctx->state;
+    t.scratch = ctx->scratch;
+    return t;
+}
+
+}  // namespace
+
+extern "C" {
+
+int came_state_size(const came_tensor_desc* descs, int32_t count, const came_options* opts,
+                    size_t* state_bytes, size_t* scratch_bytes)
+{
+    if (!state_bytes || !scratch_bytes) return CAME_EINVAL;
+    Plan plan;
+    const int rc = build_plan(descs, count, opts, &plan);
+    if (rc != CAME_OK) return rc;
+    *state_bytes = plan.state_bytes;
+    *scratch_bytes = plan.scratch_bytes;
+    return CAME_OK;
+}
+
+int came_plan_query(const came_tensor_desc* descs, int32_t count, const came_options* opts,
+                    int64_t out[8])
+{
+    if (!out) return CAME_EINVAL;
+    Plan plan;
+    const int rc = build_plan(descs, count, opts, &plan);
+    if (rc != CAME_OK) return rc;
+    int64_t tiles = 0;
+    for (const Group& g : plan.groups) tiles += g.item_end - g.item_begin;
+    out[0] = plan.tile_rows;
+    out[1] = kTileCols;
+    out[2] = tiles;
+    out[3] = static_cast<int64_t>(plan.fins.size());
+    out[4] = static_cast<int64_t>(plan.groups.size());
+    out[5] = plan.n_matrices;
+    out[6] = plan.n_vectors;
+    out[7] = plan.total_elements;
+    return CAME_OK;
+}
+
+double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which)
+{
+    const double g = static_cast<double>(grad_bytes);
+    switch (which) {
+        case 0: return 20.0 + 3.0 * g;  // whole step
+        case 1: return g;               // sweep 1: read g
+        case 2: return g + 4.0;         // sweep 2: read g, M
+        case 3: return g + 16.0;        // sweep 3: read g, M, theta; write M, theta
+        default: return 0.0;
+    }
+}
+
+int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count,
+                    const came_options* opts, void* state_dev, size_t state_bytes,
+                    void* scratch_dev, size_t scratch_bytes, void* hip_stream)
+{
+    if (!out) return CAME_EINVAL;
+    *out = nullptr;
+    if (!state_dev || !scratch_dev) return CAME_EINVAL;
+    came_ctx* ctx = new (std::nothrow) came_ctx();
+    if (!ctx) return CAME_ENOMEM;
+    int rc = build_plan(descs, count, opts, &ctx->plan);
+    if (rc != CAME_OK) { delete ctx; return rc; }
+    const Plan& p = ctx->plan;
+    if (state_bytes < p.state_bytes || scratch_bytes < p.scratch_bytes) { delete ctx; return CAME_ESIZE; }
+    if (!aligned_to(state_dev, 256) || !aligned_to(scratch_dev, 256)) { delete ctx; return CAME_EALIGN; }
+    ctx->state = static_cast<float*>(state_dev);
+    ctx->scratch = static_cast<char*>(scratch_dev);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), p.ptr_slot_bytes * kPtrSlots, hipHostMallocDefault);
+    if (e != hipSuccess) { delete ctx; return CAME_EHIP; }
+    for (int k = 0; k < kPtrSlots; ++k) {
+        e = hipEventCreateWithFlags(&ctx->slot_event[k], hipEventDisableTiming);
+        if (e != hipSuccess) {
+            for (int j = 0; j < k; ++j) (void)hipEventDestroy(ctx->slot_event[j]);
+            (void)hipHostFree(ctx->pinned);
+            delete ctx;
+            return CAME_EHIP;
+        }
+    }
+
+    // plan tables -> scratch (synchronous copies from pageable memory), then zero the
+    // per-tensor scalars/counters and the optimizer state with fill kernels
+    auto fail = [&](hipError_t err) {
+        const int code = hip_fail(ctx, err);
+        came_destroy(ctx);
+        return code;
+    };
+    e = hipMemcpy(ctx->scratch + p.off_metas, p.metas.data(), sizeof(TensorMeta) * p.metas.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(e);
+    if (!p.items.empty()) {
+        e = hipMemcpy(ctx->scratch + p.off_items, p.items.data(), sizeof(WorkItem) * p.items.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail(e);
+    }
+    if (!p.fins.empty()) {
+        e = hipMemcpy(ctx->scratch + p.off_fins, p.fins.data(), sizeof(FinalizeItem) * p.fins.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail(e);
+    }
+    e = launch_fill_zero_bytes(ctx->scratch + p.off_scalars, sizeof(TensorScalars) * p.descs.size(), s);
+    if (e != hipSuccess) return fail(e);
+    e = launch_fill_zero(ctx->state, p.state_bytes / sizeof(float), s);
+    if (e != hipSuccess) return fail(e);
+    *out = ctx;
+    return CAME_OK;
+}
+
+int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+              const came_hyper* hyper, double lr, int64_t step, void* hip_stream)
+{
+    if (!ctx || !theta_dev || !grad_dev) return CAME_EINVAL;
+    int rc = validate_hyper(hyper, lr, step);
+    if (rc != CAME_OK) return rc;
+    const Plan& p = ctx->plan;
+    const size_t count = p.descs.size();
+    for (size_t t = 0; t < count; ++t) {
+        if (!theta_dev[t] || !grad_dev[t]) return CAME_EINVAL;
+        if (!aligned_to(theta_dev[t], 16) || !aligned_to(grad_dev[t], 16)) return CAME_EALIGN;
+        if (theta_dev[t] == grad_dev[t]) return CAME_EINVAL;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    // pointer table: re-upload only when an address changed since the last call
+    bool changed = ctx->slot < 0;
+    if (!changed) {
+        for (size_t t = 0; t < count && !changed; ++t)
+            changed = ctx->cached[t] != theta_dev[t] || ctx->cached[count + t] != grad_dev[t];
+    }
+    if (changed) {
+        const int slot = (ctx->slot + 1) % kPtrSlots;
+        if (ctx->slot_used[slot]) {
+            const hipError_t e = hipEventSynchronize(ctx->slot_event[slot]);
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
+        ctx->cached.resize(2 * count);
+        for (size_t t = 0; t < count; ++t) {
+            ctx->cached[t] = theta_dev[t];
+            ctx->cached[count + t] = grad_dev[t];
+        }
+        char* host_slot = ctx->pinned + p.ptr_slot_bytes * static_cast<size_t>(slot);
+        std::memcpy(host_slot, ctx->cached.data(), sizeof(void*) * 2 * count);
+        hipError_t e = hipMemcpyAsync(ctx->scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot),
+                                      host_slot, sizeof(void*) * 2 * count, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
+        e = hipEventRecord(ctx->slot_event[slot], s);
+        if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
+        ctx->slot_used[slot] = true;
+        ctx->slot = slot;
+    }
+
+    SweepHyper sh{};
+    sh.beta1 = static_cast<float>(hyper->beta1);
+    sh.one_minus_beta1 = static_cast<float>(1.0 - hyper->beta1);
+    sh.beta2 = static_cast<float>(hyper->beta2);
+    sh.one_minus_beta2 = static_cast<float>(1.0 - hyper->beta2);
+    sh.beta3 = static_cast<float>(hyper->beta3);
+    sh.one_minus_beta3 = static_cast<float>(1.0 - hyper->beta3);
+    sh.eps1 = static_cast<float>(hyper->eps1);
+    sh.eps2 = static_cast<float>(hyper->eps2);
+    sh.lr = static_cast<float>(lr);
+    sh.algo = p.algo;
+    FinalizeHyper fh{};
+    fh.beta1 = hyper->beta1;
+    fh.beta2 = hyper->beta2;
+    fh.one_minus_beta2 = 1.0 - hyper->beta2;
+    fh.beta3 = hyper->beta3;
+    fh.one_minus_beta3 = 1.0 - hyper->beta3;
+    fh.eps1 = hyper->eps1;
+    fh.eps2 = hyper->eps2;
+    fh.clip_d = hyper->clip_d;
+    fh.algo = p.algo;
+
+    const DeviceTables tb = tables_for(ctx, ctx->slot);
+    for (const Group& g : p.groups) {
+        hipError_t e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, g.item_begin, g.item_end, sh, fh, s); });
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        if (g.tile_end == g.item_begin) continue;  // vectors only
+        e = timed_launch(ctx, 1, s, [&] { return launch_finalize1(tb, g.fin_begin, g.fin_end, fh, s); });
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, g.item_begin, g.tile_end, sh, s); });
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        e = timed_launch(ctx, 3, s, [&] { return launch_finalize2(tb, g.fin_begin, g.fin_end, fh, s); });
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, g.item_begin, g.tile_end, sh, s); });
+        if (e != hipSuccess) return hip_fail(ctx, e);
+    }
+    ctx->last_step = step;
+    return CAME_OK;
+}
+
+int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
+{
+    if (!ctx || !view) return CAME_EINVAL;
+    if (i < 0 || static_cast<size_t>(i) >= ctx->plan.metas.size()) return CAME_EINVAL;
+    const TensorMeta& tm = ctx->plan.metas[i];
+    view->m = ctx->state + tm.off_M;
+    view->r = ctx->state + tm.off_r;
+    view->R = ctx->state + tm.off_R;
+    view->c = tm.off_c >= 0 ? ctx->state + tm.off_c : nullptr;
+    view->C = tm.off_C >= 0 ? ctx->state + tm.off_C : nullptr;
+    return CAME_OK;
+}
+
+int came_profile_enable(came_ctx* ctx, int32_t on)
+{
+    if (!ctx) return CAME_EINVAL;
+    ctx->profiling = on != 0;
+    return CAME_OK;
+}
+
+int came_profile_read(came_ctx* ctx, double phase_ms[5], int64_t phase_launches[5])
+{
+    if (!ctx || !phase_ms || !phase_launches) return CAME_EINVAL;
+    for (int k = 0; k < 5; ++k) { phase_ms[k] = 0.0; phase_launches[k] = 0; }
+    int rc = CAME_OK;
+    for (const came_ctx::Timed& t : ctx->timed) {
+        hipError_t e = hipEventSynchronize(t.stop);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.start, t.stop);
+        if (e == hipSuccess) {
+            phase_ms[t.phase] += static_cast<double>(ms);
+            phase_launches[t.phase] += 1;
+        } else {
+            rc = hip_fail(ctx, e);
+        }
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    ctx->timed.clear();
+    return rc;
+}
+
+int came_last_hip_error(const came_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+void came_destroy(came_ctx* ctx)
+{
+    if (!ctx) return;
+    for (const came_ctx::Timed& t : ctx->timed) {
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    for (int k = 0; k < kPtrSlots; ++k)
+        if (ctx->slot_event[k]) (void)hipEventDestroy(ctx->slot_event[k]);
+    if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    delete ctx;
+}
+
+const char* came_strerror(int status)
+{
+    switch (status) {
+        case CAME_OK: return "ok";
+        case CAME_EINVAL: return "invalid argument";
+        case CAME_ESIZE: return "state or scratch blob too small";
+        case CAME_EALIGN: return "device pointer not aligned as required";
+        case CAME_EHIP: return "HIP runtime call failed";
+        case CAME_ENOMEM: return "host allocation failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

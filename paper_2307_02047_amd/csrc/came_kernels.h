@@ -1,0 +1,62 @@
+// Launch wrappers of the gfx950 kernels (defined in came_kernels.hip).
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include "came_plan.h"
+
+namespace came {
+
+// Coefficients the sweep kernels use, rounded once from the caller's doubles.
+struct SweepHyper {
+    float beta1, one_minus_beta1;
+    float beta2, one_minus_beta2;
+    float beta3, one_minus_beta3;
+    float eps1, eps2;
+    float lr;
+    int32_t algo;
+};
+
+// Coefficients the finalize kernels use (O(n+m) work, done in double).
+struct FinalizeHyper {
+    double beta1;
+    double beta2, one_minus_beta2;
+    double beta3, one_minus_beta3;
+    double eps1, eps2;
+    double clip_d;
+    int32_t algo;
+};
+
+// Device-side views of the scratch sections plus the caller's state blob.
+struct DeviceTables {
+    const TensorMeta* metas;
+    const WorkItem* items;
+    const FinalizeItem* fins;
+    TensorScalars* scalars;
+    void* const* theta;        // current pointer slot: theta[count]
+    const void* const* grad;   //                       grad[count]
+    float* state;
+    char* scratch;
+};
+
+hipError_t launch_fill_zero(float* p, size_t count, hipStream_t s);
+hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s);
+
+// Sweep 1: row/column sums of g^2 for the matrix tiles [begin, tile_end) and the
+// complete update of the vectors [tile_end, item_end).
+hipError_t launch_sweep1(const DeviceTables& t, int32_t item_begin, int32_t item_end,
+                         const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);
+// Finalize 1: r, c and sqrt(sum r).
+hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
+                            const FinalizeHyper& h, hipStream_t s);
+// Sweep 2: row/column sums of u^2, u*M, M^2 and the per-tile sum of u^2.
+hipError_t launch_sweep2(const DeviceTables& t, int32_t item_begin, int32_t tile_end,
+                         const SweepHyper& h, hipStream_t s);
+// Finalize 2: kappa (Eq. 1), R, C and sqrt(sum R).
+hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
+                            const FinalizeHyper& h, hipStream_t s);
+// Sweep 3: momentum and parameter update.
+hipError_t launch_sweep3(const DeviceTables& t, int32_t item_begin, int32_t tile_end,
+                         const SweepHyper& h, hipStream_t s);
+
+}  // namespace came

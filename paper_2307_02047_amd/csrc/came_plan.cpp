@@ -1,0 +1,184 @@
+// Host-only planner: argument validation, state-blob layout (Algorithm 2's
+// M, r, c, R, C per tensor), scratch layout and the tile tables that turn each
+// phase of the step into one grouped launch over all tensors.
+#include "came_plan.h"
+
+#include <algorithm>
+#include <cmath>
+
+namespace came {
+
+namespace {
+
+constexpr int64_t kAlignFloats = 64;  // 256-byte alignment of every state array
+constexpr size_t kAlignBytes = 256;
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Rows per tile when the caller does not choose: the largest multiple of 16 up
+// to 512 that still yields at least `want` tiles, so that a launch has many
+// workgroups per compute unit (256 CUs) while the per-row-block column
+// partials stay a small fraction of the traffic.
+int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count)
+{
+    const int64_t want = 256 * 24;
+    int32_t best = 16;
+    for (int32_t tr = 512; tr >= 16; tr -= 16) {
+        int64_t tiles = 0;
+        for (int32_t t = 0; t < count; ++t)
+            if (d[t].ndim == 2) tiles += ceil_div(d[t].rows, tr) * ceil_div(d[t].cols, kTileCols);
+        if (tiles >= want) { best = tr; break; }
+    }
+    return best;
+}
+
+}  // namespace
+
+int validate_hyper(const came_hyper* h, double lr, int64_t step)
+{
+    if (!h) return CAME_EINVAL;
+    const double betas[3] = {h->beta1, h->beta2, h->beta3};
+    for (double b : betas)
+        if (!(b >= 0.0 && b < 1.0)) return CAME_EINVAL;
+    if (!(h->eps1 >= 0.0) || !std::isfinite(h->eps1)) return CAME_EINVAL;
+    if (!(h->eps2 >= 0.0) || !std::isfinite(h->eps2)) return CAME_EINVAL;
+    if (!(h->clip_d > 0.0) || !std::isfinite(h->clip_d)) return CAME_EINVAL;
+    if (!std::isfinite(lr)) return CAME_EINVAL;
+    if (step < 1) return CAME_EINVAL;
+    return CAME_OK;
+}
+
+int build_plan(const came_tensor_desc* descs, int32_t count, const came_options* opts, Plan* plan)
+{
+    if (!descs || !plan || count <= 0) return CAME_EINVAL;
+    came_options o{};
+    if (opts) o = *opts;
+    for (int32_t v : o.reserved)
+        if (v != 0) return CAME_EINVAL;
+    if (o.algo != CAME_ALGO_CAME && o.algo != CAME_ALGO_ADAFACTOR) return CAME_EINVAL;
+    if (o.tile_rows != 0 && (o.tile_rows < 4 || o.tile_rows > 4096 || o.tile_rows % 4 != 0))
+        return CAME_EINVAL;
+    if (o.group_elements < 0) return CAME_EINVAL;
+
+    for (int32_t t = 0; t < count; ++t) {
+        const came_tensor_desc& d = descs[t];
+        if (d.ndim != 1 && d.ndim != 2) return CAME_EINVAL;
+        if (d.rows <= 0 || d.cols <= 0) return CAME_EINVAL;
+        if (d.ndim == 1 && d.cols != 1) return CAME_EINVAL;
+        if (d.grad_dtype != CAME_GRAD_F32 && d.grad_dtype != CAME_GRAD_BF16) return CAME_EINVAL;
+        if (d.rows > (int64_t(1) << 40) || d.cols > (int64_t(1) << 40)) return CAME_EINVAL;
+        if (d.rows * d.cols > (int64_t(1) << 46)) return CAME_EINVAL;
+    }
+
+    Plan& p = *plan;
+    p = Plan{};
+    p.descs.assign(descs, descs + count);
+    p.algo = o.algo;
+    p.tile_rows = o.tile_rows ? o.tile_rows : auto_tile_rows(descs, count);
+    p.metas.resize(count);
+
+    // ---- state blob: per tensor M | r | c | R | C, every array 256-byte aligned
+    int64_t off = 0;
+    for (int32_t t = 0; t < count; ++t) {
+        const came_tensor_desc& d = descs[t];
+        TensorMeta& tm = p.metas[t];
+        tm = TensorMeta{};
+        tm.n = d.rows;
+        tm.m = d.ndim == 2 ? d.cols : 1;
+        tm.flags = (d.grad_dtype == CAME_GRAD_BF16 ? kFlagBf16Grad : 0);
+        const int64_t nm = tm.n * tm.m;
+        p.total_elements += nm;
+        tm.off_M = off; off = round_up(off + nm, kAlignFloats);
+        tm.off_r = off; off = round_up(off + tm.n, kAlignFloats);
+        if (d.ndim == 2) {
+            tm.off_c = off; off = round_up(off + tm.m, kAlignFloats);
+        } else {
+            tm.off_c = -1;
+        }
+        tm.off_R = off; off = round_up(off + tm.n, kAlignFloats);
+        if (d.ndim == 2) {
+            tm.off_C = off; off = round_up(off + tm.m, kAlignFloats);
+            ++p.n_matrices;
+            if (tm.m % kLaneCols == 0) tm.flags |= kFlagAligned;
+        } else {
+            tm.off_C = -1;
+            tm.flags |= kFlagVector;
+            ++p.n_vectors;
+        }
+    }
+    p.state_bytes = static_cast<size_t>(off) * sizeof(float);
+
+    // ---- groups of consecutive tensors
+    {
+        Group g{};
+        g.tensor_begin = 0;
+        int64_t acc = 0;
+        for (int32_t t = 0; t < count; ++t) {
+            const int64_t nm = p.metas[t].n * p.metas[t].m;
+            if (o.group_elements > 0 && t > g.tensor_begin && acc + nm > o.group_elements) {
+                g.tensor_end = t;
+                p.groups.push_back(g);
+                g = Group{};
+                g.tensor_begin = t;
+                acc = 0;
+            }
+            acc += nm;
+        }
+        g.tensor_end = count;
+        p.groups.push_back(g);
+    }
+
+    // ---- work items and finalize items, group by group
+    for (Group& g : p.groups) {
+        g.item_begin = static_cast<int32_t>(p.items.size());
+        g.fin_begin = static_cast<int32_t>(p.fins.size());
+        for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
+            TensorMeta& tm = p.metas[t];
+            if (tm.flags & kFlagVector) continue;
+            tm.tile_rows = p.tile_rows;
+            tm.RB = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows));
+            tm.CB = static_cast<int32_t>(ceil_div(tm.m, kTileCols));
+            tm.ntiles = tm.RB * tm.CB;
+            for (int32_t rb = 0; rb < tm.RB; ++rb)
+                for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 0});
+            tm.f_row_wgs = static_cast<int32_t>(ceil_div(tm.n, kWorkgroup));
+            tm.f_col_wgs = static_cast<int32_t>(ceil_div(tm.m, kWorkgroup));
+            for (int32_t k = 0; k < tm.f_row_wgs; ++k) p.fins.push_back(FinalizeItem{t, k, 0, 0});
+            for (int32_t k = 0; k < tm.f_col_wgs; ++k) p.fins.push_back(FinalizeItem{t, k, 1, 0});
+        }
+        g.tile_end = static_cast<int32_t>(p.items.size());
+        for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t)
+            if (p.metas[t].flags & kFlagVector) p.items.push_back(WorkItem{t, 0, 0, 1});
+        g.item_end = static_cast<int32_t>(p.items.size());
+        g.fin_end = static_cast<int32_t>(p.fins.size());
+    }
+
+    // ---- scratch blob
+    size_t s = 0;
+    p.off_metas = s;   s = round_up_sz(s + sizeof(TensorMeta) * count, kAlignBytes);
+    p.off_items = s;   s = round_up_sz(s + sizeof(WorkItem) * std::max<size_t>(p.items.size(), 1), kAlignBytes);
+    p.off_fins = s;    s = round_up_sz(s + sizeof(FinalizeItem) * std::max<size_t>(p.fins.size(), 1), kAlignBytes);
+    p.off_scalars = s; s = round_up_sz(s + sizeof(TensorScalars) * count, kAlignBytes);
+    p.ptr_slot_bytes = round_up_sz(sizeof(void*) * 2 * count, kAlignBytes);
+    p.off_ptrs = s;    s += p.ptr_slot_bytes * kPtrSlots;
+    p.off_partials = s;
+    for (int32_t t = 0; t < count; ++t) {
+        TensorMeta& tm = p.metas[t];
+        if (tm.flags & kFlagVector) continue;
+        // sized for sweep 2 (three doubles per entry); sweep 1 reuses the front of each region
+        tm.off_rowpart = static_cast<int64_t>(s);
+        s = round_up_sz(s + sizeof(double) * 3 * static_cast<size_t>(tm.n) * tm.CB, kAlignBytes);
+        tm.off_colpart = static_cast<int64_t>(s);
+        s = round_up_sz(s + sizeof(double) * 3 * static_cast<size_t>(tm.RB) * tm.m, kAlignBytes);
+        tm.off_tileP = static_cast<int64_t>(s);
+        s = round_up_sz(s + sizeof(double) * tm.ntiles, kAlignBytes);
+        tm.off_fpart = static_cast<int64_t>(s);
+        s = round_up_sz(s + sizeof(double) * tm.f_row_wgs, kAlignBytes);
+    }
+    p.scratch_bytes = s;
+    return CAME_OK;
+}
+
+}  // namespace came

@@ -1,0 +1,107 @@
+// Launch plan of the CAME step: plain structs shared by the host planner and
+// the gfx950 kernels.  Host-only logic (validation, state layout, tile table)
+// lives in came_plan.cpp and needs no GPU.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "came.h"
+
+namespace came {
+
+// Geometry of a sweep tile.  A workgroup of 4 wave64s sweeps `tile_rows` rows
+// of a 512-column stripe: each lane owns 8 consecutive columns (one 16-byte
+// bf16 load or two 16-byte f32 loads), each wave takes every 4th row.
+constexpr int kWorkgroup = 256;
+constexpr int kWaves = 4;
+constexpr int kLaneCols = 8;
+constexpr int kTileCols = 64 * kLaneCols;  // 512
+
+enum TensorFlags : int32_t {
+    kFlagBf16Grad = 1,  // gradient stored as bfloat16
+    kFlagVector = 2,    // 1-D parameter: unfactored update, one workgroup
+    kFlagAligned = 4,   // cols % 8 == 0: every row starts 16-byte aligned -> vector loads
+};
+
+// Per-tensor descriptor in device memory (scratch blob).
+struct TensorMeta {
+    int64_t n, m;                             // rows, columns (m = 1 for vectors)
+    int64_t off_M, off_r, off_c, off_R, off_C;  // float offsets into the state blob (-1: absent)
+    int64_t off_rowpart;                      // byte offset in scratch: per-(row, column block) partials
+    int64_t off_colpart;                      // byte offset in scratch: per-(row block, column) partials
+    int64_t off_tileP;                        // byte offset in scratch: one double per tile (sum of u^2)
+    int64_t off_fpart;                        // byte offset in scratch: one double per row-finalize workgroup
+    int32_t RB, CB;                           // number of row blocks / column blocks
+    int32_t tile_rows;                        // rows per row block
+    int32_t ntiles;                           // RB * CB
+    int32_t f_row_wgs, f_col_wgs;             // finalize workgroups covering the rows / the columns
+    int32_t flags;                            // TensorFlags
+    int32_t pad_;
+};
+static_assert(sizeof(TensorMeta) == 120, "TensorMeta layout");
+
+// One workgroup of a sweep launch.
+struct WorkItem {
+    int32_t tensor;
+    int32_t rb, cb;  // row block, column block (matrix tiles)
+    int32_t kind;    // 0 = matrix tile, 1 = whole vector
+};
+
+// One workgroup of a finalize launch: 256 rows or 256 columns of one matrix.
+struct FinalizeItem {
+    int32_t tensor;
+    int32_t chunk;  // outputs [chunk*256, chunk*256+256)
+    int32_t kind;   // 0 = rows (r, R), 1 = columns (c, C)
+    int32_t pad_;
+};
+
+// Per-tensor scalars produced by the finalize kernels, consumed by the sweeps.
+struct TensorScalars {
+    float sqrt_sum_r;   // sqrt(1^T r_t)
+    float kappa;        // 1 / max(1, RMS(u_t)/d)                     (Eq. 1)
+    float sqrt_sum_R;   // sqrt(1^T R_t)
+    float rms_u;        // RMS(u_t), kept for inspection
+    uint32_t count_f1;  // arrival counters of the row-finalize workgroups
+    uint32_t count_f2;
+    uint32_t pad_[2];
+};
+static_assert(sizeof(TensorScalars) == 32, "TensorScalars layout");
+
+// Consecutive tensors launched together: each phase is one launch per group.
+struct Group {
+    int32_t tensor_begin, tensor_end;
+    int32_t item_begin;       // first work item (matrix tiles first, then vectors)
+    int32_t tile_end;         // one past the last matrix tile
+    int32_t item_end;         // one past the last vector item
+    int32_t fin_begin, fin_end;
+};
+
+struct Plan {
+    std::vector<came_tensor_desc> descs;
+    std::vector<TensorMeta> metas;
+    std::vector<WorkItem> items;
+    std::vector<FinalizeItem> fins;
+    std::vector<Group> groups;
+    int32_t tile_rows = 0;
+    int32_t algo = 0;
+    int64_t n_matrices = 0, n_vectors = 0, total_elements = 0;
+    // state blob
+    size_t state_bytes = 0;
+    // scratch blob sections (byte offsets)
+    size_t off_metas = 0, off_items = 0, off_fins = 0, off_scalars = 0, off_ptrs = 0;
+    size_t ptr_slot_bytes = 0;  // one slot: theta[count] then grad[count]
+    size_t off_partials = 0;
+    size_t scratch_bytes = 0;
+};
+
+constexpr int kPtrSlots = 4;
+
+// Validates descs/opts and fills `plan`.  Returns CAME_OK or CAME_EINVAL.
+int build_plan(const came_tensor_desc* descs, int32_t count, const came_options* opts, Plan* plan);
+
+int validate_hyper(const came_hyper* h, double lr, int64_t step);
+
+}  // namespace came

@@ -1,0 +1,96 @@
+"""Runs the HIP library and the CPU oracle side by side on one seeded workload
+and compares theta, M, r, c, R, C (v, s for vectors) element by element.
+
+Error measure (stated bar: max relative error 1e-5 after 1 step, 1e-4 after
+100 steps, binary32 GPU path against the binary64 oracle):
+  * r, c, R, C, v, s are sums of non-negative terms, never near zero relative
+    to their scale: plain elementwise |x - ref| / |ref|.
+  * theta and M are signed and individual entries can cancel to ~0, where an
+    elementwise relative error is meaningless; they use
+    |x - ref| / (|ref| + RMS(ref over the tensor)).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2307_02047_amd as P
+from oracle import came_oracle as O
+from paper_2307_02047_amd import workloads as W
+
+
+def rel_err_positive(x: np.ndarray, ref: np.ndarray) -> float:
+    return float(np.max(np.abs(x - ref) / np.abs(ref)))
+
+
+def rel_err_signed(x: np.ndarray, ref: np.ndarray) -> float:
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return float(np.max(np.abs(x - ref)))
+    return float(np.max(np.abs(x - ref) / (np.abs(ref) + rms)))
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float32).numpy().astype(np.float64)
+
+
+class SideBySide:
+    """GPU library on every tensor of `shapes`; oracle on the tensors in `check`."""
+
+    def __init__(self, w: W.Workload, indices=None, check=None, hyper=None, device="cuda:0", **opts):
+        self.w = w
+        self.gen = W.Generator(w, device=device)
+        self.idx = list(range(len(w.shapes))) if indices is None else list(indices)
+        self.check = list(range(len(self.idx))) if check is None else list(check)  # positions in self.idx
+        self.shapes = [w.shapes[i] for i in self.idx]
+        self.hyper = hyper or P.CameHyper()
+        self.opt = P.CameStep(self.shapes, [w.grad_dtype] * len(self.shapes), device=device, **opts)
+        self.theta = [self.gen.theta0(i) for i in self.idx]
+        self.otl = O.TensorList([self.shapes[k] for k in self.check], [to_f64(self.theta[k]) for k in self.check])
+        self.t = 0
+
+    def step(self, nthreads: int = 0):
+        self.t += 1
+        grads = [self.gen.grad(i, self.t) for i in self.idx]
+        self.opt.check_tensors(self.theta, grads)
+        self.opt.step(self.theta, grads, self.hyper, self.w.lr, self.t)
+        oh = O.Hyper(self.hyper.beta1, self.hyper.beta2, self.hyper.beta3, self.hyper.eps1, self.hyper.eps2,
+                     self.hyper.clip_d, self.w.lr)
+        self.otl.step([to_f64(grads[k]) for k in self.check], oh, nthreads=nthreads)
+        torch.cuda.synchronize()
+
+    def errors(self) -> dict:
+        """Worst error per quantity over the checked tensors, plus where it occurs."""
+        worst = {}
+
+        def upd(name, e, k):
+            if name not in worst or e > worst[name][0]:
+                worst[name] = (e, self.idx[k], self.shapes[k])
+
+        for pos, k in enumerate(self.check):
+            sv = self.opt.state_view(k)
+            st = self.otl.state[pos]
+            th = to_f64(self.theta[k])
+            assert np.all(np.isfinite(th)), f"non-finite theta in tensor {self.idx[k]} {self.shapes[k]}"
+            upd("theta", rel_err_signed(th, self.otl.theta[pos]), k)
+            upd("M", rel_err_signed(to_f64(sv["M"]), st.M), k)
+            if len(self.shapes[k]) == 2:
+                upd("r", rel_err_positive(to_f64(sv["r"]), st.r), k)
+                upd("c", rel_err_positive(to_f64(sv["c"]), st.c), k)
+                upd("R", rel_err_positive(to_f64(sv["R"]), st.R), k)
+                upd("C", rel_err_positive(to_f64(sv["C"]), st.C), k)
+            else:
+                upd("v", rel_err_positive(to_f64(sv["r"]), st.v), k)
+                upd("s", rel_err_positive(to_f64(sv["R"]), st.s), k)
+        return worst
+
+    def assert_within(self, tol: float, label: str = ""):
+        errs = self.errors()
+        bad = {k: v for k, v in errs.items() if not (v[0] <= tol)}
+        summary = ", ".join(f"{k}={v[0]:.2e}" for k, v in errs.items())
+        print(f"[parity] {self.w.name} {label} step {self.t}: {summary}", flush=True)
+        assert not bad, f"{self.w.name} step {self.t}: over tolerance {tol:g}: {bad}"
+        return errs
+
+    def close(self):
+        self.opt.close()

@@ -1,0 +1,198 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Bar: max relative error 1e-5 after 1 step, 1e-4 after 100
+steps (measure defined in parity_util.py)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2307_02047_amd as P
+from paper_2307_02047_amd import workloads as W
+from parity_util import SideBySide
+
+pytestmark = pytest.mark.gpu
+
+TOL_1, TOL_100 = 1e-5, 1e-4
+LONG = os.environ.get("CAME_LONG_PARITY", "0") == "1"
+
+
+def _run(w, steps, tol_end, check_every=None, **kw):
+    sbs = SideBySide(w, **kw)
+    try:
+        for t in range(1, steps + 1):
+            sbs.step()
+            if t == 1:
+                sbs.assert_within(TOL_1)
+            elif t == steps or (check_every and t % check_every == 0):
+                sbs.assert_within(tol_end)
+    finally:
+        sbs.close()
+
+
+def test_single_matrix_and_bias_10_steps():
+    """256x512 matrix + bias of 512, the small configuration, all 10 steps."""
+    _run(W.single_matrix(), 10, TOL_100, check_every=1)
+
+
+@pytest.mark.parametrize("tile_rows", [4, 20, 64, 512])
+def test_single_matrix_tile_rows(tile_rows):
+    """Same result whatever the row tiling (ragged last row block included)."""
+    _run(W.single_matrix(), 3, TOL_100, check_every=1, tile_rows=tile_rows)
+
+
+def _layer_subset(w, layer_len, head):
+    """Embedding-side tensors except the large vocabulary matrix, plus the first layer."""
+    return list(range(1, head)) + list(range(head, head + layer_len))
+
+
+def test_bert_base_subset_100_steps():
+    w = W.bert_base()
+    _run(w, 100, TOL_100, check_every=25, indices=_layer_subset(w, 16, 3))
+
+
+def test_gpt2_medium_subset_100_steps_heavy_tails():
+    w = W.gpt2_medium()
+    _run(w, 100, TOL_100, check_every=25, indices=_layer_subset(w, 12, 2))
+
+
+def test_bert_large_bf16_subset_100_steps_zero_rows():
+    w = W.bert_large()
+    _run(w, 100, TOL_100, check_every=25, indices=_layer_subset(w, 16, 3))
+
+
+@pytest.mark.parametrize("make", [W.bert_base, W.gpt2_medium, W.bert_large], ids=lambda f: f.__name__)
+def test_full_list_few_steps(make):
+    """Every tensor of the list in one grouped launch, oracle on all of them."""
+    w = make()
+    _run(w, 100 if LONG else 2, TOL_100 if LONG else TOL_1 * 2, check_every=25)
+
+
+def test_llama_full_size_sampled():
+    """The 6.7B-parameter list in the configuration bench.py times (all tensors,
+    default plan); the oracle follows one tensor of every distinct shape."""
+    w = W.llama_7b()
+    seen, check = set(), []
+    for k, s in enumerate(w.shapes):
+        if s not in seen and s != (32000, 4096):
+            seen.add(s)
+            check.append(k)
+    check.append(len(w.shapes) - 1)  # LM head 32000 x 4096 (last tensor, after all layers)
+    _run(w, 2, TOL_1 * 2, check=check)
+
+
+ODD_SHAPES = [(1, 1), (1, 8), (8, 1), (3, 5), (2, 768), (5, 520), (7, 1000), (130, 24), (33, 513), (257, 1031),
+              (1030, 8), (4, 4104)]
+
+
+@pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["f32", "bf16"])
+def test_odd_shapes(dtype):
+    """Ragged rows and columns, widths that are not a multiple of 8 (scalar-load
+    path), single rows/columns, vectors of awkward lengths."""
+    shapes = ODD_SHAPES + [(1,), (7,), (255,), (256,), (257,), (5000,)]
+    w = W.Workload("odd-shapes", shapes, dtype, seed=77, steps=5, grad_kind="normal",
+                   scale_range=(1e-4, 1e-1), zero_row_fraction=0.3)
+    _run(w, 5, TOL_100, check_every=1, tile_rows=8)
+
+
+def test_transposed_matrix_swaps_row_and_column_statistics():
+    """Algorithm 2 is symmetric in rows and columns: g^T, theta^T give theta^T, M^T,
+    r <-> c, R <-> C.  On the GPU the row reduction (wave shuffles) and the column
+    reduction (LDS + second stage) are different code, so this checks one against the other."""
+    n, m = 300, 1048
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    th = torch.randn((n, m), generator=gen, device=dev) * 0.02
+    tht = th.t().contiguous()
+    a = P.CameStep([(n, m)], [0], tile_rows=16)
+    b = P.CameStep([(m, n)], [0], tile_rows=16)
+    h = P.CameHyper()
+    for t in range(1, 4):
+        g = torch.randn((n, m), generator=gen, device=dev) * 0.01
+        a.step([th], [g], h, 1e-3, t)
+        b.step([tht], [g.t().contiguous()], h, 1e-3, t)
+    torch.cuda.synchronize()
+    va, vb = a.state_view(0), b.state_view(0)
+    for x, y in [(th.t(), tht), (va["M"].t(), vb["M"]), (va["r"], vb["c"]), (va["c"], vb["r"]),
+                 (va["R"], vb["C"]), (va["C"], vb["R"])]:
+        x, y = x.double().cpu().numpy(), y.double().cpu().numpy()
+        scale = np.sqrt(np.mean(y * y))
+        assert np.max(np.abs(x - y) / (np.abs(y) + scale)) < 5e-6
+    a.close(); b.close()
+
+
+def test_bitwise_reproducible():
+    """No data atomics anywhere: two runs from the same inputs agree bit for bit."""
+    w = W.Workload("repro", [(700, 1536), (1536,), (64, 520)], W.GRAD_BF16, seed=9, steps=4,
+                   grad_kind="normal", scale_range=(1e-3, 1e-1))
+    outs = []
+    for _ in range(2):
+        gen = W.Generator(w, device="cuda:0")
+        th = [gen.theta0(i) for i in range(3)]
+        opt = P.CameStep(w.shapes, [w.grad_dtype] * 3, tile_rows=32)
+        for t in range(1, 5):
+            opt.step(th, [gen.grad(i, t) for i in range(3)], P.CameHyper(), 1e-3, t)
+        torch.cuda.synchronize()
+        outs.append([x.clone() for x in th] + [opt.state_view(0)[k].clone() for k in "MrcRC"])
+        opt.close()
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
+
+
+def test_state_checkpoint_round_trip():
+    """State is exactly (M, r, c, R, C): 2 steps, copy the state out and into a fresh
+    context, 2 more steps == 4 straight steps, bit for bit."""
+    w = W.Workload("ckpt", [(300, 1024), (1024,)], W.GRAD_F32, seed=10, steps=4, grad_kind="normal",
+                   scale_range=(1e-3, 1e-1))
+    gen = W.Generator(w, device="cuda:0")
+    h = P.CameHyper()
+    th_a = [gen.theta0(i) for i in range(2)]
+    a = P.CameStep(w.shapes, [0, 0])
+    for t in range(1, 5):
+        a.step(th_a, [gen.grad(i, t) for i in range(2)], h, 1e-3, t)
+    th_b = [gen.theta0(i) for i in range(2)]
+    b1 = P.CameStep(w.shapes, [0, 0])
+    for t in range(1, 3):
+        b1.step(th_b, [gen.grad(i, t) for i in range(2)], h, 1e-3, t)
+    b2 = P.CameStep(w.shapes, [0, 0])
+    torch.cuda.synchronize()
+    for i in range(2):
+        src, dst = b1.state_view(i), b2.state_view(i)
+        for k in "MrcRC":
+            if src[k] is not None:
+                dst[k].copy_(src[k])
+    for t in range(3, 5):
+        b2.step(th_b, [gen.grad(i, t) for i in range(2)], h, 1e-3, t)
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert torch.equal(th_a[i], th_b[i])
+        for k in "MrcRC":
+            if a.state_view(i)[k] is not None:
+                assert torch.equal(a.state_view(i)[k], b2.state_view(i)[k])
+    a.close(); b1.close(); b2.close()
+
+
+def test_grouped_launch_equals_single_group():
+    """Splitting the list into launch groups changes scheduling only."""
+    w = W.Workload("groups", [(256, 512), (512,), (100, 1024), (1024,), (512, 512)], W.GRAD_BF16, seed=11,
+                   steps=3, grad_kind="normal", scale_range=(1e-3, 1e-1))
+    res = []
+    for ge in (0, 150_000):
+        gen = W.Generator(w, device="cuda:0")
+        th = [gen.theta0(i) for i in range(5)]
+        opt = P.CameStep(w.shapes, [w.grad_dtype] * 5, group_elements=ge, tile_rows=16)
+        for t in range(1, 4):
+            opt.step(th, [gen.grad(i, t) for i in range(5)], P.CameHyper(), 1e-3, t)
+        torch.cuda.synchronize()
+        res.append(th + [opt.state_view(0)["R"].clone(), opt.state_view(4)["C"].clone()])
+        opt.close()
+    for x, y in zip(*res):
+        assert torch.equal(x, y)
+
+
+def test_pointer_table_follows_new_addresses():
+    """Gradients handed over in fresh buffers every step (addresses change each call)."""
+    w = W.Workload("ptrs", [(64, 512), (512,)], W.GRAD_F32, seed=12, steps=6, grad_kind="normal",
+                   scale_range=(1e-2, 1e-1))
+    _run(w, 6, TOL_100, check_every=1)

@@ -1,0 +1,127 @@
+"""Host-side behaviour of the C-ABI library that needs no GPU: it loads, exports
+every symbol include/came.h declares, sizes and plans the state as Algorithm 2
+requires, and turns every invalid argument into an error code."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2307_02047_amd as P
+from paper_2307_02047_amd import binding as B
+from paper_2307_02047_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "came.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(came_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    lib = P.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_state_size_is_nm_plus_2n_plus_2m():
+    """Section 3.1 / 3.3: O(n+m) factored statistics beside the momentum."""
+    pad = lambda x: (x + 63) // 64 * 64
+    for (n, m) in [(256, 512), (2, 768), (30522, 768), (7, 13)]:
+        sb, _ = P.state_size([(n, m)], [0])
+        assert sb == 4 * (pad(n * m) + 2 * pad(n) + 2 * pad(m))
+        assert sb >= 4 * (n * m + 2 * (n + m))
+    sb, _ = P.state_size([(4096,)], [1])
+    assert sb == 4 * 3 * 4096
+
+
+@pytest.mark.parametrize("make,params,mats,vecs", [
+    (W.single_matrix, 131_584, 1, 1), (W.bert_base, 108_890_112, 75, 120),
+    (W.gpt2_medium, 354_821_120, 98, 192), (W.bert_large, 334_090_240, 147, 240),
+    (W.llama_7b, 6_738_415_616, 226, 65)])
+def test_plan_of_the_named_workloads(make, params, mats, vecs):
+    w = make()
+    q = P.plan_query(w.shapes, [w.grad_dtype] * len(w.shapes))
+    assert (q["elements"], q["matrices"], q["vectors"]) == (params, mats, vecs)
+    tr, tc = q["tile_rows"], q["tile_cols"]
+    want = sum(-(-s[0] // tr) * -(-s[1] // tc) for s in w.shapes if len(s) == 2) + vecs
+    assert q["sweep_items"] == want
+    assert q["finalize_items"] == sum(-(-s[0] // 256) + -(-s[1] // 256) for s in w.shapes if len(s) == 2)
+    sb, wb = P.state_size(w.shapes, [w.grad_dtype] * len(w.shapes))
+    assert sb >= 4 * sum((s[0] * s[1] + 2 * (s[0] + s[1])) if len(s) == 2 else 3 * s[0] for s in w.shapes)
+    assert wb < 0.25 * sb or wb < (1 << 20)  # scratch stays a fraction of the state
+
+
+def test_groups_split_the_list():
+    shapes = [(256, 512), (512,), (100, 1024), (1024,), (512, 512)]
+    assert P.plan_query(shapes, [0] * 5)["groups"] == 1
+    assert P.plan_query(shapes, [0] * 5, group_elements=150_000)["groups"] == 3
+    assert P.plan_query(shapes, [0] * 5, group_elements=1)["groups"] == 5
+
+
+def test_algorithmic_bytes():
+    """Three-sweep design: g read three times, M read twice and written once,
+    theta read and written once -> 20 + 3 sizeof(g) bytes per parameter."""
+    assert P.algorithmic_bytes_per_param(2) == 26
+    assert P.algorithmic_bytes_per_param(4) == 32
+    for gb in (2, 4):
+        assert sum(P.algorithmic_bytes_per_param(gb, k) for k in (1, 2, 3)) == P.algorithmic_bytes_per_param(gb)
+
+
+def _raw(shapes_rows_cols_ndim_dtype):
+    arr = (B._Desc * len(shapes_rows_cols_ndim_dtype))()
+    for i, t in enumerate(shapes_rows_cols_ndim_dtype):
+        arr[i] = B._Desc(*t)
+    return arr
+
+
+@pytest.mark.parametrize("desc", [(0, 4, 2, 0), (4, 0, 2, 0), (-1, 4, 2, 0), (4, 4, 3, 0), (4, 4, 0, 0),
+                                  (4, 2, 1, 0), (4, 4, 2, 2), (4, 4, 2, -1)])
+def test_bad_descriptors_are_rejected(desc):
+    lib = P.load_library()
+    sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
+    rc = lib.came_state_size(_raw([desc]), 1, None, ctypes.byref(sb), ctypes.byref(wb))
+    assert rc == -1
+    assert lib.came_strerror(rc) == b"invalid argument"
+
+
+def test_bad_counts_options_and_null_pointers():
+    lib = P.load_library()
+    sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
+    good = _raw([(4, 8, 2, 0)])
+    assert lib.came_state_size(good, 0, None, ctypes.byref(sb), ctypes.byref(wb)) == -1
+    assert lib.came_state_size(None, 1, None, ctypes.byref(sb), ctypes.byref(wb)) == -1
+    assert lib.came_state_size(good, 1, None, None, ctypes.byref(wb)) == -1
+    for kw in (dict(tile_rows=3), dict(tile_rows=2), dict(tile_rows=8192), dict(algo=7), dict(group_elements=-5)):
+        o = B._options(**kw)
+        assert lib.came_state_size(good, 1, ctypes.byref(o), ctypes.byref(sb), ctypes.byref(wb)) == -1, kw
+    o = B._options()
+    o.reserved[2] = 1
+    assert lib.came_state_size(good, 1, ctypes.byref(o), ctypes.byref(sb), ctypes.byref(wb)) == -1
+    assert lib.came_state_size(good, 1, None, ctypes.byref(sb), ctypes.byref(wb)) == 0
+
+
+def test_init_rejects_short_or_misaligned_blobs_before_touching_the_device():
+    lib = P.load_library()
+    good = _raw([(4, 8, 2, 0)])
+    sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.came_state_size(good, 1, None, ctypes.byref(sb), ctypes.byref(wb)) == 0
+    ctx = ctypes.c_void_p()
+    fake = 0x10000  # never dereferenced: every call below fails validation first
+    assert lib.came_init_state(ctypes.byref(ctx), good, 1, None, fake, sb.value - 1, fake, wb.value, None) == -2
+    assert lib.came_init_state(ctypes.byref(ctx), good, 1, None, fake, sb.value, fake, wb.value - 1, None) == -2
+    assert lib.came_init_state(ctypes.byref(ctx), good, 1, None, fake + 8, sb.value, fake, wb.value, None) == -3
+    assert lib.came_init_state(ctypes.byref(ctx), good, 1, None, None, sb.value, fake, wb.value, None) == -1
+    assert lib.came_init_state(None, good, 1, None, fake, sb.value, fake, wb.value, None) == -1
+    assert not ctx.value
+    assert lib.came_step(None, None, None, None, 1e-3, 1, None) == -1
+    v = B._View()
+    assert lib.came_state_view_get(None, 0, ctypes.byref(v)) == -1
+    lib.came_destroy(None)  # no-op
+    assert lib.came_last_hip_error(None) == 0
+    assert lib.came_strerror(12345) == b"unknown status"
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(ImportError):
+        P.load_library(str(tmp_path / "nope.so"))
