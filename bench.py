@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--group-elements", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 4 GiB device-to-device copy a few times: the known-size kernel "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -100,6 +103,16 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = "cuda:0"
+    if args.calibrate_copy:
+        n = (4 << 30) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n * 4, "calibrate_copy_bytes_written": n * 4,
+                          "launches": 4}), flush=True)
+        return 0
     w = W.by_name(args.workload)
     gen = W.Generator(w, device=dev)
     n = len(w.shapes)

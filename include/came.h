@@ -159,7 +159,7 @@ int came_state_view_get(const came_ctx *ctx, int32_t i, came_state_view *view);
 
 /*
  * Plan introspection (host only, no device): fills out[0..7] with
- * { tile_rows chosen, tile_cols, number of sweep work items per phase,
+ * { tile_rows chosen, tile_cols, number of work items (matrix tiles + vectors),
  *   number of finalize workgroups per phase, number of launch groups,
  *   number of matrices, number of vectors, total elements }.
  */
@@ -175,15 +175,15 @@ int came_plan_query(const came_tensor_desc *descs, int32_t count, const came_opt
 double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which);
 
 /*
- * Built-in phase timer.  While enabled, came_step brackets each of its five
- * launches per group with HIP events on the step's stream.  came_profile_read
- * waits for the recorded events, adds the elapsed milliseconds and launch
- * counts per phase { sweep 1, finalize 1, sweep 2, finalize 2, sweep 3 } since
- * the previous read into phase_ms[5] / phase_launches[5], and forgets them.
+ * Built-in phase timer.  While enabled, came_step brackets each of its
+ * launches with HIP events on the step's stream.  came_profile_read waits for
+ * the recorded events, adds the elapsed milliseconds and launch counts per
+ * phase { sweep 1, finalize 1, sweep 2, finalize 2, sweep 3, vectors } since
+ * the previous read into phase_ms[6] / phase_launches[6], and forgets them.
  * At most 65536 launches are kept between reads; further ones go untimed.
  */
 int came_profile_enable(came_ctx *ctx, int32_t on);
-int came_profile_read(came_ctx *ctx, double phase_ms[5], int64_t phase_launches[5]);
+int came_profile_read(came_ctx *ctx, double phase_ms[6], int64_t phase_launches[6]);
 
 /* hipError_t of the last failed HIP call on this context (0 if none). */
 int came_last_hip_error(const came_ctx *ctx);

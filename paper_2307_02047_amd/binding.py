@@ -235,15 +235,15 @@ class CameStep:
         return {"M": sl(v.m, n * m, s), "r": sl(v.r, n, (n,)), "c": sl(v.c, m, (m,)),
                 "R": sl(v.R, n, (n,)), "C": sl(v.C, m, (m,))}
 
-    PHASES = ("sweep1", "finalize1", "sweep2", "finalize2", "sweep3")
+    PHASES = ("sweep1", "finalize1", "sweep2", "finalize2", "sweep3", "vectors")
 
     def profile_enable(self, on: bool = True) -> None:
         _check(self.lib, self.lib.came_profile_enable(self._ctx, 1 if on else 0), "came_profile_enable")
 
     def profile_read(self) -> dict:
         """came_profile_read: {phase: (total_ms, launches)} since the previous read."""
-        ms = (ctypes.c_double * 5)()
-        cnt = (ctypes.c_int64 * 5)()
+        ms = (ctypes.c_double * 6)()
+        cnt = (ctypes.c_int64 * 6)()
         _check(self.lib, self.lib.came_profile_read(self._ctx, ms, cnt), "came_profile_read", self._ctx)
         return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(self.PHASES)}
 

@@ -49,6 +49,7 @@ template <class F>
 hipError_t timed_launch(came_ctx* ctx, int phase, hipStream_t s, F launch)
 {
     if (!ctx->profiling || ctx->timed.size() >= kMaxTimed) return launch();
+    // (an empty range launches nothing but is still bracketed: negligible)
     came_ctx::Timed t{};
     t.phase = phase;
     hipError_t e = hipEventCreate(&t.start);
@@ -102,8 +103,7 @@ int came_plan_query(const came_tensor_desc* descs, int32_t count, const came_opt
     Plan plan;
     const int rc = build_plan(descs, count, opts, &plan);
     if (rc != CAME_OK) return rc;
-    int64_t tiles = 0;
-    for (const Group& g : plan.groups) tiles += g.item_end - g.item_begin;
+    const int64_t tiles = static_cast<int64_t>(plan.items.size());
     out[0] = plan.tile_rows;
     out[1] = kTileCols;
     out[2] = tiles;
@@ -249,17 +249,28 @@ int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev
 
     const DeviceTables tb = tables_for(ctx, ctx->slot);
     for (const Group& g : p.groups) {
-        hipError_t e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, g.item_begin, g.item_end, sh, fh, s); });
+        hipError_t e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
         if (e != hipSuccess) return hip_fail(ctx, e);
-        if (g.tile_end == g.item_begin) continue;  // vectors only
+        if (g.fin_end == g.fin_begin) continue;  // vectors only
+        for (int v = 0; v < kVariants; ++v) {
+            if (g.var_end[v] == g.var_begin[v]) continue;
+            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, g.var_begin[v], g.var_end[v], s); });
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
         e = timed_launch(ctx, 1, s, [&] { return launch_finalize1(tb, g.fin_begin, g.fin_end, fh, s); });
         if (e != hipSuccess) return hip_fail(ctx, e);
-        e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, g.item_begin, g.tile_end, sh, s); });
-        if (e != hipSuccess) return hip_fail(ctx, e);
+        for (int v = 0; v < kVariants; ++v) {
+            if (g.var_end[v] == g.var_begin[v]) continue;
+            e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, g.var_begin[v], g.var_end[v], s); });
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
         e = timed_launch(ctx, 3, s, [&] { return launch_finalize2(tb, g.fin_begin, g.fin_end, fh, s); });
         if (e != hipSuccess) return hip_fail(ctx, e);
-        e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, g.item_begin, g.tile_end, sh, s); });
-        if (e != hipSuccess) return hip_fail(ctx, e);
+        for (int v = 0; v < kVariants; ++v) {
+            if (g.var_end[v] == g.var_begin[v]) continue;
+            e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, g.var_begin[v], g.var_end[v], sh, s); });
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
     }
     ctx->last_step = step;
     return CAME_OK;
@@ -285,10 +296,10 @@ int came_profile_enable(came_ctx* ctx, int32_t on)
     return CAME_OK;
 }
 
-int came_profile_read(came_ctx* ctx, double phase_ms[5], int64_t phase_launches[5])
+int came_profile_read(came_ctx* ctx, double phase_ms[6], int64_t phase_launches[6])
 {
     if (!ctx || !phase_ms || !phase_launches) return CAME_EINVAL;
-    for (int k = 0; k < 5; ++k) { phase_ms[k] = 0.0; phase_launches[k] = 0; }
+    for (int k = 0; k < 6; ++k) { phase_ms[k] = 0.0; phase_launches[k] = 0; }
     int rc = CAME_OK;
     for (const came_ctx::Timed& t : ctx->timed) {
         hipError_t e = hipEventSynchronize(t.stop);

@@ -42,21 +42,26 @@ struct DeviceTables {
 hipError_t launch_fill_zero(float* p, size_t count, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s);
 
-// Sweep 1: row/column sums of g^2 for the matrix tiles [begin, tile_end) and the
-// complete update of the vectors [tile_end, item_end).
-hipError_t launch_sweep1(const DeviceTables& t, int32_t item_begin, int32_t item_end,
-                         const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);
-// Finalize 1: r, c and sqrt(sum r).
+// `variant` (see variant_of) selects the kernel instantiation; all work items in
+// [item_begin, item_end) must be matrix tiles of tensors of that variant.
+
+// Complete Algorithm-2 update of the vectors [item_begin, item_end), one workgroup each.
+hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,
+                          const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);
+// Sweep 1: row/column sums of g^2.
+hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
+                         hipStream_t s);
+// Finalize 1: r, c and the per-workgroup sums of r.
 hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);
 // Sweep 2: row/column sums of u^2, u*M, M^2 and the per-tile sum of u^2.
-hipError_t launch_sweep2(const DeviceTables& t, int32_t item_begin, int32_t tile_end,
-                         const SweepHyper& h, hipStream_t s);
-// Finalize 2: kappa (Eq. 1), R, C and sqrt(sum R).
+hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
+                         hipStream_t s);
+// Finalize 2: kappa (Eq. 1), R, C and the per-workgroup sums of R.
 hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);
 // Sweep 3: momentum and parameter update.
-hipError_t launch_sweep3(const DeviceTables& t, int32_t item_begin, int32_t tile_end,
+hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
                          const SweepHyper& h, hipStream_t s);
 
 }  // namespace came

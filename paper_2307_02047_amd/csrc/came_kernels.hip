@@ -1,7 +1,9 @@
 // gfx950 kernels of the CAME step (Algorithm 2 of the CAME paper).
 //
-// One step is five grouped launches over ALL tensors of a group:
+// One step is six grouped launches over ALL tensors of a group (the sweeps once per
+// kernel variant present: gradient dtype x aligned/unaligned rows):
 //
+//   vectors    g, state     -> complete update of the 1-D parameters (one workgroup each)
 //   sweep 1    g            -> row/column partial sums of g^2          (r_t, c_t lines)
 //   finalize 1 partials     -> r_t, c_t, sqrt(1^T r_t)
 //   sweep 2    g, M_{t-1}   -> row/column partial sums of u^2, u M, M^2 with u = g / sqrt(v_t)
@@ -50,99 +52,174 @@ __device__ __forceinline__ float load_grad1(const void* g, int64_t idx)
         return static_cast<const float*>(g)[idx];
 }
 
-// 8 consecutive gradient entries starting at element idx, widened to binary32.
-// ALIGNED: the caller guarantees ncol is 0 or 8 and idx % 8 == 0 with a 16-byte aligned base.
+// A lane's 8 consecutive entries of one row, as they sit in memory.  Kept packed
+// between the load and its use so that the next rows' loads can be issued before
+// the current rows are consumed (the wait lands at the unpack, not at the load).
+template <bool BF16> struct GradRaw;
+template <> struct GradRaw<true>  { u32x4 v; };      // 8 bfloat16
+template <> struct GradRaw<false> { f32x4 a, b; };   // 8 binary32
+struct F32Raw { f32x4 a, b; };
+
+// ALIGNED: every row starts 16-byte aligned (m % 8 == 0) and ncol is 0 or 8: vector
+// accesses.  Otherwise element-wise accesses with per-column bounds.
 template <bool BF16, bool ALIGNED>
-__device__ __forceinline__ void load_grad8(const void* g, int64_t idx, int ncol, float (&x)[8])
+__device__ __forceinline__ GradRaw<BF16> load_grad_raw(const void* g, int64_t idx, int ncol)
 {
-    if constexpr (ALIGNED) {
-        if (ncol > 0) {
-            if constexpr (BF16) {
-                const u32x4 raw = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(g) + idx);
-                x[0] = bits_to_float(raw.x << 16); x[1] = bits_to_float(raw.x & 0xffff0000u);
-                x[2] = bits_to_float(raw.y << 16); x[3] = bits_to_float(raw.y & 0xffff0000u);
-                x[4] = bits_to_float(raw.z << 16); x[5] = bits_to_float(raw.z & 0xffff0000u);
-                x[6] = bits_to_float(raw.w << 16); x[7] = bits_to_float(raw.w & 0xffff0000u);
-            } else {
-                const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(g) + idx);
-                const f32x4 a = p[0], b = p[1];
-                x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-                x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-            }
+    GradRaw<BF16> r;
+    if constexpr (BF16) {
+        r.v = u32x4{0u, 0u, 0u, 0u};
+        const uint16_t* p = static_cast<const uint16_t*>(g) + idx;
+        if constexpr (ALIGNED) {
+            if (ncol > 0) r.v = *reinterpret_cast<const u32x4*>(p);
         } else {
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = 0.f;
+            for (int e = 0; e < 8; ++e)
+                if (e < ncol) w[e >> 1] |= static_cast<uint32_t>(p[e]) << ((e & 1) * 16);
+            r.v = u32x4{w[0], w[1], w[2], w[3]};
         }
     } else {
+        r.a = f32x4{0.f, 0.f, 0.f, 0.f};
+        r.b = r.a;
+        const float* p = static_cast<const float*>(g) + idx;
+        if constexpr (ALIGNED) {
+            if (ncol > 0) {
+                r.a = reinterpret_cast<const f32x4*>(p)[0];
+                r.b = reinterpret_cast<const f32x4*>(p)[1];
+            }
+        } else {
+            float w[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = e < ncol ? load_grad1<BF16>(g, idx + e) : 0.f;
+            for (int e = 0; e < 8; ++e) w[e] = e < ncol ? p[e] : 0.f;
+            r.a = f32x4{w[0], w[1], w[2], w[3]};
+            r.b = f32x4{w[4], w[5], w[6], w[7]};
+        }
+    }
+    return r;
+}
+
+template <bool BF16>
+__device__ __forceinline__ void unpack(const GradRaw<BF16>& r, float (&x)[8])
+{
+    if constexpr (BF16) {
+        x[0] = bits_to_float(r.v.x << 16); x[1] = bits_to_float(r.v.x & 0xffff0000u);
+        x[2] = bits_to_float(r.v.y << 16); x[3] = bits_to_float(r.v.y & 0xffff0000u);
+        x[4] = bits_to_float(r.v.z << 16); x[5] = bits_to_float(r.v.z & 0xffff0000u);
+        x[6] = bits_to_float(r.v.w << 16); x[7] = bits_to_float(r.v.w & 0xffff0000u);
+    } else {
+        x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w;
+        x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
     }
 }
 
-template <bool ALIGNED>
-__device__ __forceinline__ void load_f32x8(const float* base, int64_t idx, int ncol, float (&x)[8])
+__device__ __forceinline__ void unpack(const F32Raw& r, float (&x)[8])
 {
+    x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w;
+    x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
+}
+
+template <bool ALIGNED>
+__device__ __forceinline__ F32Raw load_f32_raw(const float* base, int64_t idx, int ncol)
+{
+    F32Raw r;
+    r.a = f32x4{0.f, 0.f, 0.f, 0.f};
+    r.b = r.a;
+    const float* p = base + idx;
     if constexpr (ALIGNED) {
         if (ncol > 0) {
-            const f32x4* p = reinterpret_cast<const f32x4*>(base + idx);
-            const f32x4 a = p[0], b = p[1];
-            x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-            x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = 0.f;
+            r.a = reinterpret_cast<const f32x4*>(p)[0];
+            r.b = reinterpret_cast<const f32x4*>(p)[1];
         }
     } else {
+        float w[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = e < ncol ? base[idx + e] : 0.f;
+        for (int e = 0; e < 8; ++e) w[e] = e < ncol ? p[e] : 0.f;
+        r.a = f32x4{w[0], w[1], w[2], w[3]};
+        r.b = f32x4{w[4], w[5], w[6], w[7]};
     }
+    return r;
 }
 
 template <bool ALIGNED>
 __device__ __forceinline__ void store_f32x8(float* base, int64_t idx, int ncol, const float (&x)[8])
 {
+    float* p = base + idx;
     if constexpr (ALIGNED) {
         if (ncol > 0) {
-            f32x4* p = reinterpret_cast<f32x4*>(base + idx);
-            f32x4 a, b;
-            a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3];
-            b.x = x[4]; b.y = x[5]; b.z = x[6]; b.w = x[7];
-            p[0] = a;
-            p[1] = b;
+            reinterpret_cast<f32x4*>(p)[0] = f32x4{x[0], x[1], x[2], x[3]};
+            reinterpret_cast<f32x4*>(p)[1] = f32x4{x[4], x[5], x[6], x[7]};
         }
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (e < ncol) base[idx + e] = x[e];
+            if (e < ncol) p[e] = x[e];
     }
 }
 
 // ---------------------------------------------------------------- reductions
 
-__device__ __forceinline__ float wave_sum(float v)
+// DPP controls (GFX9 encoding): quad_perm [1,0,3,2], quad_perm [2,3,0,1], mirror within
+// 8 lanes, mirror within 16 lanes, lane 15 of a row to the next row, lane 31 to rows 2-3.
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140,
+              kDppBcast15 = 0x142, kDppBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_get(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_get(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the 64 lanes of a wave; the total is valid in LANE 63 ONLY.  Four butterfly
+// steps inside each row of 16 lanes, then two row broadcasts; all DPP, no LDS traffic.
+// Fixed order, hence deterministic.  Every lane of the wave must be active.
+template <class T>
+__device__ __forceinline__ T wave_sum_lane63(T v)
+{
+    v += dpp_get<kDppXor1, 0xF>(v);
+    v += dpp_get<kDppXor2, 0xF>(v);
+    v += dpp_get<kDppHalfMirror, 0xF>(v);
+    v += dpp_get<kDppMirror, 0xF>(v);
+    v += dpp_get<kDppBcast15, 0xA>(v);  // rows 1, 3 += total of rows 0, 2
+    v += dpp_get<kDppBcast31, 0xC>(v);  // rows 2, 3 += total of rows 0+1
     return v;
 }
 
-__device__ __forceinline__ double wave_sum(double v)
+__device__ __forceinline__ double lane63_to_all(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
 }
+
+__device__ __forceinline__ double wave_sum(double v) { return lane63_to_all(wave_sum_lane63(v)); }
 
 // Sum over the 256 threads of a workgroup, same value returned to every thread.
 // Fixed tree, hence deterministic.  lds4: 4 doubles of LDS, reusable afterwards.
 __device__ __forceinline__ double block_sum(double v, double* lds4)
 {
-    v = wave_sum(v);
-    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    v = wave_sum_lane63(v);
+    if ((threadIdx.x & 63) == 63) lds4[threadIdx.x >> 6] = v;
     __syncthreads();
     const double total = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
     __syncthreads();
     return total;
+}
+
+// Sum of a short list of doubles (a few hundred at most), computed by one wave in a
+// fixed order; every wave that evaluates it gets the same bits.
+__device__ __forceinline__ double wave_sum_list(const double* list, int count)
+{
+    double s = 0.0;
+    for (int k = threadIdx.x & 63; k < count; k += 64) s += list[k];
+    return wave_sum(s);
 }
 
 struct TileGeom {
@@ -214,7 +291,12 @@ __device__ void vector_update(const TensorMeta& tm, const void* g, float* theta,
 
 // ---------------------------------------------------------------- sweep 1
 
-constexpr int kUnroll1 = 4;
+// Rows a wave handles per loop trip.  While one batch of rows is consumed the next
+// batch's loads are already in flight (two register buffers, ping-pong).
+#ifndef CAME_ROWS1
+#define CAME_ROWS1 4
+#endif
+constexpr int kRows1 = CAME_ROWS1;
 
 template <bool BF16, bool ALIGNED>
 __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const void* g, char* scratch,
@@ -224,41 +306,55 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const void
     float* rowpart = reinterpret_cast<float*>(scratch + tm.off_rowpart);
     float* colpart = reinterpret_cast<float*>(scratch + tm.off_colpart);
     const int64_t m = tm.m;
+    constexpr int kStep = kWaves * kRows1;
 
-    float cacc[kUnroll1][8];
+    float cacc[2][8];
 #pragma unroll
-    for (int u = 0; u < kUnroll1; ++u)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int e = 0; e < 8; ++e) cacc[u][e] = 0.f;
 
-    for (int i = t.wave; i < t.nrows; i += kWaves * kUnroll1) {
-        float x[kUnroll1][8];
+    auto load = [&](GradRaw<BF16> (&buf)[kRows1], int i) {
 #pragma unroll
-        for (int u = 0; u < kUnroll1; ++u) {
+        for (int u = 0; u < kRows1; ++u) {
             const int ii = i + kWaves * u;
-            load_grad8<BF16, ALIGNED>(g, (t.row0 + ii) * m + t.col, ii < t.nrows ? t.ncol : 0, x[u]);
+            buf[u] = load_grad_raw<BF16, ALIGNED>(g, (t.row0 + ii) * m + t.col, ii < t.nrows ? t.ncol : 0);
         }
+    };
+    auto consume = [&](const GradRaw<BF16> (&buf)[kRows1], int i) {
 #pragma unroll
-        for (int u = 0; u < kUnroll1; ++u) {
+        for (int u = 0; u < kRows1; ++u) {
             const int ii = i + kWaves * u;
+            float x[8];
+            unpack<BF16>(buf[u], x);
             float racc = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float sq = x[u][e] * x[u][e];
+                const float sq = x[e] * x[e];
                 racc += sq;
-                cacc[u][e] += sq;
+                cacc[u & 1][e] += sq;
             }
-            racc = wave_sum(racc);
-            if (t.lane == 0 && ii < t.nrows) rowpart[(t.row0 + ii) * tm.CB + it.cb] = racc;
+            racc = wave_sum_lane63(racc);
+            if (t.lane == 63 && ii < t.nrows) rowpart[(t.row0 + ii) * tm.CB + it.cb] = racc;
         }
+    };
+
+    GradRaw<BF16> A[kRows1], B[kRows1];
+    int i = t.wave;
+    if (i < t.nrows) load(A, i);
+    while (i < t.nrows) {
+        if (i + kStep < t.nrows) load(B, i + kStep);
+        consume(A, i);
+        i += kStep;
+        if (i >= t.nrows) break;
+        if (i + kStep < t.nrows) load(A, i + kStep);
+        consume(B, i);
+        i += kStep;
     }
 
-    // column sums of the tile: across the unrolled accumulators, then across the 4 waves
+    // column sums of the tile: the two accumulator sets, then the 4 waves through LDS
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float v = (cacc[0][e] + cacc[1][e]) + (cacc[2][e] + cacc[3][e]);
-        lds[t.wave * kTileCols + t.lane * kLaneCols + e] = v;
-    }
+    for (int e = 0; e < 8; ++e) lds[t.wave * kTileCols + t.lane * kLaneCols + e] = cacc[0][e] + cacc[1][e];
     __syncthreads();
     for (int j = threadIdx.x; j < kTileCols; j += kWorkgroup) {
         const int64_t cj = static_cast<int64_t>(it.cb) * kTileCols + j;
@@ -269,44 +365,47 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const void
     }
 }
 
-__global__ __launch_bounds__(kWorkgroup) void sweep1_kernel(DeviceTables tb, int32_t item_begin,
+// One __global__ entry per variant, each with the occupancy (waves per SIMD) its register
+// budget is tuned for: the compiler keeps the kernel within 512/N VGPRs.
+#ifndef CAME_WAVES1
+#define CAME_WAVES1 5
+#endif
+#define CAME_SWEEP1_KERNEL(NAME, BF16, ALIGNED, WAVES)                                              \
+    __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
+    void NAME(DeviceTables tb, int32_t item_begin)                                                  \
+    {                                                                                               \
+        __shared__ float lds[kWaves * kTileCols];                                                   \
+        const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
+        sweep1_tile<BF16, ALIGNED>(tb.metas[it.tensor], it, tb.grad[it.tensor], tb.scratch, lds);   \
+    }
+CAME_SWEEP1_KERNEL(sweep1_bf16_kernel, true, true, CAME_WAVES1)
+CAME_SWEEP1_KERNEL(sweep1_f32_kernel, false, true, 4)
+CAME_SWEEP1_KERNEL(sweep1_bf16_unaligned_kernel, true, false, 4)
+CAME_SWEEP1_KERNEL(sweep1_f32_unaligned_kernel, false, false, 4)
+
+__global__ __launch_bounds__(kWorkgroup) void vector_kernel(DeviceTables tb, int32_t item_begin,
                                                             SweepHyper h, FinalizeHyper fh)
 {
-    __shared__ float lds[kWaves * kTileCols];
     __shared__ double lds4[4];
     const WorkItem it = tb.items[item_begin + blockIdx.x];
     const TensorMeta& tm = tb.metas[it.tensor];
     const void* g = tb.grad[it.tensor];
-    const bool bf16 = tm.flags & kFlagBf16Grad;
-    if (it.kind == 1) {
-        float* theta = static_cast<float*>(tb.theta[it.tensor]);
-        if (bf16) vector_update<true>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
-        else      vector_update<false>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
-        return;
-    }
-    const bool aligned = tm.flags & kFlagAligned;
-    if (bf16) {
-        if (aligned) sweep1_tile<true, true>(tm, it, g, tb.scratch, lds);
-        else         sweep1_tile<true, false>(tm, it, g, tb.scratch, lds);
-    } else {
-        if (aligned) sweep1_tile<false, true>(tm, it, g, tb.scratch, lds);
-        else         sweep1_tile<false, false>(tm, it, g, tb.scratch, lds);
-    }
+    float* theta = static_cast<float*>(tb.theta[it.tensor]);
+    if (tm.flags & kFlagBf16Grad) vector_update<true>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
+    else                          vector_update<false>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
 }
 
 // ---------------------------------------------------------------- finalize 1
 
 // r_t = beta2 r_{t-1} + (1-beta2)(rowsum g^2 + m eps1), c_t likewise with n eps1
-// (eps1 sits inside the sums: m resp. n copies), then sqrt(1^T r_t) by the last
-// row workgroup of the tensor to arrive.
+// (eps1 sits inside the sums: m resp. n copies).  Each row workgroup also leaves the
+// sum of its 256 new r values; sweep 2 adds those few numbers up to 1^T r_t.
 __global__ __launch_bounds__(kWorkgroup) void finalize1_kernel(DeviceTables tb, int32_t fin_begin,
                                                                FinalizeHyper h)
 {
     __shared__ double lds4[4];
-    __shared__ int is_last;
     const FinalizeItem fi = tb.fins[fin_begin + blockIdx.x];
     const TensorMeta& tm = tb.metas[fi.tensor];
-    TensorScalars* sc = tb.scalars + fi.tensor;
     const int64_t idx = static_cast<int64_t>(fi.chunk) * kWorkgroup + threadIdx.x;
     if (fi.kind == 0) {
         const float* rowpart = reinterpret_cast<const float*>(tb.scratch + tm.off_rowpart);
@@ -314,37 +413,22 @@ __global__ __launch_bounds__(kWorkgroup) void finalize1_kernel(DeviceTables tb, 
         double mine = 0.0;
         if (idx < tm.n) {
             double s = 0.0;
-            for (int cb = 0; cb < tm.CB; ++cb) s += static_cast<double>(rowpart[idx * tm.CB + cb]);
+            const float* src = rowpart + idx * tm.CB;
+#pragma unroll 4
+            for (int cb = 0; cb < tm.CB; ++cb) s += static_cast<double>(src[cb]);
             s += static_cast<double>(tm.m) * h.eps1;
             const float rn = static_cast<float>(h.beta2 * static_cast<double>(r[idx]) + h.one_minus_beta2 * s);
             r[idx] = rn;
             mine = static_cast<double>(rn);
         }
         const double total = block_sum(mine, lds4);
-        double* fpart = reinterpret_cast<double*>(tb.scratch + tm.off_fpart);
-        if (threadIdx.x == 0) {
-            fpart[fi.chunk] = total;
-            __threadfence();
-            const uint32_t prev = atomicAdd(&sc->count_f1, 1u);
-            is_last = (prev == static_cast<uint32_t>(tm.f_row_wgs - 1));
-        }
-        __syncthreads();
-        if (is_last) {
-            __threadfence();
-            double s = 0.0;
-            for (int k = threadIdx.x; k < tm.f_row_wgs; k += kWorkgroup)
-                s += __hip_atomic_load(&fpart[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s = block_sum(s, lds4);
-            if (threadIdx.x == 0) {
-                sc->sqrt_sum_r = static_cast<float>(sqrt(s));
-                sc->count_f1 = 0u;
-            }
-        }
+        if (threadIdx.x == 0) reinterpret_cast<double*>(tb.scratch + tm.off_fpart)[fi.chunk] = total;
     } else {
         const float* colpart = reinterpret_cast<const float*>(tb.scratch + tm.off_colpart);
         float* c = tb.state + tm.off_c;
         if (idx < tm.m) {
             double s = 0.0;
+#pragma unroll 4
             for (int rb = 0; rb < tm.RB; ++rb) s += static_cast<double>(colpart[static_cast<int64_t>(rb) * tm.m + idx]);
             s += static_cast<double>(tm.n) * h.eps1;
             c[idx] = static_cast<float>(h.beta2 * static_cast<double>(c[idx]) + h.one_minus_beta2 * s);
@@ -354,11 +438,14 @@ __global__ __launch_bounds__(kWorkgroup) void finalize1_kernel(DeviceTables tb, 
 
 // ---------------------------------------------------------------- sweep 2
 
-constexpr int kUnroll2 = 2;
+#ifndef CAME_ROWS2
+#define CAME_ROWS2 2
+#endif
+constexpr int kRows2 = CAME_ROWS2;
 
 template <bool BF16, bool ALIGNED>
 __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void* g, const float* state,
-                            char* scratch, const TensorScalars* sc, double* lds /* [4][512] */,
+                            char* scratch, TensorScalars* sc, double* lds /* [4][512] */,
                             double* lds4)
 {
     const TileGeom t = tile_geom(tm, it);
@@ -369,7 +456,27 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void
     double* rowpart = reinterpret_cast<double*>(scratch + tm.off_rowpart);
     double* colpart = reinterpret_cast<double*>(scratch + tm.off_colpart);
     double* tileP = reinterpret_cast<double*>(scratch + tm.off_tileP);
-    const float sqrt_sum_r = sc->sqrt_sum_r;
+    constexpr int kStep = kWaves * kRows2;
+
+    struct Rows { GradRaw<BF16> g[kRows2]; F32Raw mo[kRows2]; };
+    auto load = [&](Rows& buf, int i) {
+#pragma unroll
+        for (int u = 0; u < kRows2; ++u) {
+            const int ii = i + kWaves * u;
+            const int nc = ii < t.nrows ? t.ncol : 0;
+            const int64_t idx = (t.row0 + ii) * m + t.col;
+            buf.g[u] = load_grad_raw<BF16, ALIGNED>(g, idx, nc);
+            buf.mo[u] = load_f32_raw<ALIGNED>(M, idx, nc);
+        }
+    };
+    Rows A, B;
+    int i = t.wave;
+    if (i < t.nrows) load(A, i);
+
+    // 1^T r_t from the per-workgroup sums finalize 1 left (every wave, same order, same bits)
+    const double sum_r = wave_sum_list(reinterpret_cast<const double*>(scratch + tm.off_fpart), tm.f_row_wgs);
+    const float sqrt_sum_r = static_cast<float>(sqrt(sum_r));
+    if (it.rb == 0 && it.cb == 0 && threadIdx.x == 0) sc->sqrt_sum_r = sqrt_sum_r;
 
     float b[8];  // rsqrt(c_j) of this lane's columns
 #pragma unroll
@@ -378,39 +485,44 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void
     double cP[8], cQ[8], cW[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) cP[e] = cQ[e] = cW[e] = 0.0;
-    double waveP = 0.0;
+    double waveP = 0.0;  // meaningful in lane 63
 
-    for (int i = t.wave; i < t.nrows; i += kWaves * kUnroll2) {
-        float x[kUnroll2][8], mo[kUnroll2][8];
+    auto consume = [&](const Rows& buf, int i0) {
 #pragma unroll
-        for (int u = 0; u < kUnroll2; ++u) {
-            const int ii = i + kWaves * u;
-            const int nc = ii < t.nrows ? t.ncol : 0;
-            load_grad8<BF16, ALIGNED>(g, (t.row0 + ii) * m + t.col, nc, x[u]);
-            load_f32x8<ALIGNED>(M, (t.row0 + ii) * m + t.col, nc, mo[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll2; ++u) {
-            const int ii = i + kWaves * u;
+        for (int u = 0; u < kRows2; ++u) {
+            const int ii = i0 + kWaves * u;
             if (ii < t.nrows) {
                 const float a = rsqrtf(r[t.row0 + ii]) * sqrt_sum_r;  // rsqrt(r_i / 1^T r)
+                float x[8], mo[8];
+                unpack<BF16>(buf.g[u], x);
+                unpack(buf.mo[u], mo);
                 double rP = 0.0, rQ = 0.0, rW = 0.0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float uf = (x[u][e] * a) * b[e];  // u_ij = g_ij / sqrt(v_ij)
+                    const float uf = (x[e] * a) * b[e];  // u_ij = g_ij / sqrt(v_ij)
                     const double du = static_cast<double>(uf);
-                    const double dm = static_cast<double>(mo[u][e]);
+                    const double dm = static_cast<double>(mo[e]);
                     rP = fma(du, du, rP); rQ = fma(du, dm, rQ); rW = fma(dm, dm, rW);
                     cP[e] = fma(du, du, cP[e]); cQ[e] = fma(du, dm, cQ[e]); cW[e] = fma(dm, dm, cW[e]);
                 }
-                rP = wave_sum(rP); rQ = wave_sum(rQ); rW = wave_sum(rW);
-                if (t.lane == 0) {
+                rP = wave_sum_lane63(rP); rQ = wave_sum_lane63(rQ); rW = wave_sum_lane63(rW);
+                if (t.lane == 63) {
                     double* dst = rowpart + ((t.row0 + ii) * tm.CB + it.cb) * 3;
                     dst[0] = rP; dst[1] = rQ; dst[2] = rW;
                 }
                 waveP += rP;
             }
         }
+    };
+
+    while (i < t.nrows) {
+        if (i + kStep < t.nrows) load(B, i + kStep);
+        consume(A, i);
+        i += kStep;
+        if (i >= t.nrows) break;
+        if (i + kStep < t.nrows) load(A, i + kStep);
+        consume(B, i);
+        i += kStep;
     }
 
     // column sums across the 4 waves, one statistic at a time through 16 KB of LDS
@@ -430,43 +542,41 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void
         __syncthreads();
     }
     // sum of u^2 over the tile (feeds RMS(u_t))
-    if (t.lane == 0) lds4[t.wave] = waveP;
+    if (t.lane == 63) lds4[t.wave] = waveP;
     __syncthreads();
     if (threadIdx.x == 0)
         tileP[static_cast<int64_t>(it.rb) * tm.CB + it.cb] = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
 }
 
-__global__ __launch_bounds__(kWorkgroup) void sweep2_kernel(DeviceTables tb, int32_t item_begin, SweepHyper h)
-{
-    __shared__ double lds[kWaves * kTileCols];
-    __shared__ double lds4[4];
-    (void)h;
-    const WorkItem it = tb.items[item_begin + blockIdx.x];
-    const TensorMeta& tm = tb.metas[it.tensor];
-    const void* g = tb.grad[it.tensor];
-    const TensorScalars* sc = tb.scalars + it.tensor;
-    const bool bf16 = tm.flags & kFlagBf16Grad;
-    const bool aligned = tm.flags & kFlagAligned;
-    if (bf16) {
-        if (aligned) sweep2_tile<true, true>(tm, it, g, tb.state, tb.scratch, sc, lds, lds4);
-        else         sweep2_tile<true, false>(tm, it, g, tb.state, tb.scratch, sc, lds, lds4);
-    } else {
-        if (aligned) sweep2_tile<false, true>(tm, it, g, tb.state, tb.scratch, sc, lds, lds4);
-        else         sweep2_tile<false, false>(tm, it, g, tb.state, tb.scratch, sc, lds, lds4);
+#ifndef CAME_WAVES2
+#define CAME_WAVES2 3
+#endif
+#define CAME_SWEEP2_KERNEL(NAME, BF16, ALIGNED, WAVES)                                              \
+    __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
+    void NAME(DeviceTables tb, int32_t item_begin)                                                  \
+    {                                                                                               \
+        __shared__ double lds[kWaves * kTileCols];                                                  \
+        __shared__ double lds4[4];                                                                  \
+        const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
+        sweep2_tile<BF16, ALIGNED>(tb.metas[it.tensor], it, tb.grad[it.tensor], tb.state,           \
+                                   tb.scratch, tb.scalars + it.tensor, lds, lds4);                  \
     }
-}
+CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, CAME_WAVES2)
+CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, 2)
+CAME_SWEEP2_KERNEL(sweep2_bf16_unaligned_kernel, true, false, 2)
+CAME_SWEEP2_KERNEL(sweep2_f32_unaligned_kernel, false, false, 2)
 
 // ---------------------------------------------------------------- finalize 2
 
 // kappa from the per-tile sums of u^2 (Eq. 1), then
 //   rowsum U_i = beta1^2 (kappa^2 P_i - 2 kappa Q_i + W_i),
-//   R_t = beta3 R_{t-1} + (1-beta3)(rowsum U + m eps2), C_t likewise with n eps2,
-// and sqrt(1^T R_t) by the last row workgroup of the tensor to arrive.
+//   R_t = beta3 R_{t-1} + (1-beta3)(rowsum U + m eps2), C_t likewise with n eps2.
+// Each row workgroup also leaves the sum of its 256 new R values; sweep 3 adds those
+// few numbers up to 1^T R_t.
 __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, int32_t fin_begin,
                                                                FinalizeHyper h)
 {
     __shared__ double lds4[4];
-    __shared__ int is_last;
     const FinalizeItem fi = tb.fins[fin_begin + blockIdx.x];
     const TensorMeta& tm = tb.metas[fi.tensor];
     TensorScalars* sc = tb.scalars + fi.tensor;
@@ -487,17 +597,19 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
     if (h.algo != CAME_ALGO_CAME) return;
 
     const double b1sq = h.beta1 * h.beta1;
+    const double k2 = kappa * kappa, km2 = -2.0 * kappa;
     if (fi.kind == 0) {
         const double* rowpart = reinterpret_cast<const double*>(tb.scratch + tm.off_rowpart);
         float* R = tb.state + tm.off_R;
         double mine = 0.0;
         if (idx < tm.n) {
             double sP = 0.0, sQ = 0.0, sW = 0.0;
+            const double* src = rowpart + idx * tm.CB * 3;
+#pragma unroll 4
             for (int cb = 0; cb < tm.CB; ++cb) {
-                const double* src = rowpart + (idx * tm.CB + cb) * 3;
-                sP += src[0]; sQ += src[1]; sW += src[2];
+                sP += src[3 * cb]; sQ += src[3 * cb + 1]; sW += src[3 * cb + 2];
             }
-            double U = b1sq * ((kappa * kappa * sP - 2.0 * kappa * sQ) + sW);
+            double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
             U = fmax(U, 0.0);
             U += static_cast<double>(tm.m) * h.eps2;
             const float Rn = static_cast<float>(h.beta3 * static_cast<double>(R[idx]) + h.one_minus_beta3 * U);
@@ -505,35 +617,19 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
             mine = static_cast<double>(Rn);
         }
         const double total = block_sum(mine, lds4);
-        double* fpart = reinterpret_cast<double*>(tb.scratch + tm.off_fpart);
-        if (threadIdx.x == 0) {
-            fpart[fi.chunk] = total;
-            __threadfence();
-            const uint32_t prev = atomicAdd(&sc->count_f2, 1u);
-            is_last = (prev == static_cast<uint32_t>(tm.f_row_wgs - 1));
-        }
-        __syncthreads();
-        if (is_last) {
-            __threadfence();
-            double s = 0.0;
-            for (int k = threadIdx.x; k < tm.f_row_wgs; k += kWorkgroup)
-                s += __hip_atomic_load(&fpart[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s = block_sum(s, lds4);
-            if (threadIdx.x == 0) {
-                sc->sqrt_sum_R = static_cast<float>(sqrt(s));
-                sc->count_f2 = 0u;
-            }
-        }
+        if (threadIdx.x == 0)
+            reinterpret_cast<double*>(tb.scratch + tm.off_fpart)[tm.f_row_wgs + fi.chunk] = total;
     } else {
         const double* colpart = reinterpret_cast<const double*>(tb.scratch + tm.off_colpart);
         float* C = tb.state + tm.off_C;
         if (idx < tm.m) {
             double sP = 0.0, sQ = 0.0, sW = 0.0;
+#pragma unroll 4
             for (int rb = 0; rb < tm.RB; ++rb) {
                 const int64_t base = static_cast<int64_t>(rb) * 3 * tm.m + idx;
                 sP += colpart[base]; sQ += colpart[base + tm.m]; sW += colpart[base + 2 * tm.m];
             }
-            double U = b1sq * ((kappa * kappa * sP - 2.0 * kappa * sQ) + sW);
+            double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
             U = fmax(U, 0.0);
             U += static_cast<double>(tm.n) * h.eps2;
             C[idx] = static_cast<float>(h.beta3 * static_cast<double>(C[idx]) + h.one_minus_beta3 * U);
@@ -543,13 +639,16 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
 
 // ---------------------------------------------------------------- sweep 3
 
-constexpr int kUnroll3 = 2;
+#ifndef CAME_ROWS3
+#define CAME_ROWS3 2
+#endif
+constexpr int kRows3 = CAME_ROWS3;
 
 // u^ = kappa g / sqrt(v);  M_t = beta1 M_{t-1} + (1-beta1) u^;
 // theta_t = theta_{t-1} - eta M_t / sqrt(S_t)      (Algorithm 1: theta_t = theta_{t-1} - eta M_t)
 template <bool BF16, bool ALIGNED>
 __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const void* g, float* theta,
-                            float* state, const TensorScalars* sc, const SweepHyper& h)
+                            float* state, const char* scratch, const TensorScalars* sc, const SweepHyper& h)
 {
     const TileGeom t = tile_geom(tm, it);
     const int64_t m = tm.m;
@@ -559,65 +658,90 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const void
     const float* C = state + tm.off_C;
     float* M = state + tm.off_M;
     const bool came = h.algo == CAME_ALGO_CAME;
-    const float row_scale_u = sc->sqrt_sum_r * sc->kappa;
-    const float row_scale_s = came ? sc->sqrt_sum_R * h.lr : h.lr;
+    constexpr int kStep = kWaves * kRows3;
 
-    float b[8], B[8];
+    struct Rows { GradRaw<BF16> g[kRows3]; F32Raw mo[kRows3], th[kRows3]; };
+    auto load = [&](Rows& buf, int i) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        b[e] = e < t.ncol ? rsqrtf(c[t.col + e]) : 0.f;
-        B[e] = came ? (e < t.ncol ? rsqrtf(C[t.col + e]) : 0.f) : 1.f;
-    }
-
-    for (int i = t.wave; i < t.nrows; i += kWaves * kUnroll3) {
-        float x[kUnroll3][8], mo[kUnroll3][8], th[kUnroll3][8];
-#pragma unroll
-        for (int u = 0; u < kUnroll3; ++u) {
+        for (int u = 0; u < kRows3; ++u) {
             const int ii = i + kWaves * u;
             const int nc = ii < t.nrows ? t.ncol : 0;
             const int64_t idx = (t.row0 + ii) * m + t.col;
-            load_grad8<BF16, ALIGNED>(g, idx, nc, x[u]);
-            load_f32x8<ALIGNED>(M, idx, nc, mo[u]);
-            load_f32x8<ALIGNED>(theta, idx, nc, th[u]);
+            buf.g[u] = load_grad_raw<BF16, ALIGNED>(g, idx, nc);
+            buf.mo[u] = load_f32_raw<ALIGNED>(M, idx, nc);
+            buf.th[u] = load_f32_raw<ALIGNED>(theta, idx, nc);
         }
+    };
+    Rows A, B;
+    int i = t.wave;
+    if (i < t.nrows) load(A, i);
+
+    // 1^T R_t from the per-workgroup sums finalize 2 left (every wave, same order, same bits)
+    float sqrt_sum_R = 1.f;
+    if (came)
+        sqrt_sum_R = static_cast<float>(sqrt(wave_sum_list(
+            reinterpret_cast<const double*>(scratch + tm.off_fpart) + tm.f_row_wgs, tm.f_row_wgs)));
+    const float row_scale_u = sc->sqrt_sum_r * sc->kappa;
+    const float row_scale_s = came ? sqrt_sum_R * h.lr : h.lr;
+
+    float b[8], Bc[8];
 #pragma unroll
-        for (int u = 0; u < kUnroll3; ++u) {
-            const int ii = i + kWaves * u;
+    for (int e = 0; e < 8; ++e) {
+        b[e] = e < t.ncol ? rsqrtf(c[t.col + e]) : 0.f;
+        Bc[e] = came ? (e < t.ncol ? rsqrtf(C[t.col + e]) : 0.f) : 1.f;
+    }
+
+    auto consume = [&](const Rows& buf, int i0) {
+#pragma unroll
+        for (int u = 0; u < kRows3; ++u) {
+            const int ii = i0 + kWaves * u;
             if (ii < t.nrows) {
                 const float a = rsqrtf(r[t.row0 + ii]) * row_scale_u;
-                const float A = came ? rsqrtf(R[t.row0 + ii]) * row_scale_s : row_scale_s;
-                float mn[8], tn[8];
+                const float Ar = came ? rsqrtf(R[t.row0 + ii]) * row_scale_s : row_scale_s;
+                float x[8], mo[8], th[8], mn[8], tn[8];
+                unpack<BF16>(buf.g[u], x);
+                unpack(buf.mo[u], mo);
+                unpack(buf.th[u], th);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float uh = (x[u][e] * a) * b[e];
-                    mn[e] = fmaf(h.beta1, mo[u][e], h.one_minus_beta1 * uh);
-                    tn[e] = th[u][e] - (mn[e] * A) * B[e];
+                    const float uh = (x[e] * a) * b[e];
+                    mn[e] = fmaf(h.beta1, mo[e], h.one_minus_beta1 * uh);
+                    tn[e] = th[e] - (mn[e] * Ar) * Bc[e];
                 }
                 const int64_t idx = (t.row0 + ii) * m + t.col;
                 store_f32x8<ALIGNED>(M, idx, t.ncol, mn);
                 store_f32x8<ALIGNED>(theta, idx, t.ncol, tn);
             }
         }
+    };
+
+    while (i < t.nrows) {
+        if (i + kStep < t.nrows) load(B, i + kStep);
+        consume(A, i);
+        i += kStep;
+        if (i >= t.nrows) break;
+        if (i + kStep < t.nrows) load(A, i + kStep);
+        consume(B, i);
+        i += kStep;
     }
 }
 
-__global__ __launch_bounds__(kWorkgroup) void sweep3_kernel(DeviceTables tb, int32_t item_begin, SweepHyper h)
-{
-    const WorkItem it = tb.items[item_begin + blockIdx.x];
-    const TensorMeta& tm = tb.metas[it.tensor];
-    const void* g = tb.grad[it.tensor];
-    float* theta = static_cast<float*>(tb.theta[it.tensor]);
-    const TensorScalars* sc = tb.scalars + it.tensor;
-    const bool bf16 = tm.flags & kFlagBf16Grad;
-    const bool aligned = tm.flags & kFlagAligned;
-    if (bf16) {
-        if (aligned) sweep3_tile<true, true>(tm, it, g, theta, tb.state, sc, h);
-        else         sweep3_tile<true, false>(tm, it, g, theta, tb.state, sc, h);
-    } else {
-        if (aligned) sweep3_tile<false, true>(tm, it, g, theta, tb.state, sc, h);
-        else         sweep3_tile<false, false>(tm, it, g, theta, tb.state, sc, h);
+#ifndef CAME_WAVES3
+#define CAME_WAVES3 3
+#endif
+#define CAME_SWEEP3_KERNEL(NAME, BF16, ALIGNED, WAVES)                                              \
+    __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
+    void NAME(DeviceTables tb, int32_t item_begin, SweepHyper h)                                    \
+    {                                                                                               \
+        const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
+        sweep3_tile<BF16, ALIGNED>(tb.metas[it.tensor], it, tb.grad[it.tensor],                     \
+                                   static_cast<float*>(tb.theta[it.tensor]), tb.state, tb.scratch,  \
+                                   tb.scalars + it.tensor, h);                                      \
     }
-}
+CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, CAME_WAVES3)
+CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, 3)
+CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, 3)
+CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, 3)
 
 // ---------------------------------------------------------------- fill
 
@@ -649,11 +773,25 @@ hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s)
     return launch_fill_zero(static_cast<float*>(p), bytes / sizeof(float), s);
 }
 
-hipError_t launch_sweep1(const DeviceTables& t, int32_t item_begin, int32_t item_end,
-                         const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s)
+hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,
+                          const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
-    sweep1_kernel<<<dim3(item_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin, h, fh);
+    vector_kernel<<<dim3(item_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin, h, fh);
+    return hipGetLastError();
+}
+
+hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
+                         hipStream_t s)
+{
+    if (item_end <= item_begin) return hipSuccess;
+    const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    switch (variant) {
+        case 0: sweep1_bf16_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        case 1: sweep1_f32_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        case 2: sweep1_bf16_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        default: sweep1_f32_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+    }
     return hipGetLastError();
 }
 
@@ -665,11 +803,17 @@ hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fi
     return hipGetLastError();
 }
 
-hipError_t launch_sweep2(const DeviceTables& t, int32_t item_begin, int32_t tile_end,
-                         const SweepHyper& h, hipStream_t s)
+hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
+                         hipStream_t s)
 {
-    if (tile_end <= item_begin) return hipSuccess;
-    sweep2_kernel<<<dim3(tile_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin, h);
+    if (item_end <= item_begin) return hipSuccess;
+    const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    switch (variant) {
+        case 0: sweep2_bf16_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        case 1: sweep2_f32_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        case 2: sweep2_bf16_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        default: sweep2_f32_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+    }
     return hipGetLastError();
 }
 
@@ -681,11 +825,17 @@ hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fi
     return hipGetLastError();
 }
 
-hipError_t launch_sweep3(const DeviceTables& t, int32_t item_begin, int32_t tile_end,
+hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
                          const SweepHyper& h, hipStream_t s)
 {
-    if (tile_end <= item_begin) return hipSuccess;
-    sweep3_kernel<<<dim3(tile_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin, h);
+    if (item_end <= item_begin) return hipSuccess;
+    const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    switch (variant) {
+        case 0: sweep3_bf16_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
+        case 1: sweep3_f32_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
+        case 2: sweep3_bf16_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
+        default: sweep3_f32_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
+    }
     return hipGetLastError();
 }
 

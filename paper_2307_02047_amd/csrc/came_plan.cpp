@@ -132,7 +132,6 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
 
     // ---- work items and finalize items, group by group
     for (Group& g : p.groups) {
-        g.item_begin = static_cast<int32_t>(p.items.size());
         g.fin_begin = static_cast<int32_t>(p.fins.size());
         for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
             TensorMeta& tm = p.metas[t];
@@ -141,18 +140,26 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             tm.RB = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows));
             tm.CB = static_cast<int32_t>(ceil_div(tm.m, kTileCols));
             tm.ntiles = tm.RB * tm.CB;
-            for (int32_t rb = 0; rb < tm.RB; ++rb)
-                for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 0});
             tm.f_row_wgs = static_cast<int32_t>(ceil_div(tm.n, kWorkgroup));
             tm.f_col_wgs = static_cast<int32_t>(ceil_div(tm.m, kWorkgroup));
             for (int32_t k = 0; k < tm.f_row_wgs; ++k) p.fins.push_back(FinalizeItem{t, k, 0, 0});
             for (int32_t k = 0; k < tm.f_col_wgs; ++k) p.fins.push_back(FinalizeItem{t, k, 1, 0});
         }
-        g.tile_end = static_cast<int32_t>(p.items.size());
+        g.fin_end = static_cast<int32_t>(p.fins.size());
+        for (int v = 0; v < kVariants; ++v) {
+            g.var_begin[v] = static_cast<int32_t>(p.items.size());
+            for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
+                const TensorMeta& tm = p.metas[t];
+                if ((tm.flags & kFlagVector) || variant_of(tm.flags) != v) continue;
+                for (int32_t rb = 0; rb < tm.RB; ++rb)
+                    for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 0});
+            }
+            g.var_end[v] = static_cast<int32_t>(p.items.size());
+        }
+        g.vec_begin = static_cast<int32_t>(p.items.size());
         for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t)
             if (p.metas[t].flags & kFlagVector) p.items.push_back(WorkItem{t, 0, 0, 1});
-        g.item_end = static_cast<int32_t>(p.items.size());
-        g.fin_end = static_cast<int32_t>(p.fins.size());
+        g.vec_end = static_cast<int32_t>(p.items.size());
     }
 
     // ---- scratch blob
@@ -175,7 +182,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         tm.off_tileP = static_cast<int64_t>(s);
         s = round_up_sz(s + sizeof(double) * tm.ntiles, kAlignBytes);
         tm.off_fpart = static_cast<int64_t>(s);
-        s = round_up_sz(s + sizeof(double) * tm.f_row_wgs, kAlignBytes);
+        s = round_up_sz(s + sizeof(double) * 2 * tm.f_row_wgs, kAlignBytes);
     }
     p.scratch_bytes = s;
     return CAME_OK;

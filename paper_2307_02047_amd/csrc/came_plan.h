@@ -33,7 +33,8 @@ struct TensorMeta {
     int64_t off_rowpart;                      // byte offset in scratch: per-(row, column block) partials
     int64_t off_colpart;                      // byte offset in scratch: per-(row block, column) partials
     int64_t off_tileP;                        // byte offset in scratch: one double per tile (sum of u^2)
-    int64_t off_fpart;                        // byte offset in scratch: one double per row-finalize workgroup
+    int64_t off_fpart;                        // byte offset in scratch: per row-finalize workgroup, sum of its
+                                              // r values [0, f_row_wgs) and of its R values [f_row_wgs, 2 f_row_wgs)
     int32_t RB, CB;                           // number of row blocks / column blocks
     int32_t tile_rows;                        // rows per row block
     int32_t ntiles;                           // RB * CB
@@ -64,18 +65,24 @@ struct TensorScalars {
     float kappa;        // 1 / max(1, RMS(u_t)/d)                     (Eq. 1)
     float sqrt_sum_R;   // sqrt(1^T R_t)
     float rms_u;        // RMS(u_t), kept for inspection
-    uint32_t count_f1;  // arrival counters of the row-finalize workgroups
-    uint32_t count_f2;
-    uint32_t pad_[2];
+    uint32_t pad_[4];
 };
 static_assert(sizeof(TensorScalars) == 32, "TensorScalars layout");
 
-// Consecutive tensors launched together: each phase is one launch per group.
+// Matrix tiles are launched per kernel variant so that each variant gets its own
+// register allocation: gradient dtype x (vector loads | element-wise loads).
+constexpr int kVariants = 4;
+inline int variant_of(int32_t flags)
+{
+    return ((flags & kFlagBf16Grad) ? 0 : 1) + ((flags & kFlagAligned) ? 0 : 2);
+}
+
+// Consecutive tensors launched together: each phase is one launch per group and
+// variant present.  Work items of a group: matrix tiles sorted by variant, then vectors.
 struct Group {
     int32_t tensor_begin, tensor_end;
-    int32_t item_begin;       // first work item (matrix tiles first, then vectors)
-    int32_t tile_end;         // one past the last matrix tile
-    int32_t item_end;         // one past the last vector item
+    int32_t var_begin[kVariants], var_end[kVariants];  // matrix tiles of each variant
+    int32_t vec_begin, vec_end;                        // whole-vector items
     int32_t fin_begin, fin_end;
 };
 
