@@ -98,7 +98,7 @@ typedef struct {
 /* Planner knobs; pass NULL for defaults.  Zero in a field means "default". */
 typedef struct {
     int32_t tile_rows;       /* rows of a matrix one workgroup sweeps per tile: multiple of 4,
-                                4..4096; 0 = chosen from the list so the launch fills the GPU */
+                                4..1024; 0 = chosen from the list so the launch fills the GPU */
     int32_t algo;            /* came_algo */
     int64_t group_elements;  /* 0 = all tensors in one launch group; otherwise consecutive
                                 tensors are packed into groups of at most about this many

@@ -289,24 +289,59 @@ __device__ void vector_update(const TensorMeta& tm, const void* g, float* theta,
     }
 }
 
+// ---------------------------------------------------------------- row scheduling
+
+// Rows of a tile are dealt to the 4 waves round-robin: wave w owns rows w, w+4, ...
+// (`cnt` of them).  They are consumed in batches of U rows; while one batch is consumed
+// the next batch's loads are in flight (two register buffers).  The loads of the
+// pipelined loop sit in straight-line code -- no branch between a load and the wait that
+// precedes its use -- so the compiler can wait for exactly the older batch
+// (s_waitcnt vmcnt(N)) instead of draining everything.  For that the batch index is
+// clamped (the last trip re-requests the batch it already holds: an L2 hit) and, in
+// tiles that overhang the matrix on the right, lanes beyond the last column load from
+// the tile's first columns and are masked afterwards.  Rows left over after the full
+// batches go through a plain one-row loop.
+struct WaveRows {
+    int cnt;    // rows of the tile owned by this wave
+    int nfull;  // full batches among them
+};
+
+template <int U>
+__device__ __forceinline__ WaveRows wave_rows(const TileGeom& t)
+{
+    WaveRows w;
+    w.cnt = t.wave < t.nrows ? (t.nrows - t.wave + kWaves - 1) / kWaves : 0;
+    w.nfull = w.cnt / U;
+    return w;
+}
+
+// Column this lane loads from: its own, or (overhanging lanes of a ragged tile) the
+// tile's first columns, which exist because the tile exists and m % 8 == 0.
+template <bool FULL>
+__device__ __forceinline__ int64_t load_col(const TileGeom& t, int cb)
+{
+    if constexpr (FULL) return t.col;
+    else return t.ncol > 0 ? t.col : static_cast<int64_t>(cb) * kTileCols;
+}
+
 // ---------------------------------------------------------------- sweep 1
 
-// Rows a wave handles per loop trip.  While one batch of rows is consumed the next
-// batch's loads are already in flight (two register buffers, ping-pong).
 #ifndef CAME_ROWS1
 #define CAME_ROWS1 4
 #endif
 constexpr int kRows1 = CAME_ROWS1;
 
-template <bool BF16, bool ALIGNED>
-__device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const void* g, char* scratch,
-                            float* lds /* [4][512] */)
+// ALIGNED: rows start 16-byte aligned (m % 8 == 0).  FULL: the tile's 512 columns all exist.
+template <bool BF16, bool ALIGNED, bool FULL>
+__device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
+                            char* scratch, float* lds /* [4][512] */, float* rowbuf /* [tile_rows] */)
 {
-    const TileGeom t = tile_geom(tm, it);
     float* rowpart = reinterpret_cast<float*>(scratch + tm.off_rowpart);
     float* colpart = reinterpret_cast<float*>(scratch + tm.off_colpart);
     const int64_t m = tm.m;
-    constexpr int kStep = kWaves * kRows1;
+    const bool lane_valid = t.ncol > 0;
+    const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
+    const int lncol = ALIGNED ? kLaneCols : t.ncol;
 
     float cacc[2][8];
 #pragma unroll
@@ -314,43 +349,44 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const void
 #pragma unroll
         for (int e = 0; e < 8; ++e) cacc[u][e] = 0.f;
 
-    auto load = [&](GradRaw<BF16> (&buf)[kRows1], int i) {
-#pragma unroll
-        for (int u = 0; u < kRows1; ++u) {
-            const int ii = i + kWaves * u;
-            buf[u] = load_grad_raw<BF16, ALIGNED>(g, (t.row0 + ii) * m + t.col, ii < t.nrows ? t.ncol : 0);
-        }
+    auto load_row = [&](int j) {
+        return load_grad_raw<BF16, ALIGNED>(g, (t.row0 + t.wave + kWaves * j) * m + lcol, lncol);
     };
-    auto consume = [&](const GradRaw<BF16> (&buf)[kRows1], int i) {
+    auto consume_row = [&](const GradRaw<BF16>& raw, int j, int slot) {
+        float x[8];
+        unpack<BF16>(raw, x);
+        float racc = 0.f;
 #pragma unroll
-        for (int u = 0; u < kRows1; ++u) {
-            const int ii = i + kWaves * u;
-            float x[8];
-            unpack<BF16>(buf[u], x);
-            float racc = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float sq = x[e] * x[e];
-                racc += sq;
-                cacc[u & 1][e] += sq;
-            }
-            racc = wave_sum_lane63(racc);
-            if (t.lane == 63 && ii < t.nrows) rowpart[(t.row0 + ii) * tm.CB + it.cb] = racc;
+        for (int e = 0; e < 8; ++e) {
+            if (ALIGNED && !FULL) x[e] = lane_valid ? x[e] : 0.f;
+            racc = fmaf(x[e], x[e], racc);
+            cacc[slot][e] = fmaf(x[e], x[e], cacc[slot][e]);
         }
+        racc = wave_sum_lane63(racc);
+        if (t.lane == 63) rowbuf[t.wave + kWaves * j] = racc;
     };
 
-    GradRaw<BF16> A[kRows1], B[kRows1];
-    int i = t.wave;
-    if (i < t.nrows) load(A, i);
-    while (i < t.nrows) {
-        if (i + kStep < t.nrows) load(B, i + kStep);
-        consume(A, i);
-        i += kStep;
-        if (i >= t.nrows) break;
-        if (i + kStep < t.nrows) load(A, i + kStep);
-        consume(B, i);
-        i += kStep;
+    const WaveRows wr = wave_rows<kRows1>(t);
+    if (wr.nfull > 0) {
+        GradRaw<BF16> A[kRows1], B[kRows1];
+#pragma unroll
+        for (int u = 0; u < kRows1; ++u) A[u] = load_row(u);
+        for (int k = 0;; k += 2) {
+            const int kb = min(k + 1, wr.nfull - 1);
+#pragma unroll
+            for (int u = 0; u < kRows1; ++u) B[u] = load_row(kb * kRows1 + u);
+#pragma unroll
+            for (int u = 0; u < kRows1; ++u) consume_row(A[u], k * kRows1 + u, u & 1);
+            if (k + 1 >= wr.nfull) break;
+            const int ka = min(k + 2, wr.nfull - 1);
+#pragma unroll
+            for (int u = 0; u < kRows1; ++u) A[u] = load_row(ka * kRows1 + u);
+#pragma unroll
+            for (int u = 0; u < kRows1; ++u) consume_row(B[u], (k + 1) * kRows1 + u, u & 1);
+            if (k + 2 >= wr.nfull) break;
+        }
     }
+    for (int j = wr.nfull * kRows1; j < wr.cnt; ++j) consume_row(load_row(j), j, j & 1);
 
     // column sums of the tile: the two accumulator sets, then the 4 waves through LDS
 #pragma unroll
@@ -363,6 +399,9 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const void
             colpart[static_cast<int64_t>(it.rb) * m + cj] = v;
         }
     }
+    // row sums of the tile, coalesced: rowpart[column block][row]
+    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup)
+        rowpart[static_cast<int64_t>(it.cb) * tm.n + t.row0 + i] = rowbuf[i];
 }
 
 // One __global__ entry per variant, each with the occupancy (waves per SIMD) its register
@@ -375,8 +414,15 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const void
     void NAME(DeviceTables tb, int32_t item_begin)                                                  \
     {                                                                                               \
         __shared__ float lds[kWaves * kTileCols];                                                   \
+        extern __shared__ float rowbuf_f32[];                                                       \
         const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
-        sweep1_tile<BF16, ALIGNED>(tb.metas[it.tensor], it, tb.grad[it.tensor], tb.scratch, lds);   \
+        const TensorMeta& tm = tb.metas[it.tensor];                                                 \
+        const TileGeom t = tile_geom(tm, it);                                                       \
+        const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
+        if (!ALIGNED || full)                                                                       \
+            sweep1_tile<BF16, ALIGNED, true>(tm, it, t, tb.grad[it.tensor], tb.scratch, lds, rowbuf_f32); \
+        else                                                                                        \
+            sweep1_tile<BF16, ALIGNED, false>(tm, it, t, tb.grad[it.tensor], tb.scratch, lds, rowbuf_f32); \
     }
 CAME_SWEEP1_KERNEL(sweep1_bf16_kernel, true, true, CAME_WAVES1)
 CAME_SWEEP1_KERNEL(sweep1_f32_kernel, false, true, 4)
@@ -413,9 +459,8 @@ __global__ __launch_bounds__(kWorkgroup) void finalize1_kernel(DeviceTables tb, 
         double mine = 0.0;
         if (idx < tm.n) {
             double s = 0.0;
-            const float* src = rowpart + idx * tm.CB;
 #pragma unroll 4
-            for (int cb = 0; cb < tm.CB; ++cb) s += static_cast<double>(src[cb]);
+            for (int cb = 0; cb < tm.CB; ++cb) s += static_cast<double>(rowpart[static_cast<int64_t>(cb) * tm.n + idx]);
             s += static_cast<double>(tm.m) * h.eps1;
             const float rn = static_cast<float>(h.beta2 * static_cast<double>(r[idx]) + h.one_minus_beta2 * s);
             r[idx] = rn;
@@ -443,12 +488,12 @@ __global__ __launch_bounds__(kWorkgroup) void finalize1_kernel(DeviceTables tb, 
 #endif
 constexpr int kRows2 = CAME_ROWS2;
 
-template <bool BF16, bool ALIGNED>
-__device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void* g, const float* state,
-                            char* scratch, TensorScalars* sc, double* lds /* [4][512] */,
-                            double* lds4)
+template <bool BF16, bool ALIGNED, bool FULL>
+__device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
+                            const float* state, char* scratch, TensorScalars* sc,
+                            double* lds /* [4][512] */, double* lds4, double* rowbuf /* [3][tile_rows] */,
+                            float* rowfac /* [tile_rows] */)
 {
-    const TileGeom t = tile_geom(tm, it);
     const int64_t m = tm.m;
     const float* r = state + tm.off_r;
     const float* c = state + tm.off_c;
@@ -456,74 +501,85 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void
     double* rowpart = reinterpret_cast<double*>(scratch + tm.off_rowpart);
     double* colpart = reinterpret_cast<double*>(scratch + tm.off_colpart);
     double* tileP = reinterpret_cast<double*>(scratch + tm.off_tileP);
-    constexpr int kStep = kWaves * kRows2;
+    const bool lane_valid = t.ncol > 0;
+    const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
+    const int lncol = ALIGNED ? kLaneCols : t.ncol;
+    const int TR = tm.tile_rows;
 
-    struct Rows { GradRaw<BF16> g[kRows2]; F32Raw mo[kRows2]; };
-    auto load = [&](Rows& buf, int i) {
-#pragma unroll
-        for (int u = 0; u < kRows2; ++u) {
-            const int ii = i + kWaves * u;
-            const int nc = ii < t.nrows ? t.ncol : 0;
-            const int64_t idx = (t.row0 + ii) * m + t.col;
-            buf.g[u] = load_grad_raw<BF16, ALIGNED>(g, idx, nc);
-            buf.mo[u] = load_f32_raw<ALIGNED>(M, idx, nc);
-        }
+    struct Row { GradRaw<BF16> g; F32Raw mo; };
+    auto load_row = [&](int j) {
+        Row x;
+        const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
+        x.g = load_grad_raw<BF16, ALIGNED>(g, idx, lncol);
+        x.mo = load_f32_raw<ALIGNED>(M, idx, lncol);
+        return x;
     };
-    Rows A, B;
-    int i = t.wave;
-    if (i < t.nrows) load(A, i);
+    const WaveRows wr = wave_rows<kRows2>(t);
+    Row A[kRows2], B[kRows2];
+    if (wr.nfull > 0) {
+#pragma unroll
+        for (int u = 0; u < kRows2; ++u) A[u] = load_row(u);
+    }
 
     // 1^T r_t from the per-workgroup sums finalize 1 left (every wave, same order, same bits)
     const double sum_r = wave_sum_list(reinterpret_cast<const double*>(scratch + tm.off_fpart), tm.f_row_wgs);
     const float sqrt_sum_r = static_cast<float>(sqrt(sum_r));
     if (it.rb == 0 && it.cb == 0 && threadIdx.x == 0) sc->sqrt_sum_r = sqrt_sum_r;
 
+    // per-row factor rsqrt(r_i / 1^T r) of the tile's rows, once, into LDS: inside the row
+    // loop it is then an LDS broadcast read and no global load has to be waited for there
+    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup) rowfac[i] = rsqrtf(r[t.row0 + i]) * sqrt_sum_r;
+
     float b[8];  // rsqrt(c_j) of this lane's columns
+    {
+        float cv[8];
+        unpack(load_f32_raw<ALIGNED>(c, lcol, lncol), cv);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) b[e] = e < t.ncol ? rsqrtf(c[t.col + e]) : 0.f;
+        for (int e = 0; e < 8; ++e) b[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
+    }
+    __syncthreads();
 
     double cP[8], cQ[8], cW[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) cP[e] = cQ[e] = cW[e] = 0.0;
-    double waveP = 0.0;  // meaningful in lane 63
 
-    auto consume = [&](const Rows& buf, int i0) {
+    auto consume_row = [&](const Row& row, int j) {
+        const int i = t.wave + kWaves * j;
+        const float a = rowfac[i];  // rsqrt(r_i / 1^T r)
+        float x[8], mo[8];
+        unpack<BF16>(row.g, x);
+        unpack(row.mo, mo);
+        double rP = 0.0, rQ = 0.0, rW = 0.0;
 #pragma unroll
-        for (int u = 0; u < kRows2; ++u) {
-            const int ii = i0 + kWaves * u;
-            if (ii < t.nrows) {
-                const float a = rsqrtf(r[t.row0 + ii]) * sqrt_sum_r;  // rsqrt(r_i / 1^T r)
-                float x[8], mo[8];
-                unpack<BF16>(buf.g[u], x);
-                unpack(buf.mo[u], mo);
-                double rP = 0.0, rQ = 0.0, rW = 0.0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float uf = (x[e] * a) * b[e];  // u_ij = g_ij / sqrt(v_ij)
-                    const double du = static_cast<double>(uf);
-                    const double dm = static_cast<double>(mo[e]);
-                    rP = fma(du, du, rP); rQ = fma(du, dm, rQ); rW = fma(dm, dm, rW);
-                    cP[e] = fma(du, du, cP[e]); cQ[e] = fma(du, dm, cQ[e]); cW[e] = fma(dm, dm, cW[e]);
-                }
-                rP = wave_sum_lane63(rP); rQ = wave_sum_lane63(rQ); rW = wave_sum_lane63(rW);
-                if (t.lane == 63) {
-                    double* dst = rowpart + ((t.row0 + ii) * tm.CB + it.cb) * 3;
-                    dst[0] = rP; dst[1] = rQ; dst[2] = rW;
-                }
-                waveP += rP;
-            }
+        for (int e = 0; e < 8; ++e) {
+            if (ALIGNED && !FULL) mo[e] = lane_valid ? mo[e] : 0.f;   // (b[e] = 0 already zeroes u)
+            const float uf = (x[e] * a) * b[e];  // u_ij = g_ij / sqrt(v_ij)
+            const double du = static_cast<double>(uf);
+            const double dm = static_cast<double>(mo[e]);
+            rP = fma(du, du, rP); rQ = fma(du, dm, rQ); rW = fma(dm, dm, rW);
+            cP[e] = fma(du, du, cP[e]); cQ[e] = fma(du, dm, cQ[e]); cW[e] = fma(dm, dm, cW[e]);
         }
+        rP = wave_sum_lane63(rP); rQ = wave_sum_lane63(rQ); rW = wave_sum_lane63(rW);
+        if (t.lane == 63) { rowbuf[i] = rP; rowbuf[TR + i] = rQ; rowbuf[2 * TR + i] = rW; }
     };
 
-    while (i < t.nrows) {
-        if (i + kStep < t.nrows) load(B, i + kStep);
-        consume(A, i);
-        i += kStep;
-        if (i >= t.nrows) break;
-        if (i + kStep < t.nrows) load(A, i + kStep);
-        consume(B, i);
-        i += kStep;
+    if (wr.nfull > 0) {
+        for (int k = 0;; k += 2) {
+            const int kb = min(k + 1, wr.nfull - 1);
+#pragma unroll
+            for (int u = 0; u < kRows2; ++u) B[u] = load_row(kb * kRows2 + u);
+#pragma unroll
+            for (int u = 0; u < kRows2; ++u) consume_row(A[u], k * kRows2 + u);
+            if (k + 1 >= wr.nfull) break;
+            const int ka = min(k + 2, wr.nfull - 1);
+#pragma unroll
+            for (int u = 0; u < kRows2; ++u) A[u] = load_row(ka * kRows2 + u);
+#pragma unroll
+            for (int u = 0; u < kRows2; ++u) consume_row(B[u], (k + 1) * kRows2 + u);
+            if (k + 2 >= wr.nfull) break;
+        }
     }
+    for (int j = wr.nfull * kRows2; j < wr.cnt; ++j) consume_row(load_row(j), j);
 
     // column sums across the 4 waves, one statistic at a time through 16 KB of LDS
 #pragma unroll
@@ -541,11 +597,19 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void
         }
         __syncthreads();
     }
-    // sum of u^2 over the tile (feeds RMS(u_t))
-    if (t.lane == 63) lds4[t.wave] = waveP;
-    __syncthreads();
-    if (threadIdx.x == 0)
-        tileP[static_cast<int64_t>(it.rb) * tm.CB + it.cb] = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
+    // row sums of the tile, coalesced: rowpart[column block][statistic][row]; and the
+    // tile's sum of u^2 (feeds RMS(u_t))
+    double p = 0.0;
+    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup) {
+        const double vP = rowbuf[i];
+        p += vP;
+        const int64_t base = static_cast<int64_t>(it.cb) * 3 * tm.n + t.row0 + i;
+        rowpart[base] = vP;
+        rowpart[base + tm.n] = rowbuf[TR + i];
+        rowpart[base + 2 * tm.n] = rowbuf[2 * TR + i];
+    }
+    p = block_sum(p, lds4);
+    if (threadIdx.x == 0) tileP[static_cast<int64_t>(it.rb) * tm.CB + it.cb] = p;
 }
 
 #ifndef CAME_WAVES2
@@ -557,9 +621,18 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const void
     {                                                                                               \
         __shared__ double lds[kWaves * kTileCols];                                                  \
         __shared__ double lds4[4];                                                                  \
+        extern __shared__ double rowbuf_f64[];                                                      \
         const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
-        sweep2_tile<BF16, ALIGNED>(tb.metas[it.tensor], it, tb.grad[it.tensor], tb.state,           \
-                                   tb.scratch, tb.scalars + it.tensor, lds, lds4);                  \
+        const TensorMeta& tm = tb.metas[it.tensor];                                                 \
+        const TileGeom t = tile_geom(tm, it);                                                       \
+        float* rowfac = reinterpret_cast<float*>(rowbuf_f64 + 3 * tm.tile_rows);                    \
+        const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
+        if (!ALIGNED || full)                                                                       \
+            sweep2_tile<BF16, ALIGNED, true>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch,   \
+                                             tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
+        else                                                                                        \
+            sweep2_tile<BF16, ALIGNED, false>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch,  \
+                                              tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
     }
 CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, CAME_WAVES2)
 CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, 2)
@@ -604,10 +677,10 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
         double mine = 0.0;
         if (idx < tm.n) {
             double sP = 0.0, sQ = 0.0, sW = 0.0;
-            const double* src = rowpart + idx * tm.CB * 3;
 #pragma unroll 4
             for (int cb = 0; cb < tm.CB; ++cb) {
-                sP += src[3 * cb]; sQ += src[3 * cb + 1]; sW += src[3 * cb + 2];
+                const int64_t base = static_cast<int64_t>(cb) * 3 * tm.n + idx;
+                sP += rowpart[base]; sQ += rowpart[base + tm.n]; sW += rowpart[base + 2 * tm.n];
             }
             double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
             U = fmax(U, 0.0);
@@ -646,35 +719,37 @@ constexpr int kRows3 = CAME_ROWS3;
 
 // u^ = kappa g / sqrt(v);  M_t = beta1 M_{t-1} + (1-beta1) u^;
 // theta_t = theta_{t-1} - eta M_t / sqrt(S_t)      (Algorithm 1: theta_t = theta_{t-1} - eta M_t)
-template <bool BF16, bool ALIGNED>
-__device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const void* g, float* theta,
-                            float* state, const char* scratch, const TensorScalars* sc, const SweepHyper& h)
+template <bool BF16, bool ALIGNED, bool FULL>
+__device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
+                            float* theta, float* state, const char* scratch, const TensorScalars* sc,
+                            const SweepHyper& h, float* rowfac /* [2][tile_rows] */)
 {
-    const TileGeom t = tile_geom(tm, it);
     const int64_t m = tm.m;
+    const int TR = tm.tile_rows;
     const float* r = state + tm.off_r;
     const float* c = state + tm.off_c;
     const float* R = state + tm.off_R;
     const float* C = state + tm.off_C;
     float* M = state + tm.off_M;
     const bool came = h.algo == CAME_ALGO_CAME;
-    constexpr int kStep = kWaves * kRows3;
+    const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
+    const int lncol = ALIGNED ? kLaneCols : t.ncol;
 
-    struct Rows { GradRaw<BF16> g[kRows3]; F32Raw mo[kRows3], th[kRows3]; };
-    auto load = [&](Rows& buf, int i) {
-#pragma unroll
-        for (int u = 0; u < kRows3; ++u) {
-            const int ii = i + kWaves * u;
-            const int nc = ii < t.nrows ? t.ncol : 0;
-            const int64_t idx = (t.row0 + ii) * m + t.col;
-            buf.g[u] = load_grad_raw<BF16, ALIGNED>(g, idx, nc);
-            buf.mo[u] = load_f32_raw<ALIGNED>(M, idx, nc);
-            buf.th[u] = load_f32_raw<ALIGNED>(theta, idx, nc);
-        }
+    struct Row { GradRaw<BF16> g; F32Raw mo, th; };
+    auto load_row = [&](int j) {
+        Row x;
+        const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
+        x.g = load_grad_raw<BF16, ALIGNED>(g, idx, lncol);
+        x.mo = load_f32_raw<ALIGNED>(M, idx, lncol);
+        x.th = load_f32_raw<ALIGNED>(theta, idx, lncol);
+        return x;
     };
-    Rows A, B;
-    int i = t.wave;
-    if (i < t.nrows) load(A, i);
+    const WaveRows wr = wave_rows<kRows3>(t);
+    Row A[kRows3], B[kRows3];
+    if (wr.nfull > 0) {
+#pragma unroll
+        for (int u = 0; u < kRows3; ++u) A[u] = load_row(u);
+    }
 
     // 1^T R_t from the per-workgroup sums finalize 2 left (every wave, same order, same bits)
     float sqrt_sum_R = 1.f;
@@ -684,46 +759,71 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const void
     const float row_scale_u = sc->sqrt_sum_r * sc->kappa;
     const float row_scale_s = came ? sqrt_sum_R * h.lr : h.lr;
 
-    float b[8], Bc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        b[e] = e < t.ncol ? rsqrtf(c[t.col + e]) : 0.f;
-        Bc[e] = came ? (e < t.ncol ? rsqrtf(C[t.col + e]) : 0.f) : 1.f;
+    // per-row factors kappa rsqrt(r_i / 1^T r) and eta rsqrt(R_i / 1^T R) of the tile's rows,
+    // once, into LDS (inside the row loop: LDS broadcast reads, no global load to wait for)
+    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup) {
+        rowfac[i] = rsqrtf(r[t.row0 + i]) * row_scale_u;
+        rowfac[TR + i] = came ? rsqrtf(R[t.row0 + i]) * row_scale_s : row_scale_s;
     }
 
-    auto consume = [&](const Rows& buf, int i0) {
+    float b[8], Bc[8];
+    {
+        float cv[8];
+        unpack(load_f32_raw<ALIGNED>(c, lcol, lncol), cv);
 #pragma unroll
-        for (int u = 0; u < kRows3; ++u) {
-            const int ii = i0 + kWaves * u;
-            if (ii < t.nrows) {
-                const float a = rsqrtf(r[t.row0 + ii]) * row_scale_u;
-                const float Ar = came ? rsqrtf(R[t.row0 + ii]) * row_scale_s : row_scale_s;
-                float x[8], mo[8], th[8], mn[8], tn[8];
-                unpack<BF16>(buf.g[u], x);
-                unpack(buf.mo[u], mo);
-                unpack(buf.th[u], th);
+        for (int e = 0; e < 8; ++e) b[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
+        if (came) {
+            unpack(load_f32_raw<ALIGNED>(C, lcol, lncol), cv);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float uh = (x[e] * a) * b[e];
-                    mn[e] = fmaf(h.beta1, mo[e], h.one_minus_beta1 * uh);
-                    tn[e] = th[e] - (mn[e] * Ar) * Bc[e];
-                }
-                const int64_t idx = (t.row0 + ii) * m + t.col;
-                store_f32x8<ALIGNED>(M, idx, t.ncol, mn);
-                store_f32x8<ALIGNED>(theta, idx, t.ncol, tn);
-            }
+            for (int e = 0; e < 8; ++e) Bc[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Bc[e] = 1.f;
+        }
+    }
+    __syncthreads();
+
+    auto consume_row = [&](const Row& row, int j) {
+        const int i = t.wave + kWaves * j;
+        const float a = rowfac[i];
+        const float Ar = rowfac[TR + i];
+        float x[8], mo[8], th[8], mn[8], tn[8];
+        unpack<BF16>(row.g, x);
+        unpack(row.mo, mo);
+        unpack(row.th, th);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float uh = (x[e] * a) * b[e];
+            mn[e] = fmaf(h.beta1, mo[e], h.one_minus_beta1 * uh);
+            tn[e] = th[e] - (mn[e] * Ar) * Bc[e];
+        }
+        const int64_t idx = (t.row0 + i) * m + t.col;
+        if constexpr (ALIGNED && FULL) {
+            store_f32x8<true>(M, idx, kLaneCols, mn);
+            store_f32x8<true>(theta, idx, kLaneCols, tn);
+        } else {
+            store_f32x8<ALIGNED>(M, idx, t.ncol, mn);
+            store_f32x8<ALIGNED>(theta, idx, t.ncol, tn);
         }
     };
 
-    while (i < t.nrows) {
-        if (i + kStep < t.nrows) load(B, i + kStep);
-        consume(A, i);
-        i += kStep;
-        if (i >= t.nrows) break;
-        if (i + kStep < t.nrows) load(A, i + kStep);
-        consume(B, i);
-        i += kStep;
+    if (wr.nfull > 0) {
+        for (int k = 0;; k += 2) {
+            const int kb = min(k + 1, wr.nfull - 1);
+#pragma unroll
+            for (int u = 0; u < kRows3; ++u) B[u] = load_row(kb * kRows3 + u);
+#pragma unroll
+            for (int u = 0; u < kRows3; ++u) consume_row(A[u], k * kRows3 + u);
+            if (k + 1 >= wr.nfull) break;
+            const int ka = min(k + 2, wr.nfull - 1);
+#pragma unroll
+            for (int u = 0; u < kRows3; ++u) A[u] = load_row(ka * kRows3 + u);
+#pragma unroll
+            for (int u = 0; u < kRows3; ++u) consume_row(B[u], (k + 1) * kRows3 + u);
+            if (k + 2 >= wr.nfull) break;
+        }
     }
+    for (int j = wr.nfull * kRows3; j < wr.cnt; ++j) consume_row(load_row(j), j);
 }
 
 #ifndef CAME_WAVES3
@@ -733,10 +833,18 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const void
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
     void NAME(DeviceTables tb, int32_t item_begin, SweepHyper h)                                    \
     {                                                                                               \
+        extern __shared__ float rowfac_f32[];                                                       \
         const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
-        sweep3_tile<BF16, ALIGNED>(tb.metas[it.tensor], it, tb.grad[it.tensor],                     \
-                                   static_cast<float*>(tb.theta[it.tensor]), tb.state, tb.scratch,  \
-                                   tb.scalars + it.tensor, h);                                      \
+        const TensorMeta& tm = tb.metas[it.tensor];                                                 \
+        const TileGeom t = tile_geom(tm, it);                                                       \
+        const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
+        float* theta = static_cast<float*>(tb.theta[it.tensor]);                                    \
+        if (!ALIGNED || full)                                                                       \
+            sweep3_tile<BF16, ALIGNED, true>(tm, it, t, tb.grad[it.tensor], theta, tb.state,        \
+                                             tb.scratch, tb.scalars + it.tensor, h, rowfac_f32);    \
+        else                                                                                        \
+            sweep3_tile<BF16, ALIGNED, false>(tm, it, t, tb.grad[it.tensor], theta, tb.state,       \
+                                              tb.scratch, tb.scalars + it.tensor, h, rowfac_f32);   \
     }
 CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, CAME_WAVES3)
 CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, 3)
@@ -781,16 +889,17 @@ hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t ite
     return hipGetLastError();
 }
 
-hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
-                         hipStream_t s)
+hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
+                         int32_t item_end, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    const size_t dyn = sizeof(float) * static_cast<size_t>(tile_rows);  // row sums of one tile
     switch (variant) {
-        case 0: sweep1_bf16_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
-        case 1: sweep1_f32_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
-        case 2: sweep1_bf16_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
-        default: sweep1_f32_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        case 0: sweep1_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        case 1: sweep1_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        case 2: sweep1_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        default: sweep1_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
     }
     return hipGetLastError();
 }
@@ -803,16 +912,18 @@ hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fi
     return hipGetLastError();
 }
 
-hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
-                         hipStream_t s)
+hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
+                         int32_t item_end, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    // three row statistics (double) and one row factor (float) per row of a tile
+    const size_t dyn = (sizeof(double) * 3 + sizeof(float)) * static_cast<size_t>(tile_rows);
     switch (variant) {
-        case 0: sweep2_bf16_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
-        case 1: sweep2_f32_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
-        case 2: sweep2_bf16_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
-        default: sweep2_f32_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin); break;
+        case 0: sweep2_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        case 1: sweep2_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        case 2: sweep2_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        default: sweep2_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
     }
     return hipGetLastError();
 }
@@ -825,16 +936,17 @@ hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fi
     return hipGetLastError();
 }
 
-hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
-                         const SweepHyper& h, hipStream_t s)
+hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
+                         int32_t item_end, const SweepHyper& h, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    const size_t dyn = sizeof(float) * 2 * static_cast<size_t>(tile_rows);  // two row factors per row of a tile
     switch (variant) {
-        case 0: sweep3_bf16_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
-        case 1: sweep3_f32_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
-        case 2: sweep3_bf16_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
-        default: sweep3_f32_unaligned_kernel<<<grid, block, 0, s>>>(t, item_begin, h); break;
+        case 0: sweep3_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        case 1: sweep3_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        case 2: sweep3_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        default: sweep3_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
     }
     return hipGetLastError();
 }

@@ -58,7 +58,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     for (int32_t v : o.reserved)
         if (v != 0) return CAME_EINVAL;
     if (o.algo != CAME_ALGO_CAME && o.algo != CAME_ALGO_ADAFACTOR) return CAME_EINVAL;
-    if (o.tile_rows != 0 && (o.tile_rows < 4 || o.tile_rows > 4096 || o.tile_rows % 4 != 0))
+    if (o.tile_rows != 0 && (o.tile_rows < 4 || o.tile_rows > 1024 || o.tile_rows % 4 != 0))
         return CAME_EINVAL;
     if (o.group_elements < 0) return CAME_EINVAL;
 
