@@ -50,7 +50,7 @@ def cpu_baseline(w, gen, hyper, lr, budget_s: float = 12.0):
 
     first = next(i for i, s in enumerate(w.shapes) if len(s) == 2) + 1  # skip the embedding
     per_layer = 9
-    idx = list(range(first, min(first + 2 * per_layer, len(w.shapes))))
+    idx = list(range(min(first, len(w.shapes) - 1), min(first + 2 * per_layer, len(w.shapes))))
     shapes = [w.shapes[i] for i in idx]
     n_params = sum(math.prod(s) for s in shapes)
     to64 = lambda t: t.detach().to("cpu").float().numpy().astype(np.float64)

@@ -54,9 +54,9 @@ hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, 
 // Finalize 1: r, c and the per-workgroup sums of r.
 hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);
-// Sweep 2: row/column sums of u^2, u*M, M^2 and the per-tile sum of u^2.
-hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
-                         int32_t item_end, hipStream_t s);
+// Sweep 2: row/column sums of u^2, u*M, M^2 and the per-tile sum of u^2 (Algorithm 1: the latter only).
+hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t tile_rows,
+                         int32_t item_begin, int32_t item_end, hipStream_t s);
 // Finalize 2: kappa (Eq. 1), R, C and the per-workgroup sums of R.
 hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);

@@ -37,14 +37,15 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
 class SideBySide:
     """GPU library on every tensor of `shapes`; oracle on the tensors in `check`."""
 
-    def __init__(self, w: W.Workload, indices=None, check=None, hyper=None, device="cuda:0", **opts):
+    def __init__(self, w: W.Workload, indices=None, check=None, hyper=None, device="cuda:0", algo=0, **opts):
         self.w = w
         self.gen = W.Generator(w, device=device)
         self.idx = list(range(len(w.shapes))) if indices is None else list(indices)
         self.check = list(range(len(self.idx))) if check is None else list(check)  # positions in self.idx
         self.shapes = [w.shapes[i] for i in self.idx]
         self.hyper = hyper or P.CameHyper()
-        self.opt = P.CameStep(self.shapes, [w.grad_dtype] * len(self.shapes), device=device, **opts)
+        self.algo = algo  # 0: Algorithm 2 (CAME), 1: Algorithm 1 (Adafactor with momentum)
+        self.opt = P.CameStep(self.shapes, [w.grad_dtype] * len(self.shapes), device=device, algo=algo, **opts)
         self.theta = [self.gen.theta0(i) for i in self.idx]
         self.otl = O.TensorList([self.shapes[k] for k in self.check], [to_f64(self.theta[k]) for k in self.check])
         self.t = 0
@@ -56,7 +57,19 @@ class SideBySide:
         self.opt.step(self.theta, grads, self.hyper, self.w.lr, self.t)
         oh = O.Hyper(self.hyper.beta1, self.hyper.beta2, self.hyper.beta3, self.hyper.eps1, self.hyper.eps2,
                      self.hyper.clip_d, self.w.lr)
-        self.otl.step([to_f64(grads[k]) for k in self.check], oh, nthreads=nthreads)
+        og = [to_f64(grads[k]) for k in self.check]
+        if self.algo == 0:
+            self.otl.step(og, oh, nthreads=nthreads)
+        else:
+            # Algorithm 1 per tensor; a vector is its n x 1 matrix (then v = r, c is a scalar)
+            for pos, g in enumerate(og):
+                st, th = self.otl.state[pos], self.otl.theta[pos]
+                if isinstance(st, O.MatrixState):
+                    O.adafactor_matrix_step(th, g, st.M, st.r, st.c, oh)
+                else:
+                    if not hasattr(st, "c1"):
+                        st.c1 = np.zeros(1)
+                    O.adafactor_matrix_step(th.reshape(-1, 1), g.reshape(-1, 1), st.M.reshape(-1, 1), st.v, st.c1, oh)
         torch.cuda.synchronize()
 
     def errors(self) -> dict:
@@ -77,11 +90,17 @@ class SideBySide:
             if len(self.shapes[k]) == 2:
                 upd("r", rel_err_positive(to_f64(sv["r"]), st.r), k)
                 upd("c", rel_err_positive(to_f64(sv["c"]), st.c), k)
-                upd("R", rel_err_positive(to_f64(sv["R"]), st.R), k)
-                upd("C", rel_err_positive(to_f64(sv["C"]), st.C), k)
+                if self.algo == 0:
+                    upd("R", rel_err_positive(to_f64(sv["R"]), st.R), k)
+                    upd("C", rel_err_positive(to_f64(sv["C"]), st.C), k)
+                else:  # Algorithm 1 has no confidence statistics: they must stay untouched
+                    assert not sv["R"].any() and not sv["C"].any()
             else:
                 upd("v", rel_err_positive(to_f64(sv["r"]), st.v), k)
-                upd("s", rel_err_positive(to_f64(sv["R"]), st.s), k)
+                if self.algo == 0:
+                    upd("s", rel_err_positive(to_f64(sv["R"]), st.s), k)
+                else:
+                    assert not sv["R"].any()
         return worst
 
     def assert_within(self, tol: float, label: str = ""):

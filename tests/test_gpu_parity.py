@@ -95,6 +95,37 @@ def test_odd_shapes(dtype):
     _run(w, 5, TOL_100, check_every=1, tile_rows=8)
 
 
+@pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["f32", "bf16"])
+def test_adafactor_mode_matches_algorithm_1(dtype):
+    """CAME_ALGO_ADAFACTOR against the oracle's Algorithm 1 (Adafactor with momentum):
+    same r, c, M recursion, theta moves by -eta m_t, R and C stay zero."""
+    shapes = [(256, 512), (512,), (300, 1032), (77,), (5, 13), (64, 2048), (1030, 8)]
+    w = W.Workload("adafactor", shapes, dtype, seed=21, steps=10, grad_kind="normal", scale_range=(1e-4, 1e-1),
+                   zero_row_fraction=0.05, lr=1e-3)
+    _run(w, 10, TOL_100, check_every=1, algo=P.ALGO_ADAFACTOR, tile_rows=32)
+
+
+def test_adafactor_and_came_share_momentum_and_second_moment():
+    """Algorithm 1 is Algorithm 2 without the confidence lines: on the same gradients the two
+    modes must produce the same M, r, c (they never read theta, R, C)."""
+    w = W.Workload("shared", [(300, 1024), (1024,), (130, 24)], W.GRAD_BF16, seed=22, steps=5,
+                   grad_kind="normal", scale_range=(1e-3, 1e-1))
+    res = []
+    for algo in (P.ALGO_CAME, P.ALGO_ADAFACTOR):
+        gen = W.Generator(w, device="cuda:0")
+        th = [gen.theta0(i) for i in range(3)]
+        opt = P.CameStep(w.shapes, [w.grad_dtype] * 3, algo=algo, tile_rows=64)
+        for t in range(1, 6):
+            opt.step(th, [gen.grad(i, t) for i in range(3)], P.CameHyper(), 1e-3, t)
+        torch.cuda.synchronize()
+        res.append([opt.state_view(i)[k].clone() for i in range(3) for k in "Mrc" if opt.state_view(i)[k] is not None])
+        opt.close()
+    for a, b in zip(*res):
+        a, b = a.double().cpu().numpy(), b.double().cpu().numpy()
+        scale = np.sqrt(np.mean(b * b))
+        assert np.max(np.abs(a - b) / (np.abs(b) + scale)) < 1e-6
+
+
 def test_transposed_matrix_swaps_row_and_column_statistics():
     """Algorithm 2 is symmetric in rows and columns: g^T, theta^T give theta^T, M^T,
     r <-> c, R <-> C.  On the GPU the row reduction (wave shuffles) and the column
