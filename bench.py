@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--group-elements", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0)
+    ap.add_argument("--no-placement", action="store_true",
+                    help="allocate the state blob wherever the allocator puts it (default: probe up to 3 "
+                         "addresses against the parameters and keep the fastest)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 4 GiB device-to-device copy a few times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -123,7 +126,7 @@ def main() -> int:
     # two gradient sets, alternated step by step, so that no random numbers are drawn inside the timed region
     grad_sets = [[gen.grad(i, t) for i in range(n)] for t in (1, 2)]
     opt = P.CameStep(w.shapes, [w.grad_dtype] * n, device=dev, tile_rows=args.tile_rows,
-                     group_elements=args.group_elements)
+                     group_elements=args.group_elements, place_against=None if args.no_placement else theta)
     opt.check_tensors(theta, grad_sets[0])
     plan = P.plan_query(w.shapes, [w.grad_dtype] * n, tile_rows=args.tile_rows,
                         group_elements=args.group_elements)
@@ -197,6 +200,7 @@ def main() -> int:
             "param_state_dtype": "f32",
             "tile_rows": plan["tile_rows"],
             "launch_groups": plan["groups"],
+            "state_placement_probe_GBs": [round(g, 1) for _, g in opt.placement_log],
         },
         "roofline": roofline,
     }

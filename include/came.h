@@ -175,6 +175,22 @@ int came_plan_query(const came_tensor_desc *descs, int32_t count, const came_opt
 double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which);
 
 /*
+ * Placement probe.  On MI355X the time of the one sweep that both reads and writes
+ * (sweep 3: theta and M in place) depends on WHERE the caller's buffers sit physically:
+ * when theta and the state blob share one of the HBM's three 96 GB address regions the
+ * mixed read/write stream runs at about 5.2 TB/s, when they sit in different regions at
+ * about 6.0 TB/s (pure reads and pure writes do not care).  The library owns no memory,
+ * so it can only measure: this call rewrites every matrix's theta and M with their own
+ * contents (sweep 3's traffic, no arithmetic, nothing changes) `repeats` times on
+ * hip_stream, waits, and reports the achieved GB/s (0 if the list has no matrix).  A
+ * caller can allocate its state blob at several addresses, probe each against its
+ * parameters and keep the fastest.  theta_dev: host array of `count` device pointers
+ * as for came_step.  Synchronises the stream.  Valid any time after came_init_state.
+ */
+int came_probe_placement(came_ctx *ctx, void *const *theta_dev, void *hip_stream, int32_t repeats,
+                         double *gbytes_per_s);
+
+/*
  * Built-in phase timer.  While enabled, came_step brackets each of its
  * launches with HIP events on the step's stream.  came_profile_read waits for
  * the recorded events, adds the elapsed milliseconds and launch counts per

@@ -3,6 +3,7 @@
 // are in came_kernels.hip.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -78,6 +79,41 @@ DeviceTables tables_for(const came_ctx* ctx, int slot)
     t.state = ctx->state;
     t.scratch = ctx->scratch;
     return t;
+}
+
+// Pointer table: re-uploaded only when an address changed since the last call.
+int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev, hipStream_t s)
+{
+    const Plan& p = ctx->plan;
+    const size_t count = p.descs.size();
+    bool changed = ctx->slot < 0 || ctx->cached.size() != 2 * count;
+    if (!changed) {
+        for (size_t t = 0; t < count && !changed; ++t)
+            changed = ctx->cached[t] != theta_dev[t] || ctx->cached[count + t] != grad_dev[t];
+    }
+    if (changed) {
+        const int slot = (ctx->slot + 1) % kPtrSlots;
+        if (ctx->slot_used[slot]) {
+            const hipError_t e = hipEventSynchronize(ctx->slot_event[slot]);
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
+        ctx->cached.resize(2 * count);
+        for (size_t t = 0; t < count; ++t) {
+            ctx->cached[t] = theta_dev[t];
+            ctx->cached[count + t] = grad_dev[t];
+        }
+        char* host_slot = ctx->pinned + p.ptr_slot_bytes * static_cast<size_t>(slot);
+        std::memcpy(host_slot, ctx->cached.data(), sizeof(void*) * 2 * count);
+        hipError_t e = hipMemcpyAsync(ctx->scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot),
+                                      host_slot, sizeof(void*) * 2 * count, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
+        e = hipEventRecord(ctx->slot_event[slot], s);
+        if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
+        ctx->slot_used[slot] = true;
+        ctx->slot = slot;
+    }
+
+    return CAME_OK;
 }
 
 }  // namespace
@@ -197,33 +233,8 @@ int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-    // pointer table: re-upload only when an address changed since the last call
-    bool changed = ctx->slot < 0;
-    if (!changed) {
-        for (size_t t = 0; t < count && !changed; ++t)
-            changed = ctx->cached[t] != theta_dev[t] || ctx->cached[count + t] != grad_dev[t];
-    }
-    if (changed) {
-        const int slot = (ctx->slot + 1) % kPtrSlots;
-        if (ctx->slot_used[slot]) {
-            const hipError_t e = hipEventSynchronize(ctx->slot_event[slot]);
-            if (e != hipSuccess) return hip_fail(ctx, e);
-        }
-        ctx->cached.resize(2 * count);
-        for (size_t t = 0; t < count; ++t) {
-            ctx->cached[t] = theta_dev[t];
-            ctx->cached[count + t] = grad_dev[t];
-        }
-        char* host_slot = ctx->pinned + p.ptr_slot_bytes * static_cast<size_t>(slot);
-        std::memcpy(host_slot, ctx->cached.data(), sizeof(void*) * 2 * count);
-        hipError_t e = hipMemcpyAsync(ctx->scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot),
-                                      host_slot, sizeof(void*) * 2 * count, hipMemcpyHostToDevice, s);
-        if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
-        e = hipEventRecord(ctx->slot_event[slot], s);
-        if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
-        ctx->slot_used[slot] = true;
-        ctx->slot = slot;
-    }
+    rc = upload_pointers(ctx, theta_dev, grad_dev, s);
+    if (rc != CAME_OK) return rc;
 
     SweepHyper sh{};
     sh.beta1 = static_cast<float>(hyper->beta1);
@@ -286,6 +297,62 @@ int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
     view->R = ctx->state + tm.off_R;
     view->c = tm.off_c >= 0 ? ctx->state + tm.off_c : nullptr;
     view->C = tm.off_C >= 0 ? ctx->state + tm.off_C : nullptr;
+    return CAME_OK;
+}
+
+int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream, int32_t repeats,
+                         double* gbytes_per_s)
+{
+    if (!ctx || !theta_dev || !gbytes_per_s || repeats < 1 || repeats > 1000) return CAME_EINVAL;
+    const Plan& p = ctx->plan;
+    const size_t count = p.descs.size();
+    for (size_t t = 0; t < count; ++t) {
+        if (!theta_dev[t]) return CAME_EINVAL;
+        if (!aligned_to(theta_dev[t], 16)) return CAME_EALIGN;
+    }
+    *gbytes_per_s = 0.0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // the probe reads no gradients: the pointer table's gradient half just repeats theta
+    std::vector<const void*> fake(theta_dev, theta_dev + count);
+    int rc = upload_pointers(ctx, theta_dev, fake.data(), s);
+    if (rc != CAME_OK) return rc;
+    ctx->cached.clear();  // force a fresh table at the next came_step
+    const int used_slot = ctx->slot;
+    double bytes = 0.0;
+    for (const Group& g : p.groups)
+        for (int v = 0; v < 2; ++v)  // aligned variants only
+            for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
+                const TensorMeta& tm = p.metas[p.items[k].tensor];
+                const int64_t rows = std::min<int64_t>(tm.tile_rows, tm.n - int64_t(p.items[k].rb) * tm.tile_rows);
+                const int64_t cols = std::min<int64_t>(kTileCols, tm.m - int64_t(p.items[k].cb) * kTileCols);
+                bytes += 16.0 * static_cast<double>(rows * cols);  // theta and M, read and written
+            }
+    if (bytes == 0.0) return CAME_OK;
+    const DeviceTables tb = tables_for(ctx, used_slot);
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    e = hipEventCreate(&e1);
+    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(ctx, e); }
+    auto run_once = [&]() -> hipError_t {
+        for (const Group& g : p.groups)
+            for (int v = 0; v < 2; ++v) {
+                const hipError_t le = launch_placement_probe(tb, g.var_begin[v], g.var_end[v], s);
+                if (le != hipSuccess) return le;
+            }
+        return hipSuccess;
+    };
+    e = run_once();  // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int r = 0; r < repeats && e == hipSuccess; ++r) e = run_once();
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    if (ms > 0.f) *gbytes_per_s = bytes * repeats / (static_cast<double>(ms) * 1e-3) / 1e9;
     return CAME_OK;
 }
 

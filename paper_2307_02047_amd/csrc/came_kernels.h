@@ -45,6 +45,10 @@ hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s);
 // `variant` (see variant_of) selects the kernel instantiation; all work items in
 // [item_begin, item_end) must be matrix tiles of tensors of that variant.
 
+// Rewrites theta and M of the matrix tiles [item_begin, item_end) with their own contents
+// (sweep 3's memory traffic, no arithmetic).
+hipError_t launch_placement_probe(const DeviceTables& t, int32_t item_begin, int32_t item_end, hipStream_t s);
+
 // Complete Algorithm-2 update of the vectors [item_begin, item_end), one workgroup each.
 hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,
                           const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);

@@ -882,6 +882,32 @@ CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, 3)
 CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, 3)
 CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, 3)
 
+// ---------------------------------------------------------------- placement probe
+
+// Reads every theta and M entry of the matrix tiles and writes the same bits back, in
+// sweep 3's tile order: the memory traffic of sweep 3 without its arithmetic, contents
+// unchanged.  Used to find out how well the caller's placement of theta and of the state
+// blob suits the memory system before any state exists (see came_probe_placement).
+__global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTables tb, int32_t item_begin)
+{
+    const WorkItem it = tb.items[item_begin + blockIdx.x];
+    const TensorMeta& tm = tb.metas[it.tensor];
+    if (!(tm.flags & kFlagAligned)) return;
+    const TileGeom t = tile_geom(tm, it);
+    if (t.ncol == 0) return;
+    float* theta = static_cast<float*>(tb.theta[it.tensor]);
+    float* M = tb.state + tm.off_M;
+    for (int i = t.wave; i < t.nrows; i += kWaves) {
+        const int64_t idx = (t.row0 + i) * tm.m + t.col;
+        f32x4* pm = reinterpret_cast<f32x4*>(M + idx);
+        f32x4* pt = reinterpret_cast<f32x4*>(theta + idx);
+        f32x4 m0 = pm[0], m1 = pm[1], t0 = pt[0], t1 = pt[1];
+        // opaque to the optimiser, so that the stores of just-loaded values are kept
+        asm volatile("" : "+v"(m0), "+v"(m1), "+v"(t0), "+v"(t1));
+        pm[0] = m0; pm[1] = m1; pt[0] = t0; pt[1] = t1;
+    }
+}
+
 // ---------------------------------------------------------------- fill
 
 __global__ __launch_bounds__(kWorkgroup) void fill_zero_kernel(f32x4* p4, size_t n4, float* tail, size_t ntail)
@@ -910,6 +936,13 @@ hipError_t launch_fill_zero(float* p, size_t count, hipStream_t s)
 hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s)
 {
     return launch_fill_zero(static_cast<float*>(p), bytes / sizeof(float), s);
+}
+
+hipError_t launch_placement_probe(const DeviceTables& t, int32_t item_begin, int32_t item_end, hipStream_t s)
+{
+    if (item_end <= item_begin) return hipSuccess;
+    placement_probe_kernel<<<dim3(item_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin);
+    return hipGetLastError();
 }
 
 hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,

@@ -227,3 +227,33 @@ def test_pointer_table_follows_new_addresses():
     w = W.Workload("ptrs", [(64, 512), (512,)], W.GRAD_F32, seed=12, steps=6, grad_kind="normal",
                    scale_range=(1e-2, 1e-1))
     _run(w, 6, TOL_100, check_every=1)
+
+
+def test_placement_probe_changes_nothing():
+    """came_probe_placement rewrites theta and M with their own bits: after some steps,
+    probing must leave every parameter and every state array bit-identical, report a
+    positive rate, and the following steps must match a run that never probed."""
+    w = W.Workload("probe", [(300, 1024), (1024,), (64, 520), (33, 16)], W.GRAD_BF16, seed=31, steps=4,
+                   grad_kind="normal", scale_range=(1e-3, 1e-1))
+    runs = []
+    for probe in (False, True):
+        gen = W.Generator(w, device="cuda:0")
+        th = [gen.theta0(i) for i in range(4)]
+        opt = P.CameStep(w.shapes, [w.grad_dtype] * 4, tile_rows=32, place_against=th if probe else None,
+                         placement_spacer_bytes=1 << 20)
+        for t in range(1, 5):
+            opt.step(th, [gen.grad(i, t) for i in range(4)], P.CameHyper(), 1e-3, t)
+            if probe and t == 2:
+                torch.cuda.synchronize()
+                before = [x.clone() for x in th] + [opt.state_view(0)[k].clone() for k in "MrcRC"]
+                assert opt.probe_placement(th, repeats=3) > 0
+                after = th + [opt.state_view(0)[k] for k in "MrcRC"]
+                for a, b in zip(before, after):
+                    assert torch.equal(a, b)
+        torch.cuda.synchronize()
+        runs.append([x.clone() for x in th] + [opt.state_view(i)["M"].clone() for i in range(4)])
+        if probe:
+            assert len(opt.placement_log) >= 1 and all(g > 0 for _, g in opt.placement_log)
+        opt.close()
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
