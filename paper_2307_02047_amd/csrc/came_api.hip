@@ -262,6 +262,8 @@ int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev
     for (const Group& g : p.groups) {
         hipError_t e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
         if (e != hipSuccess) return hip_fail(ctx, e);
+        e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
+        if (e != hipSuccess) return hip_fail(ctx, e);
         if (g.fin_end == g.fin_begin) continue;  // vectors only
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;

@@ -52,6 +52,10 @@ hipError_t launch_placement_probe(const DeviceTables& t, int32_t item_begin, int
 // Complete Algorithm-2 update of the vectors [item_begin, item_end), one workgroup each.
 hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,
                           const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);
+// Complete update of the long-vector chunks [item_begin, item_end): two launches (second
+// moment and chunk sums of u^2, then everything else).
+hipError_t launch_long_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,
+                               const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);
 // Sweep 1: row/column sums of g^2.
 hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
                          int32_t item_end, hipStream_t s);

@@ -298,6 +298,64 @@ __device__ void vector_update(const TensorMeta& tm, const void* g, float* theta,
     }
 }
 
+// Long vectors, pass 1 over chunk `chunk`: v_t and this chunk's sum of u^2.
+template <bool BF16>
+__device__ void vector_pass1(const TensorMeta& tm, int chunk, const void* g, float* state,
+                             const SweepHyper& h, char* scratch, double* lds4)
+{
+    float* v = state + tm.off_r;
+    const int64_t lo = static_cast<int64_t>(chunk) * tm.tile_rows;
+    const int64_t hi = lo + tm.tile_rows < tm.n ? lo + tm.tile_rows : tm.n;
+    double acc = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kWorkgroup) {
+        const float gi = load_grad1<BF16>(g, i);
+        const float vi = h.beta2 * v[i] + h.one_minus_beta2 * (gi * gi + h.eps1);
+        v[i] = vi;
+        const float u = gi * rsqrtf(vi);
+        acc += static_cast<double>(u) * static_cast<double>(u);
+    }
+    const double P = block_sum(acc, lds4);
+    if (threadIdx.x == 0) reinterpret_cast<double*>(scratch + tm.off_tileP)[chunk] = P;
+}
+
+// Long vectors, pass 2: kappa from the chunk sums (every workgroup, same order, same bits),
+// then momentum, confidence and parameter of this chunk.
+template <bool BF16>
+__device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, float* theta, float* state,
+                             const SweepHyper& h, const FinalizeHyper& fh, TensorScalars* sc,
+                             const char* scratch, double* lds4)
+{
+    float* M = state + tm.off_M;
+    const float* v = state + tm.off_r;
+    float* s = state + tm.off_R;
+    const double* part = reinterpret_cast<const double*>(scratch + tm.off_tileP);
+    double p = 0.0;
+    for (int k = threadIdx.x; k < tm.ntiles; k += kWorkgroup) p += part[k];
+    const double P = block_sum(p, lds4);
+    const double rms = sqrt(P / static_cast<double>(tm.n));
+    const float kappa = static_cast<float>(1.0 / fmax(1.0, rms / fh.clip_d));
+    if (chunk == 0 && threadIdx.x == 0) {
+        sc->kappa = kappa;
+        sc->rms_u = static_cast<float>(rms);
+    }
+    const int64_t lo = static_cast<int64_t>(chunk) * tm.tile_rows;
+    const int64_t hi = lo + tm.tile_rows < tm.n ? lo + tm.tile_rows : tm.n;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kWorkgroup) {
+        const float gi = load_grad1<BF16>(g, i);
+        const float uh = kappa * (gi * rsqrtf(v[i]));
+        const float Mi = fmaf(h.beta1, M[i], h.one_minus_beta1 * uh);
+        M[i] = Mi;
+        if (h.algo == CAME_ALGO_CAME) {
+            const float dU = uh - Mi;
+            const float si = h.beta3 * s[i] + h.one_minus_beta3 * (dU * dU + h.eps2);
+            s[i] = si;
+            theta[i] = theta[i] - h.lr * Mi * rsqrtf(si);
+        } else {
+            theta[i] = theta[i] - h.lr * Mi;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- row scheduling
 
 // Rows of a tile are dealt to the 4 waves round-robin: wave w owns rows w, w+4, ...
@@ -448,6 +506,24 @@ __global__ __launch_bounds__(kWorkgroup) void vector_kernel(DeviceTables tb, int
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
     if (tm.flags & kFlagBf16Grad) vector_update<true>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
     else                          vector_update<false>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
+}
+
+__global__ __launch_bounds__(kWorkgroup) void long_vector_kernel(DeviceTables tb, int32_t item_begin, int32_t pass,
+                                                                 SweepHyper h, FinalizeHyper fh)
+{
+    __shared__ double lds4[4];
+    const WorkItem it = tb.items[item_begin + blockIdx.x];
+    const TensorMeta& tm = tb.metas[it.tensor];
+    const void* g = tb.grad[it.tensor];
+    float* theta = static_cast<float*>(tb.theta[it.tensor]);
+    const bool bf16 = tm.flags & kFlagBf16Grad;
+    if (pass == 1) {
+        if (bf16) vector_pass1<true>(tm, it.rb, g, tb.state, h, tb.scratch, lds4);
+        else      vector_pass1<false>(tm, it.rb, g, tb.state, h, tb.scratch, lds4);
+    } else {
+        if (bf16) vector_pass2<true>(tm, it.rb, g, theta, tb.state, h, fh, tb.scalars + it.tensor, tb.scratch, lds4);
+        else      vector_pass2<false>(tm, it.rb, g, theta, tb.state, h, fh, tb.scalars + it.tensor, tb.scratch, lds4);
+    }
 }
 
 // ---------------------------------------------------------------- finalize 1
@@ -950,6 +1026,18 @@ hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t ite
 {
     if (item_end <= item_begin) return hipSuccess;
     vector_kernel<<<dim3(item_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin, h, fh);
+    return hipGetLastError();
+}
+
+hipError_t launch_long_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,
+                               const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s)
+{
+    if (item_end <= item_begin) return hipSuccess;
+    const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    long_vector_kernel<<<grid, block, 0, s>>>(t, item_begin, 1, h, fh);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    long_vector_kernel<<<grid, block, 0, s>>>(t, item_begin, 2, h, fh);
     return hipGetLastError();
 }
 

@@ -70,6 +70,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         if (d.ndim == 1 && d.cols != 1) return CAME_EINVAL;
         if (d.grad_dtype != CAME_GRAD_F32 && d.grad_dtype != CAME_GRAD_BF16) return CAME_EINVAL;
         if (d.rows > (int64_t(1) << 40) || d.cols > (int64_t(1) << 40)) return CAME_EINVAL;
+        if (d.ndim == 1 && d.rows > (int64_t(1) << 38)) return CAME_EINVAL;  // chunk size must fit int32
         if (d.rows * d.cols > (int64_t(1) << 46)) return CAME_EINVAL;
     }
 
@@ -159,8 +160,20 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         }
         g.vec_begin = static_cast<int32_t>(p.items.size());
         for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t)
-            if (p.metas[t].flags & kFlagVector) p.items.push_back(WorkItem{t, 0, 0, 1});
+            if ((p.metas[t].flags & kFlagVector) && p.metas[t].n <= kFusedVectorMax)
+                p.items.push_back(WorkItem{t, 0, 0, 1});
         g.vec_end = static_cast<int32_t>(p.items.size());
+        g.lvec_begin = g.vec_end;
+        for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
+            TensorMeta& tm = p.metas[t];
+            if (!(tm.flags & kFlagVector) || tm.n <= kFusedVectorMax) continue;
+            int64_t chunk = std::max<int64_t>(kFusedVectorMax, ceil_div(tm.n, kMaxVectorChunks));
+            chunk = round_up(chunk, kWorkgroup);
+            tm.tile_rows = static_cast<int32_t>(chunk);
+            tm.ntiles = static_cast<int32_t>(ceil_div(tm.n, chunk));
+            for (int32_t k = 0; k < tm.ntiles; ++k) p.items.push_back(WorkItem{t, k, 0, 2});
+        }
+        g.lvec_end = static_cast<int32_t>(p.items.size());
     }
 
     // ---- scratch blob
@@ -174,7 +187,13 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     p.off_partials = s;
     for (int32_t t = 0; t < count; ++t) {
         TensorMeta& tm = p.metas[t];
-        if (tm.flags & kFlagVector) continue;
+        if (tm.flags & kFlagVector) {
+            if (tm.ntiles > 0) {  // long vector: one double per chunk
+                tm.off_tileP = static_cast<int64_t>(s);
+                s = round_up_sz(s + sizeof(double) * tm.ntiles, kAlignBytes);
+            }
+            continue;
+        }
         // sized for sweep 2 (three doubles per entry); sweep 1 reuses the front of each region
         tm.off_rowpart = static_cast<int64_t>(s);
         s = round_up_sz(s + sizeof(double) * 3 * static_cast<size_t>(tm.n) * tm.CB, kAlignBytes);

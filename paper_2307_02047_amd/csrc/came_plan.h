@@ -48,8 +48,15 @@ static_assert(sizeof(TensorMeta) == 120, "TensorMeta layout");
 struct WorkItem {
     int32_t tensor;
     int32_t rb, cb;  // row block, column block (matrix tiles)
-    int32_t kind;    // 0 = matrix tile, 1 = whole vector
+    int32_t kind;    // 0 = matrix tile, 1 = whole vector, 2 = chunk `rb` of a long vector
 };
+
+// Vectors up to this length are updated by one workgroup in one kernel.  Longer ones are cut
+// into at most kMaxVectorChunks chunks (TensorMeta.tile_rows = elements per chunk,
+// TensorMeta.ntiles = number of chunks) and updated in two passes with the per-chunk sums
+// of u^2 in between (TensorMeta.off_tileP).
+constexpr int64_t kFusedVectorMax = 16384;
+constexpr int64_t kMaxVectorChunks = 1024;
 
 // One workgroup of a finalize launch: 256 rows or 256 columns of one matrix.
 struct FinalizeItem {
@@ -82,7 +89,8 @@ inline int variant_of(int32_t flags)
 struct Group {
     int32_t tensor_begin, tensor_end;
     int32_t var_begin[kVariants], var_end[kVariants];  // matrix tiles of each variant
-    int32_t vec_begin, vec_end;                        // whole-vector items
+    int32_t vec_begin, vec_end;                        // whole-vector items (one workgroup each)
+    int32_t lvec_begin, lvec_end;                      // chunks of long vectors (two passes)
     int32_t fin_begin, fin_end;
 };
 

@@ -126,6 +126,15 @@ def test_adafactor_and_came_share_momentum_and_second_moment():
         assert np.max(np.abs(a - b) / (np.abs(b) + scale)) < 1e-6
 
 
+@pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["f32", "bf16"])
+def test_long_vectors_take_the_two_pass_path(dtype):
+    """1-D parameters longer than one workgroup's share are cut into chunks and updated in two
+    passes; lengths straddle the switch-over (16384) and a chunk boundary."""
+    shapes = [(16384,), (16385,), (50257,), (300001,), (64, 512), (5,)]
+    w = W.Workload("long-vectors", shapes, dtype, seed=61, steps=4, grad_kind="normal", scale_range=(1e-4, 1e-1))
+    _run(w, 4, TOL_100, check_every=1)
+
+
 def test_transposed_matrix_swaps_row_and_column_statistics():
     """Algorithm 2 is symmetric in rows and columns: g^T, theta^T give theta^T, M^T,
     r <-> c, R <-> C.  On the GPU the row reduction (wave shuffles) and the column
@@ -257,3 +266,94 @@ def test_placement_probe_changes_nothing():
         opt.close()
     for a, b in zip(*runs):
         assert torch.equal(a, b)
+
+
+def test_hip_graph_replay_matches_eager():
+    """came_step only enqueues kernels (and no memset), so a step with unchanged tensor
+    addresses can be captured into a HIP graph.  Every replay must give exactly what the
+    eager call gives, with eager work and synchronisations between the replays."""
+    w = W.Workload("graph", [(256, 512), (512,), (100, 1032), (77,)], W.GRAD_F32, seed=41, steps=6,
+                   grad_kind="normal", scale_range=(1e-3, 1e-1))
+    h, lr = P.CameHyper(), 1e-3
+    gen = W.Generator(w, device="cuda:0")
+    n = len(w.shapes)
+
+    def fresh():
+        th = [gen.theta0(i) for i in range(n)]
+        gbuf = [torch.empty_like(gen.grad(i, 1)) for i in range(n)]  # fixed addresses, refilled per step
+        return th, gbuf, P.CameStep(w.shapes, [w.grad_dtype] * n, tile_rows=32)
+
+    # eager reference
+    th_e, g_e, opt_e = fresh()
+    for t in range(1, 7):
+        for i in range(n):
+            g_e[i].copy_(gen.grad(i, t))
+        opt_e.step(th_e, g_e, h, lr, t)
+    torch.cuda.synchronize()
+
+    # graph: one eager step first (uploads the pointer table), then capture and replay
+    th_g, g_g, opt_g = fresh()
+    for i in range(n):
+        g_g[i].copy_(gen.grad(i, 1))
+    opt_g.step(th_g, g_g, h, lr, 1)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for i in range(n):
+            g_g[i].copy_(gen.grad(i, 2))
+        with torch.cuda.graph(graph, stream=side):
+            opt_g.step(th_g, g_g, h, lr, 2)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    # capture does not execute: step 2 happens at the first replay
+    for t in range(2, 7):
+        for i in range(n):
+            g_g[i].copy_(gen.grad(i, t))
+        graph.replay()
+        torch.cuda.synchronize()
+        _ = (th_g[0] * 2).sum().item()  # unrelated eager work between replays
+    for a, b in zip(th_e, th_g):
+        assert torch.equal(a, b)
+    for i in range(n):
+        for k in "MrcRC":
+            if opt_e.state_view(i)[k] is not None:
+                assert torch.equal(opt_e.state_view(i)[k], opt_g.state_view(i)[k])
+    opt_e.close(); opt_g.close()
+
+
+def test_step_rejects_bad_arguments_on_device():
+    """Every invalid came_step argument is an error code, nothing is enqueued, state unchanged."""
+    import ctypes
+    w = W.Workload("bad", [(64, 512), (512,)], W.GRAD_F32, seed=51, steps=1, grad_kind="normal", scale_range=None)
+    gen = W.Generator(w, device="cuda:0")
+    th = [gen.theta0(i) for i in range(2)]
+    g = [gen.grad(i, 1) for i in range(2)]
+    opt = P.CameStep(w.shapes, [0, 0])
+    opt.step(th, g, P.CameHyper(), 1e-3, 1)
+    torch.cuda.synchronize()
+    snap = [x.clone() for x in th] + [opt.state_view(0)[k].clone() for k in "MrcRC"]
+    bad_hypers = [dict(beta1=1.0), dict(beta2=-0.1), dict(beta3=1.5), dict(eps1=-1e-3), dict(eps2=float("nan")),
+                  dict(clip_d=0.0), dict(clip_d=float("inf"))]
+    for kw in bad_hypers:
+        with pytest.raises(P.CameError) as e:
+            opt.step(th, g, P.CameHyper(**kw), 1e-3, 2)
+        assert e.value.status == -1, kw
+    for lr, step in [(float("nan"), 2), (float("inf"), 2), (1e-3, 0), (1e-3, -5)]:
+        with pytest.raises(P.CameError) as e:
+            opt.step(th, g, P.CameHyper(), lr, step)
+        assert e.value.status == -1
+    with pytest.raises(P.CameError) as e:  # misaligned gradient pointer
+        opt.step(th, [g[0].view(-1)[1:65 * 512 - 511].view(-1)[: 64 * 512 - 512], g[1]], P.CameHyper(), 1e-3, 2)
+    assert e.value.status == -3
+    with pytest.raises(P.CameError) as e:  # theta and grad are the same buffer
+        opt.step(th, [th[0], g[1]], P.CameHyper(), 1e-3, 2)
+    assert e.value.status == -1
+    torch.cuda.synchronize()
+    for a, b in zip(snap, th + [opt.state_view(0)[k] for k in "MrcRC"]):
+        assert torch.equal(a, b)
+    opt.step(th, g, P.CameHyper(), 1e-3, 2)  # still usable afterwards
+    torch.cuda.synchronize()
+    assert all(torch.isfinite(x).all() for x in th)
+    opt.close()

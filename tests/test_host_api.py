@@ -44,12 +44,20 @@ def test_plan_of_the_named_workloads(make, params, mats, vecs):
     q = P.plan_query(w.shapes, [w.grad_dtype] * len(w.shapes))
     assert (q["elements"], q["matrices"], q["vectors"]) == (params, mats, vecs)
     tr, tc = q["tile_rows"], q["tile_cols"]
-    want = sum(-(-s[0] // tr) * -(-s[1] // tc) for s in w.shapes if len(s) == 2) + vecs
+    want = sum(-(-s[0] // tr) * -(-s[1] // tc) for s in w.shapes if len(s) == 2) + vecs  # all vectors are short
     assert q["sweep_items"] == want
     assert q["finalize_items"] == sum(-(-s[0] // 256) + -(-s[1] // 256) for s in w.shapes if len(s) == 2)
     sb, wb = P.state_size(w.shapes, [w.grad_dtype] * len(w.shapes))
     assert sb >= 4 * sum((s[0] * s[1] + 2 * (s[0] + s[1])) if len(s) == 2 else 3 * s[0] for s in w.shapes)
     assert wb < 0.25 * sb or wb < (1 << 20)  # scratch stays a fraction of the state
+
+
+def test_long_vectors_are_chunked():
+    """Up to 16384 entries: one work item; beyond: ceil(n / chunk) items with chunk a multiple of
+    256, at least 16384, and at most 1024 chunks."""
+    for n, items in [(16384, 1), (16385, 2), (50257, 4), (16384 * 1024, 1024), (16384 * 1024 + 1, 1009),
+                     (10 ** 9, 1024)]:
+        assert P.plan_query([(n,)], [0])["sweep_items"] == items, n
 
 
 def test_groups_split_the_list():
