@@ -19,12 +19,12 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Rows per tile when the caller does not choose: the largest multiple of 16 up
 // to 512 that still yields at least `want` tiles.  Measured on BERT-base-, GPT-2-medium-
-// and BERT-large-shaped lists: about six tiles per compute unit (256 CUs) is the optimum;
-// smaller tiles pay more per-tile prologue/epilogue and more column partials, larger ones
-// leave compute units idle in the last round of a launch.
+// and BERT-large-shaped lists: six to twelve tiles per compute unit (256 CUs) is the flat
+// optimum; smaller tiles pay more per-tile prologue/epilogue and more column partials,
+// larger ones leave compute units idle in the last round of a launch.
 int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count)
 {
-    const int64_t want = 256 * 6;
+    const int64_t want = 256 * 12;
     int32_t best = 16;
     for (int32_t tr = 512; tr >= 16; tr -= 16) {
         int64_t tiles = 0;

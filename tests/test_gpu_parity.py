@@ -357,3 +357,32 @@ def test_step_rejects_bad_arguments_on_device():
     torch.cuda.synchronize()
     assert all(torch.isfinite(x).all() for x in th)
     opt.close()
+
+
+def test_mixed_gradient_dtypes_in_one_list():
+    """A list may mix fp32 and bf16 gradients and aligned / unaligned widths: each kernel variant
+    gets its own launch.  Tensors are independent, so the result must equal, bit for bit, what
+    single-dtype lists give."""
+    shapes = [(128, 1024), (1024,), (96, 520), (40, 13), (300, 512), (77,)]
+    dtypes = [W.GRAD_BF16, W.GRAD_F32, W.GRAD_F32, W.GRAD_BF16, W.GRAD_F32, W.GRAD_BF16]
+    gens = {d: W.Generator(W.Workload("mixed", shapes, d, seed=71, steps=3, grad_kind="normal",
+                                      scale_range=(1e-3, 1e-1)), device="cuda:0") for d in (0, 1)}
+    h = P.CameHyper()
+
+    def run(idx):
+        th = [gens[dtypes[i]].theta0(i) for i in idx]
+        opt = P.CameStep([shapes[i] for i in idx], [dtypes[i] for i in idx], tile_rows=32)
+        for t in range(1, 4):
+            opt.step(th, [gens[dtypes[i]].grad(i, t) for i in idx], h, 1e-3, t)
+        torch.cuda.synchronize()
+        out = {i: [th[k].clone()] + [opt.state_view(k)[q].clone() for q in "MrcRC" if opt.state_view(k)[q] is not None]
+               for k, i in enumerate(idx)}
+        opt.close()
+        return out
+
+    mixed = run(list(range(6)))
+    for d in (0, 1):
+        single = run([i for i in range(6) if dtypes[i] == d])
+        for i, arrs in single.items():
+            for a, b in zip(arrs, mixed[i]):
+                assert torch.equal(a, b), (i, d)
