@@ -386,3 +386,22 @@ def test_mixed_gradient_dtypes_in_one_list():
         for i, arrs in single.items():
             for a, b in zip(arrs, mixed[i]):
                 assert torch.equal(a, b), (i, d)
+
+
+def test_constant_gradient_where_the_instability_sums_cancel():
+    """With the same gradient every step u^ approaches M, so U = (u^ - M)^2 shrinks like
+    beta1^(2t) and the three sums sweep 2 forms (kappa^2 sum u^2 - 2 kappa sum u M + sum M^2)
+    cancel to many digits.  The fp64 accumulation must keep R, C and theta within the bar."""
+    w = W.Workload("constant-grad", [(200, 520), (96, 1024), (333,)], W.GRAD_F32, seed=81, steps=100,
+                   grad_kind="normal", scale_range=(1e-3, 1e-1))
+    sbs = SideBySide(w, tile_rows=32)
+    fixed = {}
+    real_grad = sbs.gen.grad
+    sbs.gen.grad = lambda i, t: fixed.setdefault(i, real_grad(i, 1))
+    try:
+        for t in range(1, 101):
+            sbs.step()
+            if t in (1, 10, 30, 60, 100):
+                sbs.assert_within(TOL_1 if t == 1 else TOL_100, "constant gradient")
+    finally:
+        sbs.close()
