@@ -154,6 +154,19 @@ int came_init_state(came_ctx **out, const came_tensor_desc *descs, int32_t count
 int came_step(came_ctx *ctx, void *const *theta_dev, const void *const *grad_dev,
               const came_hyper *hyper, double lr, int64_t step, void *hip_stream);
 
+/*
+ * came_step that also leaves a bfloat16 copy of the updated parameters, for trainers that
+ * keep fp32 master weights and compute in bf16: the copy is written by the same sweep
+ * that updates theta (2 more bytes per parameter written instead of a separate 6-byte
+ * cast pass).  theta_bf16_dev: host array of `count` device pointers; entry i is NULL
+ * (no copy for tensor i) or a contiguous, 16-byte aligned buffer of rows*cols bfloat16
+ * that aliases nothing else.  The copy is theta_t rounded to nearest even, NaN kept NaN.
+ * Everything else as came_step.
+ */
+int came_step_bf16_copy(came_ctx *ctx, void *const *theta_dev, const void *const *grad_dev,
+                        void *const *theta_bf16_dev, const came_hyper *hyper, double lr,
+                        int64_t step, void *hip_stream);
+
 /* Device addresses of tensor i's state arrays (for checkpointing and tests). */
 int came_state_view_get(const came_ctx *ctx, int32_t i, came_state_view *view);
 

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_PKG, "libcame_hip.so")
 GRAD_F32, GRAD_BF16 = 0, 1
 ALGO_CAME, ALGO_ADAFACTOR = 0, 1
 
-EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_state_view_get",
+EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_step_bf16_copy", "came_state_view_get",
            "came_plan_query", "came_algorithmic_bytes_per_param", "came_probe_placement", "came_profile_enable",
            "came_profile_read", "came_last_hip_error",
            "came_destroy", "came_strerror")
@@ -82,6 +82,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.came_init_state.restype = ctypes.c_int
     lib.came_step.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(_Hyper), dbl, i64, vp]
     lib.came_step.restype = ctypes.c_int
+    lib.came_step_bf16_copy.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                        ctypes.POINTER(_Hyper), dbl, i64, vp]
+    lib.came_step_bf16_copy.restype = ctypes.c_int
     lib.came_state_view_get.argtypes = [vp, i32, ctypes.POINTER(_View)]
     lib.came_state_view_get.restype = ctypes.c_int
     lib.came_plan_query.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), ctypes.POINTER(i64)]
@@ -105,16 +108,29 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     return lib
 
 
+def matrix_view_of(shape: Sequence[int]) -> tuple:
+    """The (rows, cols) a parameter of this shape is factored as: itself for 2-D; for more
+    dimensions the leading ones are merged (the paper defines the method for matrices only;
+    a contiguous tensor of shape (a, b, ..., z) is the row-major matrix (a*b*..., z))."""
+    s = tuple(int(x) for x in shape)
+    if len(s) <= 2:
+        return s
+    rows = 1
+    for x in s[:-1]:
+        rows *= x
+    return (rows, s[-1])
+
+
 def _descs(shapes: Sequence[Sequence[int]], grad_dtypes: Sequence[int]):
     arr = (_Desc * len(shapes))()
     for i, (s, d) in enumerate(zip(shapes, grad_dtypes)):
-        s = tuple(int(x) for x in s)
+        s = matrix_view_of(s)
         if len(s) == 2:
             arr[i] = _Desc(s[0], s[1], 2, int(d))
         elif len(s) == 1:
             arr[i] = _Desc(s[0], 1, 1, int(d))
         else:
-            raise ValueError(f"tensor {i}: only 1-D and 2-D parameters are supported, got shape {s}")
+            raise ValueError(f"tensor {i}: a parameter needs at least one dimension, got shape {s}")
     return arr
 
 
@@ -249,7 +265,9 @@ class CameStep:
         _check(self.lib, st, "came_probe_placement", self._ctx)
         return float(out.value)
 
-    def step(self, thetas, grads, hyper: CameHyper, lr: float, step: int, stream=None) -> None:
+    def step(self, thetas, grads, hyper: CameHyper, lr: float, step: int, stream=None, bf16_copies=None) -> None:
+        """came_step, or came_step_bf16_copy when bf16_copies is given (a list with, per tensor,
+        a bfloat16 tensor of the parameter's shape or None)."""
         torch = self._torch
         n = len(self.shapes)
         assert len(thetas) == n and len(grads) == n
@@ -259,9 +277,22 @@ class CameStep:
         h = hyper._c()
         with torch.cuda.device(self.device):
             s = stream if stream is not None else torch.cuda.current_stream(self.device).cuda_stream
-            st = self.lib.came_step(self._ctx, self._theta_arr, self._grad_arr, ctypes.byref(h), float(lr),
-                                    int(step), s)
-        _check(self.lib, st, "came_step", self._ctx)
+            if bf16_copies is None:
+                st = self.lib.came_step(self._ctx, self._theta_arr, self._grad_arr, ctypes.byref(h), float(lr),
+                                        int(step), s)
+                what = "came_step"
+            else:
+                assert len(bf16_copies) == n
+                arr = (ctypes.c_void_p * n)()
+                for i, c in enumerate(bf16_copies):
+                    if c is not None:
+                        if c.dtype != torch.bfloat16 or tuple(c.shape) != self.shapes[i] or not c.is_contiguous():
+                            raise ValueError(f"tensor {i}: bf16 copy must be a contiguous bfloat16 tensor of shape {self.shapes[i]}")
+                        arr[i] = c.data_ptr()
+                st = self.lib.came_step_bf16_copy(self._ctx, self._theta_arr, self._grad_arr, arr, ctypes.byref(h),
+                                                  float(lr), int(step), s)
+                what = "came_step_bf16_copy"
+        _check(self.lib, st, what, self._ctx)
 
     def check_tensors(self, thetas, grads) -> None:
         """Host-side shape/dtype check of what step() will hand to the kernels."""
@@ -285,7 +316,8 @@ class CameStep:
         base = self.state.data_ptr()
         f = self.state.view(self._torch.float32)
         s = self.shapes[i]
-        n, m = (s[0], s[1]) if len(s) == 2 else (s[0], 1)
+        mv = matrix_view_of(s)
+        n, m = (mv[0], mv[1]) if len(mv) == 2 else (mv[0], 1)
 
         def sl(ptr, count, shape):
             if not ptr:

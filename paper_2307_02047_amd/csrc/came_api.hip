@@ -24,7 +24,7 @@ struct came_ctx {
     hipEvent_t slot_event[kPtrSlots] = {};
     bool slot_used[kPtrSlots] = {};
     int slot = -1;
-    std::vector<const void*> cached;  // theta[count] then grad[count] of the current slot
+    std::vector<const void*> cached;  // theta[count], grad[count], bf16 copy[count] of the current slot
     int last_hip = 0;
     int64_t last_step = 0;
     // phase timer
@@ -76,20 +76,25 @@ DeviceTables tables_for(const came_ctx* ctx, int slot)
     char* slot_base = ctx->scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot);
     t.theta = reinterpret_cast<void* const*>(slot_base);
     t.grad = reinterpret_cast<const void* const*>(slot_base + sizeof(void*) * p.descs.size());
+    t.theta16 = reinterpret_cast<void* const*>(slot_base + sizeof(void*) * 2 * p.descs.size());
     t.state = ctx->state;
     t.scratch = ctx->scratch;
     return t;
 }
 
 // Pointer table: re-uploaded only when an address changed since the last call.
-int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev, hipStream_t s)
+// theta16_dev may be null (no bf16 copies at all) or hold null entries.
+int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+                    void* const* theta16_dev, hipStream_t s)
 {
     const Plan& p = ctx->plan;
     const size_t count = p.descs.size();
-    bool changed = ctx->slot < 0 || ctx->cached.size() != 2 * count;
+    auto copy_of = [&](size_t t) -> const void* { return theta16_dev ? theta16_dev[t] : nullptr; };
+    bool changed = ctx->slot < 0 || ctx->cached.size() != kPtrArrays * count;
     if (!changed) {
         for (size_t t = 0; t < count && !changed; ++t)
-            changed = ctx->cached[t] != theta_dev[t] || ctx->cached[count + t] != grad_dev[t];
+            changed = ctx->cached[t] != theta_dev[t] || ctx->cached[count + t] != grad_dev[t] ||
+                      ctx->cached[2 * count + t] != copy_of(t);
     }
     if (changed) {
         const int slot = (ctx->slot + 1) % kPtrSlots;
@@ -97,22 +102,23 @@ int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* gr
             const hipError_t e = hipEventSynchronize(ctx->slot_event[slot]);
             if (e != hipSuccess) return hip_fail(ctx, e);
         }
-        ctx->cached.resize(2 * count);
+        ctx->cached.resize(kPtrArrays * count);
         for (size_t t = 0; t < count; ++t) {
             ctx->cached[t] = theta_dev[t];
             ctx->cached[count + t] = grad_dev[t];
+            ctx->cached[2 * count + t] = copy_of(t);
         }
+        const size_t bytes = sizeof(void*) * kPtrArrays * count;
         char* host_slot = ctx->pinned + p.ptr_slot_bytes * static_cast<size_t>(slot);
-        std::memcpy(host_slot, ctx->cached.data(), sizeof(void*) * 2 * count);
+        std::memcpy(host_slot, ctx->cached.data(), bytes);
         hipError_t e = hipMemcpyAsync(ctx->scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot),
-                                      host_slot, sizeof(void*) * 2 * count, hipMemcpyHostToDevice, s);
+                                      host_slot, bytes, hipMemcpyHostToDevice, s);
         if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
         e = hipEventRecord(ctx->slot_event[slot], s);
         if (e != hipSuccess) { ctx->slot = -1; return hip_fail(ctx, e); }
         ctx->slot_used[slot] = true;
         ctx->slot = slot;
     }
-
     return CAME_OK;
 }
 
@@ -218,8 +224,9 @@ int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count
     return CAME_OK;
 }
 
-int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
-              const came_hyper* hyper, double lr, int64_t step, void* hip_stream)
+static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+                     void* const* theta16_dev, const came_hyper* hyper, double lr, int64_t step,
+                     void* hip_stream)
 {
     if (!ctx || !theta_dev || !grad_dev) return CAME_EINVAL;
     int rc = validate_hyper(hyper, lr, step);
@@ -230,10 +237,14 @@ int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev
         if (!theta_dev[t] || !grad_dev[t]) return CAME_EINVAL;
         if (!aligned_to(theta_dev[t], 16) || !aligned_to(grad_dev[t], 16)) return CAME_EALIGN;
         if (theta_dev[t] == grad_dev[t]) return CAME_EINVAL;
+        if (theta16_dev && theta16_dev[t]) {
+            if (!aligned_to(theta16_dev[t], 16)) return CAME_EALIGN;
+            if (theta16_dev[t] == theta_dev[t] || theta16_dev[t] == grad_dev[t]) return CAME_EINVAL;
+        }
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-    rc = upload_pointers(ctx, theta_dev, grad_dev, s);
+    rc = upload_pointers(ctx, theta_dev, grad_dev, theta16_dev, s);
     if (rc != CAME_OK) return rc;
 
     SweepHyper sh{};
@@ -289,6 +300,20 @@ int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev
     return CAME_OK;
 }
 
+int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+              const came_hyper* hyper, double lr, int64_t step, void* hip_stream)
+{
+    return step_impl(ctx, theta_dev, grad_dev, nullptr, hyper, lr, step, hip_stream);
+}
+
+int came_step_bf16_copy(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+                        void* const* theta_bf16_dev, const came_hyper* hyper, double lr, int64_t step,
+                        void* hip_stream)
+{
+    if (!theta_bf16_dev) return CAME_EINVAL;
+    return step_impl(ctx, theta_dev, grad_dev, theta_bf16_dev, hyper, lr, step, hip_stream);
+}
+
 int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
 {
     if (!ctx || !view) return CAME_EINVAL;
@@ -316,7 +341,7 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // the probe reads no gradients: the pointer table's gradient half just repeats theta
     std::vector<const void*> fake(theta_dev, theta_dev + count);
-    int rc = upload_pointers(ctx, theta_dev, fake.data(), s);
+    int rc = upload_pointers(ctx, theta_dev, fake.data(), nullptr, s);
     if (rc != CAME_OK) return rc;
     ctx->cached.clear();  // force a fresh table at the next came_step
     const int used_slot = ctx->slot;

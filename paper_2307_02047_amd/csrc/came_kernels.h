@@ -35,6 +35,7 @@ struct DeviceTables {
     TensorScalars* scalars;
     void* const* theta;        // current pointer slot: theta[count]
     const void* const* grad;   //                       grad[count]
+    void* const* theta16;      //                       bf16 copy of theta[count]; null entries: no copy
     float* state;
     char* scratch;
 };

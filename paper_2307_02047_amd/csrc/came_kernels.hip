@@ -158,6 +158,36 @@ __device__ __forceinline__ void store_f32x8(float* base, int64_t idx, int ncol, 
     }
 }
 
+// binary32 -> bfloat16, round to nearest even; NaN stays NaN (quiet bit forced).
+__device__ __forceinline__ uint32_t bf16_bits(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : rounded;
+}
+
+// Stores 8 values as bfloat16 at element idx of a bfloat16 array (same alignment rules
+// as the binary32 stores: vector store when ALIGNED, element-wise with bounds otherwise).
+template <bool ALIGNED>
+__device__ __forceinline__ void store_bf16x8(void* base, int64_t idx, int ncol, const float (&x)[8])
+{
+    uint16_t* p = static_cast<uint16_t*>(base) + idx;
+    if constexpr (ALIGNED) {
+        if (ncol > 0) {
+            u32x4 v;
+            v.x = bf16_bits(x[0]) | (bf16_bits(x[1]) << 16);
+            v.y = bf16_bits(x[2]) | (bf16_bits(x[3]) << 16);
+            v.z = bf16_bits(x[4]) | (bf16_bits(x[5]) << 16);
+            v.w = bf16_bits(x[6]) | (bf16_bits(x[7]) << 16);
+            *reinterpret_cast<u32x4*>(p) = v;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < ncol) p[e] = static_cast<uint16_t>(bf16_bits(x[e]));
+    }
+}
+
 // ---------------------------------------------------------------- reductions
 
 // DPP controls (GFX9 encoding): quad_perm [1,0,3,2], quad_perm [2,3,0,1], mirror within
@@ -258,7 +288,7 @@ __device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkIt
 // Algorithm 2 on a 1-D parameter (n x 1 special case: v = r, s = R).  One
 // workgroup owns the whole vector; the RMS of Eq. 1 is a workgroup reduction.
 template <bool BF16>
-__device__ void vector_update(const TensorMeta& tm, const void* g, float* theta, float* state,
+__device__ void vector_update(const TensorMeta& tm, const void* g, float* theta, uint16_t* theta16, float* state,
                               const SweepHyper& h, const FinalizeHyper& fh, TensorScalars* sc,
                               double* lds4)
 {
@@ -287,14 +317,17 @@ __device__ void vector_update(const TensorMeta& tm, const void* g, float* theta,
         const float uh = kappa * (gi * rsqrtf(v[i]));
         const float Mi = fmaf(h.beta1, M[i], h.one_minus_beta1 * uh);
         M[i] = Mi;
+        float tn;
         if (h.algo == CAME_ALGO_CAME) {
             const float dU = uh - Mi;
             const float si = h.beta3 * s[i] + h.one_minus_beta3 * (dU * dU + h.eps2);
             s[i] = si;
-            theta[i] = theta[i] - h.lr * Mi * rsqrtf(si);
+            tn = theta[i] - h.lr * Mi * rsqrtf(si);
         } else {
-            theta[i] = theta[i] - h.lr * Mi;
+            tn = theta[i] - h.lr * Mi;
         }
+        theta[i] = tn;
+        if (theta16) theta16[i] = static_cast<uint16_t>(bf16_bits(tn));
     }
 }
 
@@ -321,7 +354,7 @@ __device__ void vector_pass1(const TensorMeta& tm, int chunk, const void* g, flo
 // Long vectors, pass 2: kappa from the chunk sums (every workgroup, same order, same bits),
 // then momentum, confidence and parameter of this chunk.
 template <bool BF16>
-__device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, float* theta, float* state,
+__device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, float* theta, uint16_t* theta16, float* state,
                              const SweepHyper& h, const FinalizeHyper& fh, TensorScalars* sc,
                              const char* scratch, double* lds4)
 {
@@ -345,14 +378,17 @@ __device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, flo
         const float uh = kappa * (gi * rsqrtf(v[i]));
         const float Mi = fmaf(h.beta1, M[i], h.one_minus_beta1 * uh);
         M[i] = Mi;
+        float tn;
         if (h.algo == CAME_ALGO_CAME) {
             const float dU = uh - Mi;
             const float si = h.beta3 * s[i] + h.one_minus_beta3 * (dU * dU + h.eps2);
             s[i] = si;
-            theta[i] = theta[i] - h.lr * Mi * rsqrtf(si);
+            tn = theta[i] - h.lr * Mi * rsqrtf(si);
         } else {
-            theta[i] = theta[i] - h.lr * Mi;
+            tn = theta[i] - h.lr * Mi;
         }
+        theta[i] = tn;
+        if (theta16) theta16[i] = static_cast<uint16_t>(bf16_bits(tn));
     }
 }
 
@@ -504,8 +540,9 @@ __global__ __launch_bounds__(kWorkgroup) void vector_kernel(DeviceTables tb, int
     const TensorMeta& tm = tb.metas[it.tensor];
     const void* g = tb.grad[it.tensor];
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
-    if (tm.flags & kFlagBf16Grad) vector_update<true>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
-    else                          vector_update<false>(tm, g, theta, tb.state, h, fh, tb.scalars + it.tensor, lds4);
+    uint16_t* theta16 = static_cast<uint16_t*>(tb.theta16[it.tensor]);
+    if (tm.flags & kFlagBf16Grad) vector_update<true>(tm, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, lds4);
+    else                          vector_update<false>(tm, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, lds4);
 }
 
 __global__ __launch_bounds__(kWorkgroup) void long_vector_kernel(DeviceTables tb, int32_t item_begin, int32_t pass,
@@ -521,8 +558,9 @@ __global__ __launch_bounds__(kWorkgroup) void long_vector_kernel(DeviceTables tb
         if (bf16) vector_pass1<true>(tm, it.rb, g, tb.state, h, tb.scratch, lds4);
         else      vector_pass1<false>(tm, it.rb, g, tb.state, h, tb.scratch, lds4);
     } else {
-        if (bf16) vector_pass2<true>(tm, it.rb, g, theta, tb.state, h, fh, tb.scalars + it.tensor, tb.scratch, lds4);
-        else      vector_pass2<false>(tm, it.rb, g, theta, tb.state, h, fh, tb.scalars + it.tensor, tb.scratch, lds4);
+        uint16_t* theta16 = static_cast<uint16_t*>(tb.theta16[it.tensor]);
+        if (bf16) vector_pass2<true>(tm, it.rb, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, tb.scratch, lds4);
+        else      vector_pass2<false>(tm, it.rb, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, tb.scratch, lds4);
     }
 }
 
@@ -826,10 +864,11 @@ constexpr int kRows3 = CAME_ROWS3;
 
 // u^ = kappa g / sqrt(v);  M_t = beta1 M_{t-1} + (1-beta1) u^;
 // theta_t = theta_{t-1} - eta M_t / sqrt(S_t)      (Algorithm 1: theta_t = theta_{t-1} - eta M_t)
-template <bool BF16, bool ALIGNED, bool FULL>
+// COPY16: also write theta_t as bfloat16 to theta16 (came_step_bf16_copy).
+template <bool BF16, bool ALIGNED, bool FULL, bool COPY16>
 __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
-                            float* theta, float* state, const char* scratch, const TensorScalars* sc,
-                            const SweepHyper& h, float* rowfac /* [2][tile_rows] */)
+                            float* theta, void* theta16, float* state, const char* scratch,
+                            const TensorScalars* sc, const SweepHyper& h, float* rowfac /* [2][tile_rows] */)
 {
     const int64_t m = tm.m;
     const int TR = tm.tile_rows;
@@ -908,9 +947,11 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         if constexpr (ALIGNED && FULL) {
             store_f32x8<true>(M, idx, kLaneCols, mn);
             store_f32x8<true>(theta, idx, kLaneCols, tn);
+            if constexpr (COPY16) store_bf16x8<true>(theta16, idx, kLaneCols, tn);
         } else {
             store_f32x8<ALIGNED>(M, idx, t.ncol, mn);
             store_f32x8<ALIGNED>(theta, idx, t.ncol, tn);
+            if constexpr (COPY16) store_bf16x8<ALIGNED>(theta16, idx, t.ncol, tn);
         }
     };
 
@@ -946,17 +987,21 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const TileGeom t = tile_geom(tm, it);                                                       \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
         float* theta = static_cast<float*>(tb.theta[it.tensor]);                                    \
-        if (!ALIGNED || full)                                                                       \
-            sweep3_tile<BF16, ALIGNED, true>(tm, it, t, tb.grad[it.tensor], theta, tb.state,        \
-                                             tb.scratch, tb.scalars + it.tensor, h, rowfac_f32);    \
-        else                                                                                        \
-            sweep3_tile<BF16, ALIGNED, false>(tm, it, t, tb.grad[it.tensor], theta, tb.state,       \
-                                              tb.scratch, tb.scalars + it.tensor, h, rowfac_f32);   \
+        void* theta16 = tb.theta16[it.tensor];                                                      \
+        const void* g = tb.grad[it.tensor];                                                         \
+        const TensorScalars* sc = tb.scalars + it.tensor;                                           \
+        if (!ALIGNED || full) {                                                                     \
+            if (theta16) sweep3_tile<BF16, ALIGNED, true, true>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, true, false>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+        } else {                                                                                    \
+            if (theta16) sweep3_tile<BF16, ALIGNED, false, true>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, false, false>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+        }                                                                                           \
     }
 CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, CAME_WAVES3)
 CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, 3)
-CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, 3)
-CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, 3)
+CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, 2)
+CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, 2)
 
 // ---------------------------------------------------------------- placement probe
 

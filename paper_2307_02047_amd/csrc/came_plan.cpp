@@ -182,7 +182,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     p.off_items = s;   s = round_up_sz(s + sizeof(WorkItem) * std::max<size_t>(p.items.size(), 1), kAlignBytes);
     p.off_fins = s;    s = round_up_sz(s + sizeof(FinalizeItem) * std::max<size_t>(p.fins.size(), 1), kAlignBytes);
     p.off_scalars = s; s = round_up_sz(s + sizeof(TensorScalars) * count, kAlignBytes);
-    p.ptr_slot_bytes = round_up_sz(sizeof(void*) * 2 * count, kAlignBytes);
+    p.ptr_slot_bytes = round_up_sz(sizeof(void*) * kPtrArrays * count, kAlignBytes);
     p.off_ptrs = s;    s += p.ptr_slot_bytes * kPtrSlots;
     p.off_partials = s;
     for (int32_t t = 0; t < count; ++t) {

@@ -107,12 +107,13 @@ struct Plan {
     size_t state_bytes = 0;
     // scratch blob sections (byte offsets)
     size_t off_metas = 0, off_items = 0, off_fins = 0, off_scalars = 0, off_ptrs = 0;
-    size_t ptr_slot_bytes = 0;  // one slot: theta[count] then grad[count]
+    size_t ptr_slot_bytes = 0;  // one slot: theta[count], grad[count], bf16 parameter copy[count] (entries may be null)
     size_t off_partials = 0;
     size_t scratch_bytes = 0;
 };
 
 constexpr int kPtrSlots = 4;
+constexpr int kPtrArrays = 3;
 
 // Validates descs/opts and fills `plan`.  Returns CAME_OK or CAME_EINVAL.
 int build_plan(const came_tensor_desc* descs, int32_t count, const came_options* opts, Plan* plan);

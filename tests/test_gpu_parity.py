@@ -405,3 +405,67 @@ def test_constant_gradient_where_the_instability_sums_cancel():
                 sbs.assert_within(TOL_1 if t == 1 else TOL_100, "constant gradient")
     finally:
         sbs.close()
+
+
+@pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["f32", "bf16"])
+def test_bf16_parameter_copy_is_the_rounded_parameter(dtype):
+    """came_step_bf16_copy: theta, M and all statistics are exactly what came_step gives, and the
+    copy is theta_t rounded to nearest even (what torch's .to(bfloat16) does), bit for bit --
+    matrices (aligned, ragged, unaligned widths), short and long vectors, and tensors whose
+    copy is switched off."""
+    shapes = [(256, 512), (512,), (300, 1032), (40, 13), (64, 2048), (20000,), (5, 520)]
+    w = W.Workload("copy", shapes, dtype, seed=91, steps=3, grad_kind="normal", scale_range=(1e-3, 1e-1))
+    n = len(shapes)
+    gen = W.Generator(w, device="cuda:0")
+    h = P.CameHyper()
+    th_a = [gen.theta0(i) for i in range(n)]
+    th_b = [gen.theta0(i) for i in range(n)]
+    a = P.CameStep(shapes, [dtype] * n, tile_rows=32)
+    b = P.CameStep(shapes, [dtype] * n, tile_rows=32)
+    copies = [torch.full(s, float("nan"), dtype=torch.bfloat16, device="cuda:0") for s in shapes]
+    skip = {3, 5}  # no copy wanted for these
+    arg = [None if i in skip else copies[i] for i in range(n)]
+    for t in range(1, 4):
+        g = [gen.grad(i, t) for i in range(n)]
+        a.step(th_a, g, h, 1e-2, t)
+        b.step(th_b, g, h, 1e-2, t, bf16_copies=arg)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert torch.equal(th_a[i], th_b[i])
+        for k in "MrcRC":
+            if a.state_view(i)[k] is not None:
+                assert torch.equal(a.state_view(i)[k], b.state_view(i)[k])
+        if i in skip:
+            assert torch.isnan(copies[i].float()).all()  # untouched
+        else:
+            assert torch.equal(copies[i].view(torch.int16), th_b[i].to(torch.bfloat16).view(torch.int16)), i
+    # special values go through the same rounding: NaN stays NaN, infinities and zeros keep their sign
+    th = [torch.tensor([[float("inf"), -float("inf"), 0.0, -0.0, 1.0, 3.0e38, 1e-40, -1.5]], device="cuda:0")]
+    g0 = [torch.zeros((1, 8), device="cuda:0")]
+    c = P.CameStep([(1, 8)], [0])
+    out = [torch.zeros((1, 8), dtype=torch.bfloat16, device="cuda:0")]
+    c.step(th, g0, h, 1e-3, 1, bf16_copies=out)  # zero gradient: theta unchanged
+    torch.cuda.synchronize()
+    assert torch.equal(out[0].view(torch.int16), th[0].to(torch.bfloat16).view(torch.int16))
+    a.close(); b.close(); c.close()
+
+
+def test_more_than_two_dimensions_are_merged_leading_dimensions():
+    """The binding hands a contiguous (a, b, c) parameter to the library as the (a*b, c) matrix
+    it is in memory: same bits as stepping the reshaped tensor."""
+    w = W.Workload("nd", [(6, 50, 520)], W.GRAD_F32, seed=95, steps=3, grad_kind="normal", scale_range=(1e-2, 1e-1))
+    gen = W.Generator(w, device="cuda:0")
+    th3, th2 = gen.theta0(0), gen.theta0(0).reshape(300, 520).clone()
+    a, b = P.CameStep([(6, 50, 520)], [0], tile_rows=32), P.CameStep([(300, 520)], [0], tile_rows=32)
+    for t in range(1, 4):
+        g = gen.grad(0, t)
+        a.check_tensors([th3], [g])
+        a.step([th3], [g], P.CameHyper(), 1e-3, t)
+        b.step([th2], [g.reshape(300, 520).clone()], P.CameHyper(), 1e-3, t)
+    torch.cuda.synchronize()
+    assert torch.equal(th3.reshape(300, 520), th2)
+    va, vb = a.state_view(0), b.state_view(0)
+    assert va["M"].shape == (6, 50, 520) and torch.equal(va["M"].reshape(300, 520), vb["M"])
+    for k in "rcRC":
+        assert torch.equal(va[k], vb[k])
+    a.close(); b.close()

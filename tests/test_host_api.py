@@ -60,6 +60,13 @@ def test_long_vectors_are_chunked():
         assert P.plan_query([(n,)], [0])["sweep_items"] == items, n
 
 
+def test_tensors_with_more_than_two_dimensions_merge_their_leading_dimensions():
+    assert B.matrix_view_of((6, 50, 520)) == (300, 520)
+    assert B.matrix_view_of((2, 3, 4, 5)) == (24, 5)
+    assert B.matrix_view_of((7, 9)) == (7, 9) and B.matrix_view_of((11,)) == (11,)
+    assert P.state_size([(6, 50, 520)], [0]) == P.state_size([(300, 520)], [0])
+
+
 def test_groups_split_the_list():
     shapes = [(256, 512), (512,), (100, 1024), (1024,), (512, 512)]
     assert P.plan_query(shapes, [0] * 5)["groups"] == 1
