@@ -65,6 +65,12 @@ def cpu_baseline(w, gen, hyper, lr, budget_s: float = 12.0):
         dt = time.perf_counter() - t0
         if dt >= budget_s or steps >= 50:
             break
+    # the same oracle on one thread: one step of one attention projection
+    one = next(k for k, s in enumerate(shapes) if len(s) == 2)
+    tl1 = O.TensorList([shapes[one]], [to64(gen.theta0(idx[one]))])
+    t2 = time.perf_counter()
+    tl1.step([grads[one]], oh, nthreads=1)
+    dt1 = time.perf_counter() - t2
     return {
         "value": n_params * steps / dt,
         "unit": "params/s",
@@ -73,6 +79,8 @@ def cpu_baseline(w, gen, hyper, lr, budget_s: float = 12.0):
         "sample": f"{steps} step(s) of tensors {idx[0]}..{idx[-1]} (two transformer layers, "
                   f"{len(idx)} tensors, {n_params} params), one tensor per thread, float64",
         "seconds": dt,
+        "single_thread": {"value": math.prod(shapes[one]) / dt1, "unit": "params/s", "cores": 1,
+                          "sample": f"1 step of tensor {idx[one]} {tuple(shapes[one])}", "seconds": dt1},
     }
 
 
@@ -138,18 +146,27 @@ def main() -> int:
         opt.step(theta, grad_sets[step_no % 2], hyper, lr, step_no)
     torch.cuda.synchronize()
 
+    # one event before each step and one after the last, on the stream the steps run on:
+    # per-step durations (median, min) beside the wall-clock mean
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     opt.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for k in range(args.steps):
         step_no += 1
+        marks[k].record()
         opt.step(theta, grad_sets[step_no % 2], hyper, lr, step_no)
+    marks[args.steps].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     opt.profile_enable(False)
     phases = opt.profile_read()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
+    step_ms = {"median": per_step[len(per_step) // 2] if len(per_step) % 2 else
+               0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2]),
+               "min": per_step[0], "max": per_step[-1]}
     n_params = w.n_params
     n_matrix_params = sum(s[0] * s[1] for s in w.shapes if len(s) == 2)
     value = n_params / (ms_per_step * 1e-3)
@@ -187,6 +204,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "step_ms": step_ms,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
