@@ -32,6 +32,8 @@
  *     came_oracle_vector_step writes that special case out; a test pins it to
  *     came_oracle_matrix_step on shape n x 1.
  *
+ *   - reduced-precision momentum (not in the paper): see came_oracle_round_bf16.
+ *
  * Pinned by tests/test_oracle_pins.py (closed forms, invariants, dense brute
  * force, a hand-checkable worked example, mutation checks).
  */
@@ -303,6 +305,39 @@ int adafactor_oracle_matrix_step(int64_t n, int64_t m, double *theta, const doub
     if (diag) { diag[0] = rms_u; diag[1] = rms_of(u, nm); }
     free(u);
     return 0;
+}
+
+/*
+ * Storage rounding of the reduced-precision-momentum variant (NOT in the paper, which
+ * does not say in what precision the states are kept): the momentum is held in
+ * bfloat16 between steps.  A step reads the stored value as m_{t-1}, forms m_t, U_t and
+ * theta_t exactly as Algorithm 2 prints them, and only then replaces m_t by the nearest
+ * bfloat16 for storage.  The GPU path takes that rounding decision on a binary32 m_t,
+ * so the value is first rounded to binary32 here as well.
+ *
+ * bfloat16 is binary32 cut to its upper 16 bits: 1 sign, 8 exponent, 7 fraction bits,
+ * i.e. 8 significant bits over binary32's exponent range; its subnormals are the
+ * multiples of 2^-133.  Rounding is to nearest, ties to the even significand.
+ */
+double came_oracle_round_bf16(double x)
+{
+    if (isnan(x) || isinf(x) || x == 0.0) return x;
+    const double f = (double)(float)x;           /* the binary32 the kernel would hold */
+    if (isinf(f) || f == 0.0) return f;
+    int e;
+    (void)frexp(f, &e);                          /* |f| = mant * 2^e with mant in [0.5, 1) */
+    int q = e - 8;                               /* 8 significant bits: spacing 2^(e-8) */
+    if (q < -133) q = -133;                      /* never finer than the subnormal spacing */
+    const double steps = nearbyint(ldexp(f, -q)); /* default rounding mode: ties to even */
+    const double y = ldexp(steps, q);
+    if (fabs(y) >= ldexp(1.0, 128)) return copysign(INFINITY, y);
+    return y;
+}
+
+/* came_oracle_round_bf16 applied to every element of x, in place. */
+void came_oracle_store_bf16(double *x, int64_t count)
+{
+    for (int64_t k = 0; k < count; ++k) x[k] = came_oracle_round_bf16(x[k]);
 }
 
 /*

@@ -80,6 +80,10 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.came_oracle_step_list.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i64),
                                           ctypes.POINTER(i32), pp, pp, pp, pp, pp, pp, pp, hp, i32]
     lib.came_oracle_step_list.restype = ctypes.c_int
+    lib.came_oracle_round_bf16.argtypes = [ctypes.c_double]
+    lib.came_oracle_round_bf16.restype = ctypes.c_double
+    lib.came_oracle_store_bf16.argtypes = [dp, i64]
+    lib.came_oracle_store_bf16.restype = None
     lib.came_oracle_max_threads.argtypes = []
     lib.came_oracle_max_threads.restype = i32
     if path == _LIB:
@@ -203,7 +207,10 @@ class TensorList:
     def state_elems(self) -> int:
         return sum(s.elems() for s in self.state)
 
-    def step(self, grads, h: Hyper, nthreads: int = 1, lib=None) -> None:
+    def step(self, grads, h: Hyper, nthreads: int = 1, lib=None, momentum_bf16: bool = False) -> None:
+        """One step of every tensor.  momentum_bf16: after the step (theta and all other
+        state already updated from the unrounded m_t) every momentum is replaced by its
+        nearest bfloat16, the value the next step reads as m_{t-1}."""
         lib = lib or load()
         T = len(self.shapes)
         grads = [np.ascontiguousarray(g, dtype=np.float64) for g in grads]
@@ -228,6 +235,19 @@ class TensorList:
                                        ctypes.byref(hc), nthreads)
         if rc != 0:
             raise RuntimeError(f"came_oracle_step_list failed: {rc}")
+        if momentum_bf16:
+            for st in self.state:
+                store_bf16(st.M, lib)
+
+
+def round_bf16(x: float, lib=None) -> float:
+    """Nearest bfloat16 (ties to even) of the binary32 nearest to x."""
+    return float((lib or load()).came_oracle_round_bf16(float(x)))
+
+
+def store_bf16(a: np.ndarray, lib=None) -> None:
+    """round_bf16 on every element of a float64 array, in place."""
+    (lib or load()).came_oracle_store_bf16(_p(a.reshape(-1)), a.size)
 
 
 def max_threads(lib=None) -> int:

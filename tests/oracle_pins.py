@@ -406,6 +406,93 @@ def pin_list_driver(lib):
                     assert np.array_equal(L.state[i].v, single_st[i].v)
 
 
+# --------------------------------------------------------------------------- bfloat16 momentum storage
+def _torch_bf16(x64):
+    """float64 -> binary32 -> bfloat16 -> float64 by torch's CPU conversion (a library
+    routine independent of the oracle)."""
+    import torch
+    return torch.from_numpy(np.asarray(x64, dtype=np.float64)).to(torch.float32).to(torch.bfloat16) \
+        .to(torch.float64).numpy()
+
+
+def pin_bf16_rounding_by_hand(lib):
+    """bfloat16 format: 8 significant bits, ties to the even significand, subnormal
+    spacing 2^-133, overflow to infinity at 2^128.  Cases worked out by hand."""
+    r = lambda x: O.round_bf16(x, lib)
+    assert r(1.0) == 1.0 and r(-2.5) == -2.5 and r(0.0) == 0.0
+    assert r(1.0 + 2.0 ** -8) == 1.0                       # tie: 1.0000000|1 -> even below
+    assert r(1.0 + 3.0 * 2.0 ** -8) == 1.0 + 2.0 ** -6     # tie: 1.0000001|1 -> even above
+    assert r(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7   # just above the tie
+    assert r(-(1.0 + 2.0 ** -8 - 2.0 ** -20)) == -1.0           # just below the tie
+    assert r(3.0 * 2.0 ** -10 + 2.0 ** -17) == 3.0 * 2.0 ** -10  # a quarter step: stays
+    assert r(0.5 * 2.0 ** -133) == 0.0                     # tie between 0 and the smallest subnormal
+    assert r(1.5 * 2.0 ** -133) == 2.0 ** -132             # tie between 1 and 2 steps -> even
+    assert r(0.75 * 2.0 ** -133) == 2.0 ** -133
+    assert r((2.0 - 2.0 ** -7) * 2.0 ** 127) == (2.0 - 2.0 ** -7) * 2.0 ** 127   # largest bfloat16
+    assert r((2.0 - 2.0 ** -8) * 2.0 ** 127) == np.inf     # tie between it and 2^128 -> even = 2^128 = inf
+    assert r(-3.4e38) == -np.inf
+    assert np.isnan(r(np.nan)) and r(np.inf) == np.inf
+    # a double that is not a binary32: goes through binary32 first.  1 + 2^-8 + 2^-40 rounds to
+    # the binary32 1 + 2^-8 (a tie for bfloat16 -> 1.0), although it lies above the tie itself.
+    assert r(1.0 + 2.0 ** -8 + 2.0 ** -40) == 1.0
+
+
+def pin_bf16_rounding_matches_library(lib):
+    """Same rounding as torch's float32 -> bfloat16 conversion on random bit patterns of
+    every exponent, on exact ties, on subnormals and around the overflow threshold."""
+    rng = _rng(31)
+    bits = rng.integers(0, 2 ** 32, size=200000, dtype=np.uint64).astype(np.uint32)
+    ties = (rng.integers(0, 2 ** 16, size=20000, dtype=np.uint64).astype(np.uint32) << np.uint32(16)) | np.uint32(0x8000)
+    near = ties + rng.integers(-1, 2, size=ties.size).astype(np.int64).astype(np.uint32)
+    sub = rng.integers(0, 2 ** 23, size=20000, dtype=np.uint64).astype(np.uint32)      # binary32 subnormals
+    top = np.uint32(0x7f7f0000) + rng.integers(0, 2 ** 16, size=2000, dtype=np.uint64).astype(np.uint32)
+    allbits = np.concatenate([bits, ties, near, sub, sub | np.uint32(0x80000000), top])
+    x32 = allbits.view(np.float32)
+    x = x32[np.isfinite(x32)].astype(np.float64)
+    got = x.copy()
+    O.store_bf16(got, lib)
+    want = _torch_bf16(x)
+    assert np.array_equal(got, want)
+    assert np.array_equal(np.signbit(got), np.signbit(want))
+    # doubles between binary32 values
+    y = rng.normal(size=50000) * np.exp(rng.uniform(-80, 80, size=50000))
+    got = y.copy()
+    O.store_bf16(got, lib)
+    assert np.array_equal(got, _torch_bf16(y))
+
+
+def pin_bf16_momentum_mode(lib):
+    """The stored momentum is rounded AFTER the step: theta, r, c, R, C of a step are those of
+    Algorithm 2 run from the stored m_{t-1}; only the m handed to the next step is rounded.
+    Checked against the plain list driver with torch doing the rounding between steps."""
+    rng = _rng(32)
+    shapes = [(5, 7), (9,), (3, 4)]
+    th0 = [rng.normal(size=s) * 0.1 for s in shapes]
+    h = O.Hyper(lr=1e-2)
+    A = O.TensorList(shapes, [t.copy() for t in th0])
+    B = O.TensorList(shapes, [t.copy() for t in th0])
+    for step in range(4):
+        grads = [rng.normal(size=s) for s in shapes]
+        A.step(grads, h, lib=lib, momentum_bf16=True)
+        B.step(grads, h, lib=lib)
+        for i, s in enumerate(shapes):
+            assert np.array_equal(A.theta[i], B.theta[i]), f"step {step}: theta must come from the unrounded m_t"
+            B.state[i].M[...] = _torch_bf16(B.state[i].M)
+            assert np.array_equal(A.state[i].M, B.state[i].M)
+            if len(s) == 2:
+                for k in "rcRC":
+                    assert np.array_equal(getattr(A.state[i], k), getattr(B.state[i], k))
+            else:
+                assert np.array_equal(A.state[i].v, B.state[i].v) and np.array_equal(A.state[i].s, B.state[i].s)
+    # and the rounding does change something (the mode is not a no-op)
+    C = O.TensorList(shapes, [t.copy() for t in th0])
+    rng2 = _rng(32)
+    [rng2.normal(size=s) for s in shapes]
+    g = [rng2.normal(size=s) for s in shapes]
+    C.step(g, h, lib=lib)
+    assert not np.array_equal(C.state[0].M, _torch_bf16(C.state[0].M))
+
+
 ALL_PINS = [
     pin_step1_rank1_reconstruction,
     pin_rms_clip,
@@ -422,4 +509,7 @@ ALL_PINS = [
     pin_adafactor_subset,
     pin_worked_example,
     pin_list_driver,
+    pin_bf16_rounding_by_hand,
+    pin_bf16_rounding_matches_library,
+    pin_bf16_momentum_mode,
 ]

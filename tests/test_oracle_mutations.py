@@ -67,6 +67,18 @@ MUTATIONS = [
      "v[i] = v[i] + (g[i] * g[i] + h->eps1);", 1),
     ("adafactor_applies_confidence",
      "theta[k] = theta[k] - h->lr * M[k];", "theta[k] = theta[k] - h->lr * M[k] / sqrt(fabs(M[k]) + 1.0);", 1),
+    ("bf16_truncates",
+     "nearbyint(ldexp(f, -q))", "trunc(ldexp(f, -q))", 1),
+    ("bf16_rounds_half_away",
+     "nearbyint(ldexp(f, -q))", "round(ldexp(f, -q))", 1),
+    ("bf16_keeps_nine_bits",
+     "int q = e - 8; ", "int q = e - 9; ", 1),
+    ("bf16_subnormals_too_fine",
+     "if (q < -133) q = -133;", "", 1),
+    ("bf16_never_overflows",
+     "if (fabs(y) >= ldexp(1.0, 128)) return copysign(INFINITY, y);", "", 1),
+    ("bf16_rounds_the_double_not_the_binary32",
+     "const double f = (double)(float)x; ", "const double f = x; ", 1),
     ("list_driver_skips_vectors",
      "e = came_oracle_vector_step(rows[t], theta[t], g[t], M[t], r[t], R[t], h, NULL);",
      "e = 0;", 1),
