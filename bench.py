@@ -92,10 +92,13 @@ def main() -> int:
     ap.add_argument("--workload", default="llama_7b")
     ap.add_argument("--tile-rows", type=int, default=0)
     ap.add_argument("--group-elements", type=int, default=0)
+    ap.add_argument("--momentum-dtype", choices=("f32", "bf16"), default="f32",
+                    help="storage type of the momentum M between steps (f32: the configuration the metric is "
+                         "quoted on; bf16: the reduced-precision-momentum variant, 6 bytes per parameter less)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0)
     ap.add_argument("--no-placement", action="store_true",
-                    help="allocate the state blob wherever the allocator puts it (default: probe up to 3 "
+                    help="allocate the state blob wherever the allocator puts it (default: probe several "
                          "addresses against the parameters and keep the fastest)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 4 GiB device-to-device copy a few times: the known-size kernel "
@@ -133,8 +136,11 @@ def main() -> int:
     theta = [gen.theta0(i) for i in range(n)]
     # two gradient sets, alternated step by step, so that no random numbers are drawn inside the timed region
     grad_sets = [[gen.grad(i, t) for i in range(n)] for t in (1, 2)]
+    mdt = P.MOMENTUM_BF16 if args.momentum_dtype == "bf16" else P.MOMENTUM_F32
+    mbytes = 2 if mdt == P.MOMENTUM_BF16 else 4
     opt = P.CameStep(w.shapes, [w.grad_dtype] * n, device=dev, tile_rows=args.tile_rows,
-                     group_elements=args.group_elements, place_against=None if args.no_placement else theta)
+                     group_elements=args.group_elements, momentum_dtype=mdt,
+                     place_against=None if args.no_placement else theta)
     opt.check_tensors(theta, grad_sets[0])
     plan = P.plan_query(w.shapes, [w.grad_dtype] * n, tile_rows=args.tile_rows,
                         group_elements=args.group_elements)
@@ -176,7 +182,8 @@ def main() -> int:
     s3_avg_ms = s3_ms / max(s3_launches, 1)
     # one sweep-3 launch covers every matrix element of a launch group
     units_per_launch = n_matrix_params * (args.steps / max(s3_launches, 1))
-    s3_bytes = P.algorithmic_bytes_per_param(gb, 3) * units_per_launch
+    step_bpp = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 0)
+    s3_bytes = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 3) * units_per_launch
     achieved = s3_bytes / (s3_avg_ms * 1e-3) / 1e9 if s3_avg_ms > 0 else 0.0
     roofline = {
         "bound": "hbm",
@@ -185,13 +192,14 @@ def main() -> int:
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS,
-        "traffic": read_traffic(os.path.join(ROOT, "profiles", f"sweep3_{args.workload}_traffic.txt")),
+        "traffic": read_traffic(os.path.join(ROOT, "profiles", f"sweep3_{args.workload}_traffic.txt"))
+        if mdt == P.MOMENTUM_F32 else None,
         "bytes_per_launch": s3_bytes,
         "avg_launch_ms": s3_avg_ms,
         "whole_step": {
-            "algorithmic_bytes_per_param": P.algorithmic_bytes_per_param(gb, 0),
-            "achieved_GBs": P.algorithmic_bytes_per_param(gb, 0) * n_params / (ms_per_step * 1e-3) / 1e9,
-            "frac": P.algorithmic_bytes_per_param(gb, 0) * n_params / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_param": step_bpp,
+            "achieved_GBs": step_bpp * n_params / (ms_per_step * 1e-3) / 1e9,
+            "frac": step_bpp * n_params / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },
         "phase_ms_per_step": {k: v[0] / args.steps for k, v in phases.items()},
     }
@@ -216,6 +224,7 @@ def main() -> int:
             "tensors": n,
             "grad_dtype": "bf16" if gb == 2 else "f32",
             "param_state_dtype": "f32",
+            "momentum_dtype": args.momentum_dtype,
             "tile_rows": plan["tile_rows"],
             "launch_groups": plan["groups"],
             "state_placement_probe_GBs": [round(g, 1) for _, g in opt.placement_log],

@@ -72,10 +72,21 @@ typedef enum {
                                instability/confidence lines, theta <- theta - eta M; R, C stay zero */
 } came_algo;
 
+typedef enum {
+    CAME_MOMENTUM_F32 = 0, /* M kept as binary32 (Algorithm 2 evaluated in binary32 throughout) */
+    CAME_MOMENTUM_BF16 = 1 /* M kept as bfloat16 BETWEEN steps: a step widens the stored M_{t-1}
+                              exactly, forms M_t, U_t and theta_t from it in binary32 as printed in
+                              Algorithm 2, and stores M_t rounded to nearest even.  The paper does
+                              not say in what precision states are kept; this halves M's bytes
+                              (state rows*cols*2 + ..., step traffic 14 + 3*grad_bytes per
+                              parameter instead of 20 + 3*grad_bytes) at the cost of a relative
+                              storage error of at most 2^-9 in M */
+} came_momentum_dtype;
+
 /* One parameter tensor.  ndim == 2: rows x cols matrix (factored statistics).
  * ndim == 1: vector of `rows` entries, cols must be 1 (unfactored statistics).
- * Parameters (theta) and all optimizer state are binary32; only the gradient
- * dtype varies. */
+ * Parameters (theta) and the factored statistics are binary32; the gradient dtype is
+ * per tensor, the momentum dtype per context (came_options). */
 typedef struct {
     int64_t rows;
     int64_t cols;
@@ -105,12 +116,14 @@ typedef struct {
                                 elements and the phases run group after group, so that a
                                 group's gradient and momentum can stay in the on-package cache
                                 between phases */
-    int32_t reserved[4];     /* must be zero */
+    int32_t momentum_dtype;  /* came_momentum_dtype, for every tensor of the context */
+    int32_t reserved[3];     /* must be zero */
 } came_options;
 
 /* Device addresses of one tensor's state inside the caller's state blob.
  * Matrix: m = M (rows*cols), r, R (rows), c, C (cols).
- * Vector: m = M, r = v, R = s (rows each); c = C = NULL.   All binary32. */
+ * Vector: m = M, r = v, R = s (rows each); c = C = NULL.   All binary32, except m under
+ * CAME_MOMENTUM_BF16: rows*cols bfloat16. */
 typedef struct {
     void *m, *r, *c, *R, *C;
 } came_state_view;
@@ -120,7 +133,8 @@ typedef struct came_ctx came_ctx;
 /*
  * Bytes the caller must provide for the optimizer state (Algorithm 2's M, r,
  * c, R, C for every tensor: rows*cols + 2(rows+cols) floats per matrix, 3*rows
- * per vector, each array padded to 256 B) and for the library's scratch
+ * per vector, each array padded to 256 B; M takes 2 bytes per entry instead of 4
+ * under CAME_MOMENTUM_BF16) and for the library's scratch
  * (tile/descriptor tables, per-tile partial sums, per-tensor scalars).
  * Host-only: touches no device.  descs: host, `count` entries.
  */
@@ -186,6 +200,15 @@ int came_plan_query(const came_tensor_desc *descs, int32_t count, const came_opt
  * which: 0 = whole step, 1/2/3 = that sweep alone.
  */
 double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which);
+
+/*
+ * The same count for any mode: momentum_bytes 4 or 2 (came_momentum_dtype), algo a
+ * came_algo (Algorithm 1's sweep 2 does not read M).  Sweep 1 reads g; sweep 2 reads g
+ * and M; sweep 3 reads g, M, theta and writes M, theta:
+ *   8 + 3*grad_bytes + 3*momentum_bytes   (Algorithm 1: ... + 2*momentum_bytes).
+ * Returns 0 for arguments out of range.
+ */
+double came_algorithmic_bytes(int32_t grad_bytes, int32_t momentum_bytes, int32_t algo, int32_t which);
 
 /*
  * Placement probe.  On MI355X the time of the one sweep that both reads and writes

@@ -15,9 +15,10 @@ _LIB_PATH = os.path.join(_PKG, "libcame_hip.so")
 
 GRAD_F32, GRAD_BF16 = 0, 1
 ALGO_CAME, ALGO_ADAFACTOR = 0, 1
+MOMENTUM_F32, MOMENTUM_BF16 = 0, 1
 
 EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_step_bf16_copy", "came_state_view_get",
-           "came_plan_query", "came_algorithmic_bytes_per_param", "came_probe_placement", "came_profile_enable",
+           "came_plan_query", "came_algorithmic_bytes_per_param", "came_algorithmic_bytes", "came_probe_placement", "came_profile_enable",
            "came_profile_read", "came_last_hip_error",
            "came_destroy", "came_strerror")
 
@@ -40,7 +41,8 @@ class _Hyper(ctypes.Structure):
 
 class _Options(ctypes.Structure):
     _fields_ = [("tile_rows", ctypes.c_int32), ("algo", ctypes.c_int32),
-                ("group_elements", ctypes.c_int64), ("reserved", ctypes.c_int32 * 4)]
+                ("group_elements", ctypes.c_int64), ("momentum_dtype", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 3)]
 
 
 class _View(ctypes.Structure):
@@ -91,6 +93,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.came_plan_query.restype = ctypes.c_int
     lib.came_algorithmic_bytes_per_param.argtypes = [i32, i32]
     lib.came_algorithmic_bytes_per_param.restype = dbl
+    lib.came_algorithmic_bytes.argtypes = [i32, i32, i32, i32]
+    lib.came_algorithmic_bytes.restype = dbl
     lib.came_probe_placement.argtypes = [vp, ctypes.POINTER(vp), vp, i32, ctypes.POINTER(dbl)]
     lib.came_probe_placement.restype = ctypes.c_int
     lib.came_profile_enable.argtypes = [vp, i32]
@@ -134,9 +138,11 @@ def _descs(shapes: Sequence[Sequence[int]], grad_dtypes: Sequence[int]):
     return arr
 
 
-def _options(tile_rows: int = 0, algo: int = ALGO_CAME, group_elements: int = 0):
+def _options(tile_rows: int = 0, algo: int = ALGO_CAME, group_elements: int = 0,
+             momentum_dtype: int = MOMENTUM_F32):
     o = _Options()
     o.tile_rows, o.algo, o.group_elements = int(tile_rows), int(algo), int(group_elements)
+    o.momentum_dtype = int(momentum_dtype)
     return o
 
 
@@ -172,6 +178,10 @@ def algorithmic_bytes_per_param(grad_bytes: int, which: int = 0) -> float:
     return float(load_library().came_algorithmic_bytes_per_param(int(grad_bytes), int(which)))
 
 
+def algorithmic_bytes(grad_bytes: int, momentum_bytes: int = 4, algo: int = ALGO_CAME, which: int = 0) -> float:
+    return float(load_library().came_algorithmic_bytes(int(grad_bytes), int(momentum_bytes), int(algo), int(which)))
+
+
 class CameStep:
     """came_init_state / came_step / came_state_view_get / came_destroy for one tensor list.
 
@@ -180,8 +190,8 @@ class CameStep:
     """
 
     def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
-                 group_elements: int = 0, place_against=None, placement_candidates: int = 4,
-                 placement_spacer_bytes: int = 32 << 30, placement_accept_gbs: float = 5750.0):
+                 group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32, place_against=None, placement_candidates: int = 6,
+                 placement_spacer_bytes: int = 8 << 30, placement_accept_gbs: float = 5750.0):
         """place_against: the parameter tensors the context will be stepped with.  When given,
         the state blob is allocated at up to `placement_candidates` different addresses
         (separated by temporary spacer allocations), each is measured with
@@ -197,7 +207,8 @@ class CameStep:
         self.grad_dtypes = [int(d) for d in grad_dtypes]
         self.device = torch.device(device)
         self._d = _descs(self.shapes, self.grad_dtypes)
-        self._o = _options(tile_rows, algo, group_elements)
+        self._o = _options(tile_rows, algo, group_elements, momentum_dtype)
+        self.momentum_dtype = int(momentum_dtype)
         n = len(self.shapes)
         sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
         _check(self.lib, self.lib.came_state_size(self._d, n, ctypes.byref(self._o), ctypes.byref(sb),
@@ -210,29 +221,33 @@ class CameStep:
             self.state, self.scratch, self._ctx = self._create()
             return
         assert len(place_against) == n
-        best, spacers = None, []
+        # Every candidate and spacer stays allocated until the search ends, so that each new
+        # candidate really lies at a new place (a freed block would be handed out again).
+        tried, spacers, best = [], [], None
         for k in range(max(1, placement_candidates)):
             try:
                 cand = self._create()
             except (RuntimeError, CameError):
                 break  # out of memory for another candidate: keep what we have
+            tried.append(cand)
             self.state, self.scratch, self._ctx = cand
             gbs = self.probe_placement(place_against)
             self.placement_log.append((k, gbs))
             if best is None or gbs > best[0]:
-                if best is not None:
-                    self._destroy(best[1])
                 best = (gbs, cand)
-            else:
-                self._destroy(cand)
-            if gbs >= placement_accept_gbs or k + 1 >= placement_candidates:
+            if gbs >= placement_accept_gbs:
                 break
             try:
                 spacers.append(torch.empty(int(placement_spacer_bytes), dtype=torch.uint8, device=self.device))
             except RuntimeError:
                 break
+        if best is None:
+            raise CameError(-5, "no memory for the optimizer state")
+        for cand in tried:
+            if cand is not best[1]:
+                self._destroy(cand)
         self.state, self.scratch, self._ctx = best[1]
-        del spacers, cand
+        del spacers, tried, cand
         torch.cuda.empty_cache()  # hand the losing candidates and the spacers back to the driver
 
     def _create(self):
@@ -310,7 +325,8 @@ class CameStep:
                 raise ValueError(f"tensor {i}: tensors must live on {self.device}")
 
     def state_view(self, i: int) -> dict:
-        """came_state_view_get as float32 torch views into the state blob."""
+        """came_state_view_get as torch views into the state blob (float32; M is bfloat16
+        when the context keeps a bfloat16 momentum)."""
         v = _View()
         _check(self.lib, self.lib.came_state_view_get(self._ctx, int(i), ctypes.byref(v)), "came_state_view_get")
         base = self.state.data_ptr()
@@ -325,7 +341,13 @@ class CameStep:
             off = (ptr - base) // 4
             return f[off:off + count].view(shape)
 
-        return {"M": sl(v.m, n * m, s), "r": sl(v.r, n, (n,)), "c": sl(v.c, m, (m,)),
+        if self.momentum_dtype == MOMENTUM_BF16:
+            h = self.state.view(self._torch.bfloat16)
+            off = (v.m - base) // 2
+            M = h[off:off + n * m].view(s)
+        else:
+            M = sl(v.m, n * m, s)
+        return {"M": M, "r": sl(v.r, n, (n,)), "c": sl(v.c, m, (m,)),
                 "R": sl(v.R, n, (n,)), "C": sl(v.C, m, (m,))}
 
     PHASES = ("sweep1", "finalize1", "sweep2", "finalize2", "sweep3", "vectors")

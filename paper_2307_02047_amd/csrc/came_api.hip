@@ -169,6 +169,23 @@ double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which)
     }
 }
 
+double came_algorithmic_bytes(int32_t grad_bytes, int32_t momentum_bytes, int32_t algo, int32_t which)
+{
+    if ((grad_bytes != 2 && grad_bytes != 4) || (momentum_bytes != 2 && momentum_bytes != 4)) return 0.0;
+    if (algo != CAME_ALGO_CAME && algo != CAME_ALGO_ADAFACTOR) return 0.0;
+    const double g = static_cast<double>(grad_bytes), mb = static_cast<double>(momentum_bytes);
+    const double s1 = g;                                          // read g
+    const double s2 = g + (algo == CAME_ALGO_CAME ? mb : 0.0);    // read g (and M)
+    const double s3 = g + 2.0 * mb + 8.0;                         // read g, M, theta; write M, theta
+    switch (which) {
+        case 0: return s1 + s2 + s3;
+        case 1: return s1;
+        case 2: return s2;
+        case 3: return s3;
+        default: return 0.0;
+    }
+}
+
 int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count,
                     const came_options* opts, void* state_dev, size_t state_bytes,
                     void* scratch_dev, size_t scratch_bytes, void* hip_stream)
@@ -347,13 +364,16 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream
     const int used_slot = ctx->slot;
     double bytes = 0.0;
     for (const Group& g : p.groups)
-        for (int v = 0; v < 2; ++v)  // aligned variants only
+        for (int v = 0; v < kVariants; ++v) {
+            if (v & 2) continue;  // aligned variants only
             for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
                 const TensorMeta& tm = p.metas[p.items[k].tensor];
                 const int64_t rows = std::min<int64_t>(tm.tile_rows, tm.n - int64_t(p.items[k].rb) * tm.tile_rows);
                 const int64_t cols = std::min<int64_t>(kTileCols, tm.m - int64_t(p.items[k].cb) * kTileCols);
-                bytes += 16.0 * static_cast<double>(rows * cols);  // theta and M, read and written
+                // theta and M, read and written
+                bytes += ((tm.flags & kFlagBf16Momentum) ? 12.0 : 16.0) * static_cast<double>(rows * cols);
             }
+        }
     if (bytes == 0.0) return CAME_OK;
     const DeviceTables tb = tables_for(ctx, used_slot);
     hipEvent_t e0, e1;
@@ -363,7 +383,8 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream
     if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(ctx, e); }
     auto run_once = [&]() -> hipError_t {
         for (const Group& g : p.groups)
-            for (int v = 0; v < 2; ++v) {
+            for (int v = 0; v < kVariants; ++v) {
+                if (v & 2) continue;
                 const hipError_t le = launch_placement_probe(tb, g.var_begin[v], g.var_end[v], s);
                 if (le != hipSuccess) return le;
             }

@@ -1,9 +1,10 @@
 // gfx950 kernels of the CAME step (Algorithm 2 of the CAME paper).
 //
 // One step is six grouped launches over ALL tensors of a group (the sweeps once per
-// kernel variant present: gradient dtype x aligned/unaligned rows):
+// kernel variant present: gradient dtype x aligned/unaligned rows x momentum dtype):
 //
-//   vectors    g, state     -> complete update of the 1-D parameters (one workgroup each)
+//   vectors    g, state     -> complete update of the 1-D parameters (one workgroup each;
+//                              vectors too long for that: two passes over chunks)
 //   sweep 1    g            -> row/column partial sums of g^2          (r_t, c_t lines)
 //   finalize 1 partials     -> r_t, c_t, sqrt(1^T r_t)
 //   sweep 2    g, M_{t-1}   -> row/column partial sums of u^2, u M, M^2 with u = g / sqrt(v_t)
@@ -62,7 +63,8 @@ struct F32Raw { f32x4 a, b; };
 
 // ALIGNED: every row starts 16-byte aligned (m % 8 == 0) and ncol is 0 or 8: vector
 // accesses.  Otherwise element-wise accesses with per-column bounds.
-template <bool BF16, bool ALIGNED>
+// NT: non-temporal (streaming) loads, for data read once per sweep and never written.
+template <bool BF16, bool ALIGNED, bool NT = true>
 __device__ __forceinline__ GradRaw<BF16> load_grad_raw(const void* g, int64_t idx, int ncol)
 {
     GradRaw<BF16> r;
@@ -72,7 +74,10 @@ __device__ __forceinline__ GradRaw<BF16> load_grad_raw(const void* g, int64_t id
         if constexpr (ALIGNED) {
             // gradients are read once per sweep and never written: stream them (measured: sweep 2
             // 6 % faster; the same hint on the M / theta loads or on the stores is slower)
-            if (ncol > 0) r.v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+            if (ncol > 0) {
+                if constexpr (NT) r.v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+                else r.v = *reinterpret_cast<const u32x4*>(p);
+            }
         } else {
             uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -86,8 +91,13 @@ __device__ __forceinline__ GradRaw<BF16> load_grad_raw(const void* g, int64_t id
         const float* p = static_cast<const float*>(g) + idx;
         if constexpr (ALIGNED) {
             if (ncol > 0) {
-                r.a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-                r.b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + 1);
+                if constexpr (NT) {
+                    r.a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+                    r.b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + 1);
+                } else {
+                    r.a = reinterpret_cast<const f32x4*>(p)[0];
+                    r.b = reinterpret_cast<const f32x4*>(p)[1];
+                }
             }
         } else {
             float w[8];
@@ -186,6 +196,33 @@ __device__ __forceinline__ void store_bf16x8(void* base, int64_t idx, int ncol, 
         for (int e = 0; e < 8; ++e)
             if (e < ncol) p[e] = static_cast<uint16_t>(bf16_bits(x[e]));
     }
+}
+
+// The momentum as stored: binary32, or bfloat16 (MB16) widened exactly on load and rounded
+// to nearest even on store.  `M` is the tensor's momentum array inside the state blob; idx
+// counts elements.  Plain cached accesses: sweep 3 re-reads what sweep 2 read.
+template <bool MB16, bool ALIGNED>
+__device__ __forceinline__ GradRaw<MB16> load_mom_raw(const float* M, int64_t idx, int ncol)
+{
+    return load_grad_raw<MB16, ALIGNED, false>(M, idx, ncol);
+}
+
+template <bool MB16, bool ALIGNED>
+__device__ __forceinline__ void store_mom(float* M, int64_t idx, int ncol, const float (&x)[8])
+{
+    if constexpr (MB16) store_bf16x8<ALIGNED>(M, idx, ncol, x);
+    else store_f32x8<ALIGNED>(M, idx, ncol, x);
+}
+
+__device__ __forceinline__ float load_mom1(const float* M, int64_t i, bool mb16)
+{
+    return mb16 ? bits_to_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(M)[i]) << 16) : M[i];
+}
+
+__device__ __forceinline__ void store_mom1(float* M, int64_t i, bool mb16, float x)
+{
+    if (mb16) reinterpret_cast<uint16_t*>(M)[i] = static_cast<uint16_t>(bf16_bits(x));
+    else M[i] = x;
 }
 
 // ---------------------------------------------------------------- reductions
@@ -296,6 +333,7 @@ __device__ void vector_update(const TensorMeta& tm, const void* g, float* theta,
     float* v = state + tm.off_r;
     float* s = state + tm.off_R;
     const int64_t n = tm.n;
+    const bool mb16 = tm.flags & kFlagBf16Momentum;
     double acc = 0.0;
     for (int64_t i = threadIdx.x; i < n; i += kWorkgroup) {
         const float gi = load_grad1<BF16>(g, i);
@@ -315,8 +353,8 @@ __device__ void vector_update(const TensorMeta& tm, const void* g, float* theta,
     for (int64_t i = threadIdx.x; i < n; i += kWorkgroup) {
         const float gi = load_grad1<BF16>(g, i);
         const float uh = kappa * (gi * rsqrtf(v[i]));
-        const float Mi = fmaf(h.beta1, M[i], h.one_minus_beta1 * uh);
-        M[i] = Mi;
+        const float Mi = fmaf(h.beta1, load_mom1(M, i, mb16), h.one_minus_beta1 * uh);
+        store_mom1(M, i, mb16, Mi);
         float tn;
         if (h.algo == CAME_ALGO_CAME) {
             const float dU = uh - Mi;
@@ -361,6 +399,7 @@ __device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, flo
     float* M = state + tm.off_M;
     const float* v = state + tm.off_r;
     float* s = state + tm.off_R;
+    const bool mb16 = tm.flags & kFlagBf16Momentum;
     const double* part = reinterpret_cast<const double*>(scratch + tm.off_tileP);
     double p = 0.0;
     for (int k = threadIdx.x; k < tm.ntiles; k += kWorkgroup) p += part[k];
@@ -376,8 +415,8 @@ __device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, flo
     for (int64_t i = lo + threadIdx.x; i < hi; i += kWorkgroup) {
         const float gi = load_grad1<BF16>(g, i);
         const float uh = kappa * (gi * rsqrtf(v[i]));
-        const float Mi = fmaf(h.beta1, M[i], h.one_minus_beta1 * uh);
-        M[i] = Mi;
+        const float Mi = fmaf(h.beta1, load_mom1(M, i, mb16), h.one_minus_beta1 * uh);
+        store_mom1(M, i, mb16, Mi);
         float tn;
         if (h.algo == CAME_ALGO_CAME) {
             const float dU = uh - Mi;
@@ -614,7 +653,8 @@ constexpr int kRows2 = CAME_ROWS2;
 // CAME_STATS: Algorithm 2 needs all three statistics per row and column.  Algorithm 1
 // (no instability / confidence lines) needs only the total of u^2 for Eq. 1, so M is not
 // read at all and there are no column accumulators.
-template <bool BF16, bool ALIGNED, bool FULL, bool CAME_STATS>
+// MB16: M is stored as bfloat16.
+template <bool BF16, bool ALIGNED, bool FULL, bool CAME_STATS, bool MB16>
 __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
                             const float* state, char* scratch, TensorScalars* sc,
                             double* lds /* [4][512] */, double* lds4, double* rowbuf /* [3][tile_rows] */,
@@ -632,12 +672,12 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
     const int TR = tm.tile_rows;
 
-    struct Row { GradRaw<BF16> g; F32Raw mo; };
+    struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; };
     auto load_row = [&](int j) {
         Row x;
         const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
         x.g = load_grad_raw<BF16, ALIGNED>(g, idx, lncol);
-        if constexpr (CAME_STATS) x.mo = load_f32_raw<ALIGNED>(M, idx, lncol);
+        if constexpr (CAME_STATS) x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         return x;
     };
     const WaveRows wr = wave_rows<kRows2>(t);
@@ -676,7 +716,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         unpack<BF16>(row.g, x);
         if constexpr (CAME_STATS) {
             float mo[8];
-            unpack(row.mo, mo);
+            unpack<MB16>(row.mo, mo);
             double rP = 0.0, rQ = 0.0, rW = 0.0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -756,7 +796,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #ifndef CAME_WAVES2
 #define CAME_WAVES2 3
 #endif
-#define CAME_SWEEP2_KERNEL(NAME, BF16, ALIGNED, STATS, WAVES)                                             \
+#define CAME_SWEEP2_KERNEL(NAME, BF16, ALIGNED, STATS, MB16, WAVES)                                             \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
     void NAME(DeviceTables tb, int32_t item_begin)                                                  \
     {                                                                                               \
@@ -769,20 +809,25 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         float* rowfac = reinterpret_cast<float*>(rowbuf_f64 + 3 * tm.tile_rows);                    \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
         if (!ALIGNED || full)                                                                       \
-            sweep2_tile<BF16, ALIGNED, true, STATS>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch, \
+            sweep2_tile<BF16, ALIGNED, true, STATS, MB16>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch, \
                                              tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
         else                                                                                        \
-            sweep2_tile<BF16, ALIGNED, false, STATS>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch, \
+            sweep2_tile<BF16, ALIGNED, false, STATS, MB16>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch, \
                                               tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
     }
-CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, true, CAME_WAVES2)
-CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, true, 2)
-CAME_SWEEP2_KERNEL(sweep2_bf16_unaligned_kernel, true, false, true, 2)
-CAME_SWEEP2_KERNEL(sweep2_f32_unaligned_kernel, false, false, true, 2)
-CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_kernel, true, true, false, 8)
-CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_kernel, false, true, false, 8)
-CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_unaligned_kernel, true, false, false, 4)
-CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_unaligned_kernel, false, false, false, 4)
+CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, true, false, CAME_WAVES2)
+CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, true, false, 2)
+CAME_SWEEP2_KERNEL(sweep2_bf16_unaligned_kernel, true, false, true, false, 2)
+CAME_SWEEP2_KERNEL(sweep2_f32_unaligned_kernel, false, false, true, false, 2)
+CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_kernel, true, true, true, true, CAME_WAVES2)
+CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_kernel, false, true, true, true, 2)
+CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_unaligned_kernel, true, false, true, true, 2)
+CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_unaligned_kernel, false, false, true, true, 2)
+// Algorithm 1: M is not read, so its storage type does not matter here
+CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_kernel, true, true, false, false, 8)
+CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_kernel, false, true, false, false, 8)
+CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_unaligned_kernel, true, false, false, false, 4)
+CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_unaligned_kernel, false, false, false, false, 4)
 
 // ---------------------------------------------------------------- finalize 2
 
@@ -865,7 +910,8 @@ constexpr int kRows3 = CAME_ROWS3;
 // u^ = kappa g / sqrt(v);  M_t = beta1 M_{t-1} + (1-beta1) u^;
 // theta_t = theta_{t-1} - eta M_t / sqrt(S_t)      (Algorithm 1: theta_t = theta_{t-1} - eta M_t)
 // COPY16: also write theta_t as bfloat16 to theta16 (came_step_bf16_copy).
-template <bool BF16, bool ALIGNED, bool FULL, bool COPY16>
+// MB16: M is stored as bfloat16; theta_t is formed from the unrounded M_t.
+template <bool BF16, bool ALIGNED, bool FULL, bool COPY16, bool MB16>
 __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
                             float* theta, void* theta16, float* state, const char* scratch,
                             const TensorScalars* sc, const SweepHyper& h, float* rowfac /* [2][tile_rows] */)
@@ -881,12 +927,12 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
 
-    struct Row { GradRaw<BF16> g; F32Raw mo, th; };
+    struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; F32Raw th; };
     auto load_row = [&](int j) {
         Row x;
         const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
         x.g = load_grad_raw<BF16, ALIGNED>(g, idx, lncol);
-        x.mo = load_f32_raw<ALIGNED>(M, idx, lncol);
+        x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         x.th = load_f32_raw<ALIGNED>(theta, idx, lncol);
         return x;
     };
@@ -935,7 +981,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const float Ar = rowfac[TR + i];
         float x[8], mo[8], th[8], mn[8], tn[8];
         unpack<BF16>(row.g, x);
-        unpack(row.mo, mo);
+        unpack<MB16>(row.mo, mo);
         unpack(row.th, th);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -945,11 +991,11 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         }
         const int64_t idx = (t.row0 + i) * m + t.col;
         if constexpr (ALIGNED && FULL) {
-            store_f32x8<true>(M, idx, kLaneCols, mn);
+            store_mom<MB16, true>(M, idx, kLaneCols, mn);
             store_f32x8<true>(theta, idx, kLaneCols, tn);
             if constexpr (COPY16) store_bf16x8<true>(theta16, idx, kLaneCols, tn);
         } else {
-            store_f32x8<ALIGNED>(M, idx, t.ncol, mn);
+            store_mom<MB16, ALIGNED>(M, idx, t.ncol, mn);
             store_f32x8<ALIGNED>(theta, idx, t.ncol, tn);
             if constexpr (COPY16) store_bf16x8<ALIGNED>(theta16, idx, t.ncol, tn);
         }
@@ -977,7 +1023,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #ifndef CAME_WAVES3
 #define CAME_WAVES3 3
 #endif
-#define CAME_SWEEP3_KERNEL(NAME, BF16, ALIGNED, WAVES)                                              \
+#define CAME_SWEEP3_KERNEL(NAME, BF16, ALIGNED, MB16, WAVES)                                              \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
     void NAME(DeviceTables tb, int32_t item_begin, SweepHyper h)                                    \
     {                                                                                               \
@@ -991,17 +1037,21 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const void* g = tb.grad[it.tensor];                                                         \
         const TensorScalars* sc = tb.scalars + it.tensor;                                           \
         if (!ALIGNED || full) {                                                                     \
-            if (theta16) sweep3_tile<BF16, ALIGNED, true, true>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
-            else sweep3_tile<BF16, ALIGNED, true, false>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            if (theta16) sweep3_tile<BF16, ALIGNED, true, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, true, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
         } else {                                                                                    \
-            if (theta16) sweep3_tile<BF16, ALIGNED, false, true>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
-            else sweep3_tile<BF16, ALIGNED, false, false>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            if (theta16) sweep3_tile<BF16, ALIGNED, false, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, false, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
         }                                                                                           \
     }
-CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, CAME_WAVES3)
-CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, 3)
-CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, 2)
-CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, 2)
+CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, false, CAME_WAVES3)
+CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, false, 3)
+CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, false, 2)
+CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, false, 2)
+CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_kernel, true, true, true, CAME_WAVES3)
+CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_kernel, false, true, true, 3)
+CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_unaligned_kernel, true, false, true, 2)
+CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_unaligned_kernel, false, false, true, 2)
 
 // ---------------------------------------------------------------- placement probe
 
@@ -1018,6 +1068,18 @@ __global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTable
     if (t.ncol == 0) return;
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
     float* M = tb.state + tm.off_M;
+    if (tm.flags & kFlagBf16Momentum) {
+        for (int i = t.wave; i < t.nrows; i += kWaves) {
+            const int64_t idx = (t.row0 + i) * tm.m + t.col;
+            u32x4* pm = reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(M) + idx);
+            f32x4* pt = reinterpret_cast<f32x4*>(theta + idx);
+            u32x4 m0 = pm[0];
+            f32x4 t0 = pt[0], t1 = pt[1];
+            asm volatile("" : "+v"(m0), "+v"(t0), "+v"(t1));
+            pm[0] = m0; pt[0] = t0; pt[1] = t1;
+        }
+        return;
+    }
     for (int i = t.wave; i < t.nrows; i += kWaves) {
         const int64_t idx = (t.row0 + i) * tm.m + t.col;
         f32x4* pm = reinterpret_cast<f32x4*>(M + idx);
@@ -1092,7 +1154,7 @@ hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, 
     if (item_end <= item_begin) return hipSuccess;
     const dim3 grid(item_end - item_begin), block(kWorkgroup);
     const size_t dyn = sizeof(float) * static_cast<size_t>(tile_rows);  // row sums of one tile
-    switch (variant) {
+    switch (variant & 3) {  // sweep 1 does not touch M
         case 0: sweep1_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
         case 1: sweep1_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
         case 2: sweep1_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
@@ -1121,10 +1183,14 @@ hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32
             case 0: sweep2_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
             case 1: sweep2_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
             case 2: sweep2_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            default: sweep2_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+            case 3: sweep2_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+            case 4: sweep2_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+            case 5: sweep2_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+            case 6: sweep2_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+            default: sweep2_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
         }
     } else {
-        switch (variant) {
+        switch (variant & 3) {
             case 0: sweep2_adafactor_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
             case 1: sweep2_adafactor_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
             case 2: sweep2_adafactor_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
@@ -1152,7 +1218,11 @@ hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, 
         case 0: sweep3_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
         case 1: sweep3_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
         case 2: sweep3_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        default: sweep3_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        case 3: sweep3_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        case 4: sweep3_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        case 5: sweep3_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        case 6: sweep3_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        default: sweep3_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
     }
     return hipGetLastError();
 }

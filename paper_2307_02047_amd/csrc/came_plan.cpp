@@ -62,6 +62,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     if (o.tile_rows != 0 && (o.tile_rows < 4 || o.tile_rows > 1024 || o.tile_rows % 4 != 0))
         return CAME_EINVAL;
     if (o.group_elements < 0) return CAME_EINVAL;
+    if (o.momentum_dtype != CAME_MOMENTUM_F32 && o.momentum_dtype != CAME_MOMENTUM_BF16) return CAME_EINVAL;
 
     for (int32_t t = 0; t < count; ++t) {
         const came_tensor_desc& d = descs[t];
@@ -78,6 +79,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     p = Plan{};
     p.descs.assign(descs, descs + count);
     p.algo = o.algo;
+    p.momentum_dtype = o.momentum_dtype;
     p.tile_rows = o.tile_rows ? o.tile_rows : auto_tile_rows(descs, count);
     p.metas.resize(count);
 
@@ -89,10 +91,13 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         tm = TensorMeta{};
         tm.n = d.rows;
         tm.m = d.ndim == 2 ? d.cols : 1;
-        tm.flags = (d.grad_dtype == CAME_GRAD_BF16 ? kFlagBf16Grad : 0);
+        tm.flags = (d.grad_dtype == CAME_GRAD_BF16 ? kFlagBf16Grad : 0) |
+                   (o.momentum_dtype == CAME_MOMENTUM_BF16 ? kFlagBf16Momentum : 0);
         const int64_t nm = tm.n * tm.m;
         p.total_elements += nm;
-        tm.off_M = off; off = round_up(off + nm, kAlignFloats);
+        // a bfloat16 M occupies half as many floats of the blob
+        const int64_t m_floats = o.momentum_dtype == CAME_MOMENTUM_BF16 ? (nm + 1) / 2 : nm;
+        tm.off_M = off; off = round_up(off + m_floats, kAlignFloats);
         tm.off_r = off; off = round_up(off + tm.n, kAlignFloats);
         if (d.ndim == 2) {
             tm.off_c = off; off = round_up(off + tm.m, kAlignFloats);

@@ -24,6 +24,7 @@ enum TensorFlags : int32_t {
     kFlagBf16Grad = 1,  // gradient stored as bfloat16
     kFlagVector = 2,    // 1-D parameter: unfactored update, one workgroup
     kFlagAligned = 4,   // cols % 8 == 0: every row starts 16-byte aligned -> vector loads
+    kFlagBf16Momentum = 8,  // M stored as bfloat16 (off_M still counts floats from the blob's start)
 };
 
 // Per-tensor descriptor in device memory (scratch blob).
@@ -77,11 +78,13 @@ struct TensorScalars {
 static_assert(sizeof(TensorScalars) == 32, "TensorScalars layout");
 
 // Matrix tiles are launched per kernel variant so that each variant gets its own
-// register allocation: gradient dtype x (vector loads | element-wise loads).
-constexpr int kVariants = 4;
+// register allocation: gradient dtype x (vector loads | element-wise loads) x momentum dtype.
+// Bit 0: binary32 gradient, bit 1: unaligned rows, bit 2: bfloat16 momentum.
+constexpr int kVariants = 8;
 inline int variant_of(int32_t flags)
 {
-    return ((flags & kFlagBf16Grad) ? 0 : 1) + ((flags & kFlagAligned) ? 0 : 2);
+    return ((flags & kFlagBf16Grad) ? 0 : 1) + ((flags & kFlagAligned) ? 0 : 2) +
+           ((flags & kFlagBf16Momentum) ? 4 : 0);
 }
 
 // Consecutive tensors launched together: each phase is one launch per group and
@@ -102,6 +105,7 @@ struct Plan {
     std::vector<Group> groups;
     int32_t tile_rows = 0;
     int32_t algo = 0;
+    int32_t momentum_dtype = 0;
     int64_t n_matrices = 0, n_vectors = 0, total_elements = 0;
     // state blob
     size_t state_bytes = 0;

@@ -67,6 +67,23 @@ def test_tensors_with_more_than_two_dimensions_merge_their_leading_dimensions():
     assert P.state_size([(6, 50, 520)], [0]) == P.state_size([(300, 520)], [0])
 
 
+def test_bf16_momentum_halves_the_momentum_bytes():
+    shapes, dt = [(4096, 4096), (4096,)], [1, 1]
+    f32, _ = P.state_size(shapes, dt)
+    b16, _ = P.state_size(shapes, dt, momentum_dtype=P.MOMENTUM_BF16)
+    assert f32 - b16 == 2 * (4096 * 4096 + 4096)
+    with pytest.raises(P.CameError):
+        P.state_size(shapes, dt, momentum_dtype=2)
+    assert P.algorithmic_bytes(2, 4) == 26 and P.algorithmic_bytes(4, 4) == 32
+    assert P.algorithmic_bytes(2, 2) == 20 and P.algorithmic_bytes(4, 2) == 26
+    assert P.algorithmic_bytes(2, 4, P.ALGO_ADAFACTOR) == 22 and P.algorithmic_bytes(2, 2, P.ALGO_ADAFACTOR) == 18
+    assert [P.algorithmic_bytes(2, 2, P.ALGO_CAME, k) for k in (1, 2, 3)] == [2, 4, 14]
+    assert P.algorithmic_bytes(3, 4) == 0 and P.algorithmic_bytes(2, 8) == 0
+    for g in (2, 4):
+        for k in range(4):
+            assert P.algorithmic_bytes(g, 4, P.ALGO_CAME, k) == P.algorithmic_bytes_per_param(g, k)
+
+
 def test_groups_split_the_list():
     shapes = [(256, 512), (512,), (100, 1024), (1024,), (512, 512)]
     assert P.plan_query(shapes, [0] * 5)["groups"] == 1
