@@ -1048,7 +1048,10 @@ CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, false, CAME_WAVES3)
 CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, false, 3)
 CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, false, 2)
 CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, false, 2)
-CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_kernel, true, true, true, CAME_WAVES3)
+#ifndef CAME_WAVES3M
+#define CAME_WAVES3M CAME_WAVES3
+#endif
+CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_kernel, true, true, true, CAME_WAVES3M)
 CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_kernel, false, true, true, 3)
 CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_unaligned_kernel, true, false, true, 2)
 CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_unaligned_kernel, false, false, true, 2)
