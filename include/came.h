@@ -159,8 +159,11 @@ int came_init_state(came_ctx **out, const came_tensor_desc *descs, int32_t count
  * loop; Algorithm 1 if the context was created with CAME_ALGO_ADAFACTOR).
  * theta_dev / grad_dev: host arrays of `count` device pointers, one per
  * tensor in descriptor order; theta[i] (binary32, updated in place) and
- * grad[i] (dtype of the descriptor, read only) are contiguous, 16-byte
- * aligned, and alias neither each other nor the state/scratch blobs.
+ * grad[i] (dtype of the descriptor, read only) are contiguous and 16-byte
+ * aligned.  No parameter may overlap any other buffer of the call or the
+ * state/scratch blobs (CAME_EINVAL, checked whenever an address differs from
+ * the previous call's); gradients are only read and may share memory with
+ * each other.
  * lr is the learning rate eta; step is the 1-based iteration number t, which
  * is validated (must be >= 1) and recorded but, as in Algorithm 2, never used
  * in the arithmetic.  Asynchronous on hip_stream.

@@ -82,10 +82,45 @@ DeviceTables tables_for(const came_ctx* ctx, int slot)
     return t;
 }
 
+// The caller's buffers must not overlap anything that is written: a parameter (or its
+// bfloat16 copy) may overlap no other buffer and neither blob; gradients are only read,
+// so two tensors may share one.  Sorted sweep over the address ranges.
+int check_overlaps(const came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+                   void* const* theta16_dev)
+{
+    struct Range { uintptr_t lo, hi; bool written; };
+    const Plan& p = ctx->plan;
+    const size_t count = p.descs.size();
+    std::vector<Range> r;
+    r.reserve(3 * count + 2);
+    auto add = [&](const void* ptr, size_t bytes, bool written) {
+        const uintptr_t lo = reinterpret_cast<uintptr_t>(ptr);
+        r.push_back(Range{lo, lo + bytes, written});
+    };
+    for (size_t t = 0; t < count; ++t) {
+        const size_t nm = static_cast<size_t>(p.metas[t].n) * static_cast<size_t>(p.metas[t].m);
+        add(theta_dev[t], nm * sizeof(float), true);
+        if (grad_dev) add(grad_dev[t], nm * ((p.metas[t].flags & kFlagBf16Grad) ? 2 : 4), false);
+        if (theta16_dev && theta16_dev[t]) add(theta16_dev[t], nm * 2, true);
+    }
+    add(ctx->state, p.state_bytes, true);
+    add(ctx->scratch, p.scratch_bytes, true);
+    std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
+    uintptr_t end_written = 0, end_any = 0;  // furthest end among the ranges already passed
+    for (const Range& x : r) {
+        if (x.lo < end_written) return CAME_EINVAL;
+        if (x.written && x.lo < end_any) return CAME_EINVAL;
+        end_any = std::max(end_any, x.hi);
+        if (x.written) end_written = std::max(end_written, x.hi);
+    }
+    return CAME_OK;
+}
+
 // Pointer table: re-uploaded only when an address changed since the last call.
-// theta16_dev may be null (no bf16 copies at all) or hold null entries.
+// theta16_dev may be null (no bf16 copies at all) or hold null entries.  check_grads: the
+// gradient entries are real buffers (the placement probe fills them with placeholders).
 int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
-                    void* const* theta16_dev, hipStream_t s)
+                    void* const* theta16_dev, hipStream_t s, bool check_grads = true)
 {
     const Plan& p = ctx->plan;
     const size_t count = p.descs.size();
@@ -97,6 +132,8 @@ int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* gr
                       ctx->cached[2 * count + t] != copy_of(t);
     }
     if (changed) {
+        const int rc = check_overlaps(ctx, theta_dev, check_grads ? grad_dev : nullptr, theta16_dev);
+        if (rc != CAME_OK) return rc;
         const int slot = (ctx->slot + 1) % kPtrSlots;
         if (ctx->slot_used[slot]) {
             const hipError_t e = hipEventSynchronize(ctx->slot_event[slot]);
@@ -358,7 +395,7 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // the probe reads no gradients: the pointer table's gradient half just repeats theta
     std::vector<const void*> fake(theta_dev, theta_dev + count);
-    int rc = upload_pointers(ctx, theta_dev, fake.data(), nullptr, s);
+    int rc = upload_pointers(ctx, theta_dev, fake.data(), nullptr, s, false);
     if (rc != CAME_OK) return rc;
     ctx->cached.clear();  // force a fresh table at the next came_step
     const int used_slot = ctx->slot;

@@ -350,6 +350,22 @@ def test_step_rejects_bad_arguments_on_device():
     with pytest.raises(P.CameError) as e:  # theta and grad are the same buffer
         opt.step(th, [th[0], g[1]], P.CameHyper(), 1e-3, 2)
     assert e.value.status == -1
+    big = torch.zeros(64 * 512 + 512 + 64, dtype=torch.float32, device="cuda:0")
+    overlapping = [big[: 64 * 512].view(64, 512), big[64 * 512 - 64: 64 * 512 - 64 + 512]]  # theta[1] starts inside theta[0]
+    with pytest.raises(P.CameError) as e:
+        opt.step(overlapping, g, P.CameHyper(), 1e-3, 2)
+    assert e.value.status == -1
+    with pytest.raises(P.CameError) as e:  # a gradient that lies inside a parameter
+        opt.step(th, [g[0], th[0].view(-1)[1024:1536]], P.CameHyper(), 1e-3, 2)
+    assert e.value.status == -1
+    with pytest.raises(P.CameError) as e:  # a parameter inside the state blob
+        opt.step([th[0], opt.state_view(0)["M"].view(-1)[:512]], g, P.CameHyper(), 1e-3, 2)
+    assert e.value.status == -1
+    shared = [g[0], g[0].view(-1)[:512]]   # two tensors reading one gradient buffer: allowed
+    opt2 = P.CameStep(w.shapes, [0, 0])
+    t2 = [x.clone() for x in th]
+    opt2.step(t2, shared, P.CameHyper(), 1e-3, 1)
+    opt2.close()
     torch.cuda.synchronize()
     for a, b in zip(snap, th + [opt.state_view(0)[k] for k in "MrcRC"]):
         assert torch.equal(a, b)
