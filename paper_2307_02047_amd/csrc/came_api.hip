@@ -325,15 +325,20 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
 
     const DeviceTables tb = tables_for(ctx, ctx->slot);
     for (const Group& g : p.groups) {
-        hipError_t e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
+        hipError_t e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
         if (e != hipSuccess) return hip_fail(ctx, e);
-        e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
-        if (e != hipSuccess) return hip_fail(ctx, e);
-        if (g.fin_end == g.fin_begin) continue;  // vectors only
+        if (g.fin_end == g.fin_begin) {  // vectors only
+            e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
+            if (e != hipSuccess) return hip_fail(ctx, e);
+            continue;
+        }
+        bool vectors_pending = g.vec_end > g.vec_begin;  // they ride along with the first sweep-1 launch
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], s); });
+            const int32_t vb = vectors_pending ? g.vec_begin : 0, ve = vectors_pending ? g.vec_end : 0;
+            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], vb, ve, sh, fh, s); });
             if (e != hipSuccess) return hip_fail(ctx, e);
+            vectors_pending = false;
         }
         e = timed_launch(ctx, 1, s, [&] { return launch_finalize1(tb, g.fin_begin, g.fin_end, fh, s); });
         if (e != hipSuccess) return hip_fail(ctx, e);

@@ -325,16 +325,20 @@ __device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkIt
 // Algorithm 2 on a 1-D parameter (n x 1 special case: v = r, s = R).  One
 // workgroup owns the whole vector; the RMS of Eq. 1 is a workgroup reduction.
 template <bool BF16>
-__device__ void vector_update(const TensorMeta& tm, const void* g, float* theta, uint16_t* theta16, float* state,
+__device__ void vector_update(const TensorMeta& tm, const void* __restrict__ g, float* __restrict__ theta,
+                              uint16_t* __restrict__ theta16, float* state,
                               const SweepHyper& h, const FinalizeHyper& fh, TensorScalars* sc,
                               double* lds4)
 {
-    float* M = state + tm.off_M;
-    float* v = state + tm.off_r;
-    float* s = state + tm.off_R;
+    // the arrays of one tensor never overlap (the host checks the caller's buffers): say so, so
+    // that the loads of several iterations can be in flight instead of waiting for each store
+    float* __restrict__ M = state + tm.off_M;
+    float* __restrict__ v = state + tm.off_r;
+    float* __restrict__ s = state + tm.off_R;
     const int64_t n = tm.n;
     const bool mb16 = tm.flags & kFlagBf16Momentum;
     double acc = 0.0;
+#pragma unroll 4
     for (int64_t i = threadIdx.x; i < n; i += kWorkgroup) {
         const float gi = load_grad1<BF16>(g, i);
         const float vi = h.beta2 * v[i] + h.one_minus_beta2 * (gi * gi + h.eps1);
@@ -350,6 +354,7 @@ __device__ void vector_update(const TensorMeta& tm, const void* g, float* theta,
         sc->kappa = kappa;
         sc->rms_u = static_cast<float>(rms);
     }
+#pragma unroll 4
     for (int64_t i = threadIdx.x; i < n; i += kWorkgroup) {
         const float gi = load_grad1<BF16>(g, i);
         const float uh = kappa * (gi * rsqrtf(v[i]));
@@ -429,6 +434,19 @@ __device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, flo
         theta[i] = tn;
         if (theta16) theta16[i] = static_cast<uint16_t>(bf16_bits(tn));
     }
+}
+
+// Work item `item` is a whole 1-D parameter: its complete update by this workgroup.
+__device__ __forceinline__ void vector_item(const DeviceTables& tb, int32_t item, const SweepHyper& h,
+                                            const FinalizeHyper& fh, double* lds4)
+{
+    const WorkItem it = tb.items[item];
+    const TensorMeta& tm = tb.metas[it.tensor];
+    const void* g = tb.grad[it.tensor];
+    float* theta = static_cast<float*>(tb.theta[it.tensor]);
+    uint16_t* theta16 = static_cast<uint16_t*>(tb.theta16[it.tensor]);
+    if (tm.flags & kFlagBf16Grad) vector_update<true>(tm, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, lds4);
+    else                          vector_update<false>(tm, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, lds4);
 }
 
 // ---------------------------------------------------------------- row scheduling
@@ -551,12 +569,21 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #ifndef CAME_WAVES1
 #define CAME_WAVES1 5
 #endif
+// The last vec_count workgroups of a sweep-1 launch update whole 1-D parameters instead
+// (work items vec_begin...): that work is independent of the matrices and latency-bound,
+// so it hides behind the tiles instead of costing a launch of its own.
 #define CAME_SWEEP1_KERNEL(NAME, BF16, ALIGNED, WAVES)                                              \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
-    void NAME(DeviceTables tb, int32_t item_begin)                                                  \
+    void NAME(DeviceTables tb, int32_t item_begin, int32_t vec_begin, int32_t vec_count,            \
+              SweepHyper h, FinalizeHyper fh)                                                       \
     {                                                                                               \
-        __shared__ float lds[kWaves * kTileCols];                                                   \
+        __shared__ __attribute__((aligned(16))) float lds[kWaves * kTileCols];                      \
         extern __shared__ float rowbuf_f32[];                                                       \
+        const int32_t ntile = static_cast<int32_t>(gridDim.x) - vec_count;                          \
+        if (static_cast<int32_t>(blockIdx.x) >= ntile) {                                            \
+            vector_item(tb, vec_begin + (blockIdx.x - ntile), h, fh, reinterpret_cast<double*>(lds)); \
+            return;                                                                                 \
+        }                                                                                           \
         const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
@@ -575,13 +602,7 @@ __global__ __launch_bounds__(kWorkgroup) void vector_kernel(DeviceTables tb, int
                                                             SweepHyper h, FinalizeHyper fh)
 {
     __shared__ double lds4[4];
-    const WorkItem it = tb.items[item_begin + blockIdx.x];
-    const TensorMeta& tm = tb.metas[it.tensor];
-    const void* g = tb.grad[it.tensor];
-    float* theta = static_cast<float*>(tb.theta[it.tensor]);
-    uint16_t* theta16 = static_cast<uint16_t*>(tb.theta16[it.tensor]);
-    if (tm.flags & kFlagBf16Grad) vector_update<true>(tm, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, lds4);
-    else                          vector_update<false>(tm, g, theta, theta16, tb.state, h, fh, tb.scalars + it.tensor, lds4);
+    vector_item(tb, item_begin + blockIdx.x, h, fh, lds4);
 }
 
 __global__ __launch_bounds__(kWorkgroup) void long_vector_kernel(DeviceTables tb, int32_t item_begin, int32_t pass,
@@ -605,6 +626,27 @@ __global__ __launch_bounds__(kWorkgroup) void long_vector_kernel(DeviceTables tb
 
 // ---------------------------------------------------------------- finalize 1
 
+// Column workgroup of a finalize launch: lane l of every wave owns column chunk*64 + l,
+// wave w adds the row blocks [rb0, rb1), a quarter of them; wave 0 then combines the four
+// partial sums in a fixed order.
+struct FinalizeCols {
+    int lane, wave;
+    int64_t col;
+    int rb0, rb1;
+};
+
+__device__ __forceinline__ FinalizeCols finalize_cols(const TensorMeta& tm, const FinalizeItem& fi)
+{
+    FinalizeCols f;
+    f.lane = threadIdx.x & 63;
+    f.wave = threadIdx.x >> 6;
+    f.col = static_cast<int64_t>(fi.chunk) * kFinalizeCols + f.lane;
+    const int per = (tm.RB + kWaves - 1) / kWaves;
+    f.rb0 = min(f.wave * per, tm.RB);
+    f.rb1 = min(f.rb0 + per, tm.RB);
+    return f;
+}
+
 // r_t = beta2 r_{t-1} + (1-beta2)(rowsum g^2 + m eps1), c_t likewise with n eps1
 // (eps1 sits inside the sums: m resp. n copies).  Each row workgroup also leaves the
 // sum of its 256 new r values; sweep 2 adds those few numbers up to 1^T r_t.
@@ -612,6 +654,7 @@ __global__ __launch_bounds__(kWorkgroup) void finalize1_kernel(DeviceTables tb, 
                                                                FinalizeHyper h)
 {
     __shared__ double lds4[4];
+    __shared__ double colsum[kWaves][kFinalizeCols];
     const FinalizeItem fi = tb.fins[fin_begin + blockIdx.x];
     const TensorMeta& tm = tb.metas[fi.tensor];
     const int64_t idx = static_cast<int64_t>(fi.chunk) * kWorkgroup + threadIdx.x;
@@ -633,12 +676,18 @@ __global__ __launch_bounds__(kWorkgroup) void finalize1_kernel(DeviceTables tb, 
     } else {
         const float* colpart = reinterpret_cast<const float*>(tb.scratch + tm.off_colpart);
         float* c = tb.state + tm.off_c;
-        if (idx < tm.m) {
-            double s = 0.0;
-#pragma unroll 4
-            for (int rb = 0; rb < tm.RB; ++rb) s += static_cast<double>(colpart[static_cast<int64_t>(rb) * tm.m + idx]);
+        const FinalizeCols fc = finalize_cols(tm, fi);
+        double s = 0.0;
+        if (fc.col < tm.m) {
+#pragma unroll 8
+            for (int rb = fc.rb0; rb < fc.rb1; ++rb) s += static_cast<double>(colpart[static_cast<int64_t>(rb) * tm.m + fc.col]);
+        }
+        colsum[fc.wave][fc.lane] = s;
+        __syncthreads();
+        if (fc.wave == 0 && fc.col < tm.m) {
+            s = (colsum[0][fc.lane] + colsum[1][fc.lane]) + (colsum[2][fc.lane] + colsum[3][fc.lane]);
             s += static_cast<double>(tm.n) * h.eps1;
-            c[idx] = static_cast<float>(h.beta2 * static_cast<double>(c[idx]) + h.one_minus_beta2 * s);
+            c[fc.col] = static_cast<float>(h.beta2 * static_cast<double>(c[fc.col]) + h.one_minus_beta2 * s);
         }
     }
 }
@@ -840,6 +889,7 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
                                                                FinalizeHyper h)
 {
     __shared__ double lds4[4];
+    __shared__ double colsum[3][kWaves][kFinalizeCols];
     const FinalizeItem fi = tb.fins[fin_begin + blockIdx.x];
     const TensorMeta& tm = tb.metas[fi.tensor];
     TensorScalars* sc = tb.scalars + fi.tensor;
@@ -885,17 +935,26 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
     } else {
         const double* colpart = reinterpret_cast<const double*>(tb.scratch + tm.off_colpart);
         float* C = tb.state + tm.off_C;
-        if (idx < tm.m) {
-            double sP = 0.0, sQ = 0.0, sW = 0.0;
+        const FinalizeCols fc = finalize_cols(tm, fi);
+        double sP = 0.0, sQ = 0.0, sW = 0.0;
+        if (fc.col < tm.m) {
 #pragma unroll 4
-            for (int rb = 0; rb < tm.RB; ++rb) {
-                const int64_t base = static_cast<int64_t>(rb) * 3 * tm.m + idx;
+            for (int rb = fc.rb0; rb < fc.rb1; ++rb) {
+                const int64_t base = static_cast<int64_t>(rb) * 3 * tm.m + fc.col;
                 sP += colpart[base]; sQ += colpart[base + tm.m]; sW += colpart[base + 2 * tm.m];
             }
+        }
+        colsum[0][fc.wave][fc.lane] = sP; colsum[1][fc.wave][fc.lane] = sQ; colsum[2][fc.wave][fc.lane] = sW;
+        __syncthreads();
+        if (fc.wave == 0 && fc.col < tm.m) {
+            const int l = fc.lane;
+            sP = (colsum[0][0][l] + colsum[0][1][l]) + (colsum[0][2][l] + colsum[0][3][l]);
+            sQ = (colsum[1][0][l] + colsum[1][1][l]) + (colsum[1][2][l] + colsum[1][3][l]);
+            sW = (colsum[2][0][l] + colsum[2][1][l]) + (colsum[2][2][l] + colsum[2][3][l]);
             double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
             U = fmax(U, 0.0);
             U += static_cast<double>(tm.n) * h.eps2;
-            C[idx] = static_cast<float>(h.beta3 * static_cast<double>(C[idx]) + h.one_minus_beta3 * U);
+            C[fc.col] = static_cast<float>(h.beta3 * static_cast<double>(C[fc.col]) + h.one_minus_beta3 * U);
         }
     }
 }
@@ -1152,16 +1211,18 @@ hipError_t launch_long_vectors(const DeviceTables& t, int32_t item_begin, int32_
 }
 
 hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
-                         int32_t item_end, hipStream_t s)
+                         int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
+                         const FinalizeHyper& fh, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
-    const dim3 grid(item_end - item_begin), block(kWorkgroup);
+    const int32_t nvec = vec_end > vec_begin ? vec_end - vec_begin : 0;
+    const dim3 grid(nvec + (item_end - item_begin)), block(kWorkgroup);
     const size_t dyn = sizeof(float) * static_cast<size_t>(tile_rows);  // row sums of one tile
     switch (variant & 3) {  // sweep 1 does not touch M
-        case 0: sweep1_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-        case 1: sweep1_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-        case 2: sweep1_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-        default: sweep1_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        case 0: sweep1_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
+        case 1: sweep1_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
+        case 2: sweep1_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
+        default: sweep1_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
     }
     return hipGetLastError();
 }

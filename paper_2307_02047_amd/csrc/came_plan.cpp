@@ -148,7 +148,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             tm.CB = static_cast<int32_t>(ceil_div(tm.m, kTileCols));
             tm.ntiles = tm.RB * tm.CB;
             tm.f_row_wgs = static_cast<int32_t>(ceil_div(tm.n, kWorkgroup));
-            tm.f_col_wgs = static_cast<int32_t>(ceil_div(tm.m, kWorkgroup));
+            tm.f_col_wgs = static_cast<int32_t>(ceil_div(tm.m, kFinalizeCols));
             for (int32_t k = 0; k < tm.f_row_wgs; ++k) p.fins.push_back(FinalizeItem{t, k, 0, 0});
             for (int32_t k = 0; k < tm.f_col_wgs; ++k) p.fins.push_back(FinalizeItem{t, k, 1, 0});
         }

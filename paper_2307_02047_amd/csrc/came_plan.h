@@ -59,10 +59,13 @@ struct WorkItem {
 constexpr int64_t kFusedVectorMax = 16384;
 constexpr int64_t kMaxVectorChunks = 1024;
 
-// One workgroup of a finalize launch: 256 rows or 256 columns of one matrix.
+// One workgroup of a finalize launch: 256 rows of one matrix (a thread per row, adding the
+// row's partials over the column blocks), or 64 columns (a wave per quarter of the row
+// blocks, a lane per column: tall matrices have hundreds of row blocks to add per column).
+constexpr int kFinalizeCols = 64;
 struct FinalizeItem {
     int32_t tensor;
-    int32_t chunk;  // outputs [chunk*256, chunk*256+256)
+    int32_t chunk;  // rows [chunk*256, chunk*256+256) or columns [chunk*64, chunk*64+64)
     int32_t kind;   // 0 = rows (r, R), 1 = columns (c, C)
     int32_t pad_;
 };

@@ -46,7 +46,7 @@ def test_plan_of_the_named_workloads(make, params, mats, vecs):
     tr, tc = q["tile_rows"], q["tile_cols"]
     want = sum(-(-s[0] // tr) * -(-s[1] // tc) for s in w.shapes if len(s) == 2) + vecs  # all vectors are short
     assert q["sweep_items"] == want
-    assert q["finalize_items"] == sum(-(-s[0] // 256) + -(-s[1] // 256) for s in w.shapes if len(s) == 2)
+    assert q["finalize_items"] == sum(-(-s[0] // 256) + -(-s[1] // 64) for s in w.shapes if len(s) == 2)
     sb, wb = P.state_size(w.shapes, [w.grad_dtype] * len(w.shapes))
     assert sb >= 4 * sum((s[0] * s[1] + 2 * (s[0] + s[1])) if len(s) == 2 else 3 * s[0] for s in w.shapes)
     assert wb < 0.25 * sb or wb < (1 << 20)  # scratch stays a fraction of the state
