@@ -192,8 +192,8 @@ def main() -> int:
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS,
-        "traffic": read_traffic(os.path.join(ROOT, "profiles", f"sweep3_{args.workload}_traffic.txt"))
-        if mdt == P.MOMENTUM_F32 else None,
+        "traffic": read_traffic(os.path.join(
+            ROOT, "profiles", f"sweep3_{args.workload}{'_bf16_momentum' if mbytes == 2 else ''}_traffic.txt")),
         "bytes_per_launch": s3_bytes,
         "avg_launch_ms": s3_avg_ms,
         "whole_step": {

@@ -206,3 +206,58 @@ def test_bf16_copy_together_with_bf16_momentum():
             assert torch.equal(a.state_view(k)["M"], b.state_view(k)["M"])
     finally:
         a.close(); b.close()
+
+
+def test_llama_full_size_sampled_bf16_momentum():
+    """The whole 6.7B-parameter list with a bfloat16 momentum in the launch configuration
+    `bench.py --momentum-dtype bf16` times (all tensors, default plan, 512-row tiles); the oracle
+    follows one tensor of every distinct shape.  Step 1 starts from the same (zero) state on
+    both sides, so it is compared directly; step 2 restarts the sampled tensors from the
+    oracle's state."""
+    w = W.llama_7b()
+    seen, check = set(), []
+    for k, s in enumerate(w.shapes):
+        if s not in seen and s != (32000, 4096):
+            seen.add(s)
+            check.append(k)
+    check.append(len(w.shapes) - 1)  # LM head 32000 x 4096
+    n = len(w.shapes)
+    gen = W.Generator(w, device="cuda:0")
+    opt = P.CameStep(w.shapes, [w.grad_dtype] * n, momentum_dtype=P.MOMENTUM_BF16)
+    theta = [gen.theta0(i) for i in range(n)]
+    shapes = [w.shapes[k] for k in check]
+    otl = O.TensorList(shapes, [to_f64(theta[k]) for k in check])
+    h, oh = P.CameHyper(), O.Hyper(lr=w.lr)
+
+    class Sampled:  # the library's tensors the oracle follows, addressed by the oracle's positions
+        def state_view(self, pos):
+            return opt.state_view(check[pos])
+
+    try:
+        for t in (1, 2):
+            grads = [gen.grad(i, t) for i in range(n)]
+            if t > 1:
+                load_oracle_state(Sampled(), [theta[k] for k in check], otl, P.ALGO_CAME)
+            M_prev = [st.M.copy() for st in otl.state]
+            opt.step(theta, grads, h, w.lr, t)
+            exact = oracle_step(otl, [to_f64(grads[k]) for k in check], oh, P.ALGO_CAME)
+            torch.cuda.synchronize()
+            del grads
+            for pos, k in enumerate(check):
+                sv, st = opt.state_view(k), otl.state[pos]
+                e = {"theta": float(signed_err(to_f64(theta[k]), otl.theta[pos]).max())}
+                if isinstance(st, O.MatrixState):
+                    for q in "rcRC":
+                        e[q] = rel_err_positive(to_f64(sv[q]), getattr(st, q))
+                else:
+                    e["v"] = rel_err_positive(to_f64(sv["r"]), st.v)
+                    e["s"] = rel_err_positive(to_f64(sv["R"]), st.s)
+                assert all(v <= 1e-5 for v in e.values()), f"step {t} tensor {k} {w.shapes[k]}: {e}"
+                M = to_f64(sv["M"])
+                noise = 2.0 ** -20 * (np.abs(h.beta1 * M_prev[pos]) + np.abs(exact[pos] - h.beta1 * M_prev[pos]))
+                allowed = 0.5 * bf16_spacing(np.maximum(np.abs(M), np.abs(exact[pos]))) + noise
+                assert not (np.abs(M - exact[pos]) > allowed).any(), f"step {t} tensor {k}: stored M is not a rounding of M_t"
+                print(f"[bf16-M llama] step {t} tensor {k} {w.shapes[k]}: " + ", ".join(f"{q}={v:.1e}" for q, v in e.items()) +
+                      f", M stored differently {(M != st.M).mean():.1e}", flush=True)
+    finally:
+        opt.close()
