@@ -341,6 +341,18 @@ void came_oracle_store_bf16(double *x, int64_t count)
 }
 
 /*
+ * Decoupled weight decay (NOT in the paper; the usual companion of such optimizers in
+ * practice): before the step's update the parameter shrinks by eta * lambda * theta,
+ *   theta <- theta - eta lambda theta,
+ * independently of the gradient statistics.  The step functions above then run unchanged
+ * on the shrunk theta.
+ */
+void came_oracle_decay(double *theta, int64_t count, double lr, double weight_decay)
+{
+    for (int64_t k = 0; k < count; ++k) theta[k] = theta[k] - lr * weight_decay * theta[k];
+}
+
+/*
  * One CAME step over a list of tensors.  Tensors are independent (Algorithm 2
  * is stated per parameter matrix), so the only parallelism is one tensor per
  * OpenMP thread; the arithmetic of each tensor is the serial code above.

@@ -84,6 +84,8 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.came_oracle_round_bf16.restype = ctypes.c_double
     lib.came_oracle_store_bf16.argtypes = [dp, i64]
     lib.came_oracle_store_bf16.restype = None
+    lib.came_oracle_decay.argtypes = [dp, i64, ctypes.c_double, ctypes.c_double]
+    lib.came_oracle_decay.restype = None
     lib.came_oracle_max_threads.argtypes = []
     lib.came_oracle_max_threads.restype = i32
     if path == _LIB:
@@ -207,11 +209,31 @@ class TensorList:
     def state_elems(self) -> int:
         return sum(s.elems() for s in self.state)
 
-    def step(self, grads, h: Hyper, nthreads: int = 1, lib=None, momentum_bf16: bool = False) -> None:
+    def step(self, grads, h: Hyper, nthreads: int = 1, lib=None, momentum_bf16: bool = False,
+             weight_decay: float = 0.0, vector_confidence: bool = True) -> None:
         """One step of every tensor.  momentum_bf16: after the step (theta and all other
         state already updated from the unrounded m_t) every momentum is replaced by its
-        nearest bfloat16, the value the next step reads as m_{t-1}."""
+        nearest bfloat16, the value the next step reads as m_{t-1}.  weight_decay: decoupled
+        decay theta <- theta - eta*lambda*theta applied before the step.  vector_confidence
+        False: 1-D parameters take Algorithm 1's update theta <- theta - eta*m_t (no
+        instability / confidence statistics; their s stays untouched); matrices are unaffected."""
         lib = lib or load()
+        if weight_decay != 0.0:
+            for th in self.theta:
+                lib.came_oracle_decay(_p(th.reshape(-1)), th.size, h.lr, float(weight_decay))
+        if not vector_confidence:
+            self._step_vectors_without_confidence(grads, h, lib)
+            mats = [i for i, s in enumerate(self.shapes) if len(s) == 2]
+            if mats:
+                sub = TensorList.__new__(TensorList)
+                sub.shapes = [self.shapes[i] for i in mats]
+                sub.theta = [self.theta[i] for i in mats]
+                sub.state = [self.state[i] for i in mats]
+                sub.step([grads[i] for i in mats], h, nthreads=nthreads, lib=lib)
+            if momentum_bf16:
+                for st in self.state:
+                    store_bf16(st.M, lib)
+            return
         T = len(self.shapes)
         grads = [np.ascontiguousarray(g, dtype=np.float64) for g in grads]
         rows = (ctypes.c_int64 * T)(*[s[0] for s in self.shapes])
@@ -238,6 +260,22 @@ class TensorList:
         if momentum_bf16:
             for st in self.state:
                 store_bf16(st.M, lib)
+
+
+def _vector_adafactor(self, grads, h, lib):
+    """Algorithm 1 on every 1-D parameter of the list, as its n x 1 matrix (then c is the
+    scalar sum of v, kept beside the state)."""
+    for i, s in enumerate(self.shapes):
+        if len(s) != 1:
+            continue
+        st = self.state[i]
+        if not hasattr(st, "c1"):
+            st.c1 = np.zeros(1)
+        g = np.ascontiguousarray(grads[i], dtype=np.float64)
+        adafactor_matrix_step(self.theta[i].reshape(-1, 1), g.reshape(-1, 1), st.M.reshape(-1, 1), st.v, st.c1, h, lib)
+
+
+TensorList._step_vectors_without_confidence = _vector_adafactor
 
 
 def round_bf16(x: float, lib=None) -> float:

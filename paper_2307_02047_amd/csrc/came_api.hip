@@ -50,7 +50,6 @@ template <class F>
 hipError_t timed_launch(came_ctx* ctx, int phase, hipStream_t s, F launch)
 {
     if (!ctx->profiling || ctx->timed.size() >= kMaxTimed) return launch();
-    // (an empty range launches nothing but is still bracketed: negligible)
     came_ctx::Timed t{};
     t.phase = phase;
     hipError_t e = hipEventCreate(&t.start);
@@ -325,8 +324,11 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
 
     const DeviceTables tb = tables_for(ctx, ctx->slot);
     for (const Group& g : p.groups) {
-        hipError_t e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
-        if (e != hipSuccess) return hip_fail(ctx, e);
+        hipError_t e = hipSuccess;
+        if (g.lvec_end > g.lvec_begin) {
+            e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
         if (g.fin_end == g.fin_begin) {  // vectors only
             e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
             if (e != hipSuccess) return hip_fail(ctx, e);

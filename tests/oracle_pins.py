@@ -493,6 +493,63 @@ def pin_bf16_momentum_mode(lib):
     assert not np.array_equal(C.state[0].M, _torch_bf16(C.state[0].M))
 
 
+# --------------------------------------------------------------------------- options beyond the paper
+def pin_weight_decay(lib):
+    """Decoupled decay: with a zero gradient nothing but the decay moves theta (u = 0, so
+    m = 0), hence theta_t = theta_0 (1 - eta lambda)^t exactly; lambda = 0 changes nothing;
+    and the decay acts before the update: one step equals a plain step from the shrunk theta."""
+    rng = _rng(41)
+    shapes = [(4, 5), (6,)]
+    th0 = [rng.normal(size=s) for s in shapes]
+    h = O.Hyper(lr=1e-2)
+    A = O.TensorList(shapes, [t.copy() for t in th0])
+    for _ in range(5):
+        A.step([np.zeros(s) for s in shapes], h, lib=lib, weight_decay=0.3)
+    for t, t0 in zip(A.theta, th0):
+        np.testing.assert_allclose(t, t0 * (1 - 1e-2 * 0.3) ** 5, rtol=1e-14)
+    g = [rng.normal(size=s) for s in shapes]
+    B = O.TensorList(shapes, [t.copy() for t in th0])
+    C = O.TensorList(shapes, [t.copy() for t in th0])
+    B.step(g, h, lib=lib, weight_decay=0.0)
+    C.step(g, h, lib=lib)
+    D = O.TensorList(shapes, [t.copy() for t in th0])
+    E = O.TensorList(shapes, [t * (1 - 1e-2 * 0.3) for t in th0])
+    D.step(g, h, lib=lib, weight_decay=0.3)
+    E.step(g, h, lib=lib)
+    for i in range(2):
+        assert np.array_equal(B.theta[i], C.theta[i])
+        np.testing.assert_allclose(D.theta[i], E.theta[i], rtol=1e-15)
+        assert np.array_equal(D.state[i].M, E.state[i].M)
+        assert not np.array_equal(D.theta[i], C.theta[i])
+
+
+def pin_vectors_without_confidence(lib):
+    """Option: 1-D parameters move by -eta m_t (Algorithm 1's last line) while matrices keep
+    Algorithm 2.  The vector's m and v are the same as with confidence (those lines do not
+    involve S), its s stays zero, theta_t - theta_{t-1} = -eta m_t; the matrices are untouched
+    by the option."""
+    rng = _rng(42)
+    shapes = [(4, 5), (7,), (3, 3), (9,)]
+    th0 = [rng.normal(size=s) for s in shapes]
+    h = O.Hyper(lr=1e-2)
+    A = O.TensorList(shapes, [t.copy() for t in th0])
+    B = O.TensorList(shapes, [t.copy() for t in th0])
+    for _ in range(4):
+        g = [rng.normal(size=s) for s in shapes]
+        before = [t.copy() for t in A.theta]
+        A.step(g, h, lib=lib, vector_confidence=False)
+        B.step(g, h, lib=lib)
+        for i, s in enumerate(shapes):
+            if len(s) == 2:
+                assert np.array_equal(A.theta[i], B.theta[i]) and np.array_equal(A.state[i].R, B.state[i].R)
+            else:
+                np.testing.assert_allclose(A.state[i].M, B.state[i].M, rtol=1e-13)
+                np.testing.assert_allclose(A.state[i].v, B.state[i].v, rtol=1e-13)
+                assert not A.state[i].s.any() and B.state[i].s.all()
+                np.testing.assert_allclose(A.theta[i] - before[i], -h.lr * A.state[i].M, rtol=1e-9, atol=1e-15)
+                assert not np.allclose(A.theta[i], B.theta[i])
+
+
 ALL_PINS = [
     pin_step1_rank1_reconstruction,
     pin_rms_clip,
@@ -512,4 +569,6 @@ ALL_PINS = [
     pin_bf16_rounding_by_hand,
     pin_bf16_rounding_matches_library,
     pin_bf16_momentum_mode,
+    pin_weight_decay,
+    pin_vectors_without_confidence,
 ]

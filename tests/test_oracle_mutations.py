@@ -79,6 +79,10 @@ MUTATIONS = [
      "if (fabs(y) >= ldexp(1.0, 128)) return copysign(INFINITY, y);", "", 1),
     ("bf16_rounds_the_double_not_the_binary32",
      "const double f = (double)(float)x; ", "const double f = x; ", 1),
+    ("decay_grows_the_parameter",
+     "theta[k] = theta[k] - lr * weight_decay * theta[k];", "theta[k] = theta[k] + lr * weight_decay * theta[k];", 1),
+    ("decay_ignores_the_learning_rate",
+     "theta[k] = theta[k] - lr * weight_decay * theta[k];", "theta[k] = theta[k] - weight_decay * theta[k];", 1),
     ("list_driver_skips_vectors",
      "e = came_oracle_vector_step(rows[t], theta[t], g[t], M[t], r[t], R[t], h, NULL);",
      "e = 0;", 1),
