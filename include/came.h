@@ -53,7 +53,7 @@ extern "C" {
 typedef enum {
     CAME_OK = 0,
     CAME_EINVAL = -1, /* null pointer, count <= 0, rows/cols <= 0, ndim not 1 or 2, bad dtype,
-                         beta outside [0,1), eps < 0, clip_d <= 0, non-finite lr, step < 1,
+                         beta outside [0,1), eps < 0, clip_d <= 0, weight_decay < 0, non-finite lr, step < 1,
                          option out of range */
     CAME_ESIZE = -2,  /* state or scratch blob smaller than came_state_size reports */
     CAME_EALIGN = -3, /* a device pointer is not aligned as documented */
@@ -83,6 +83,13 @@ typedef enum {
                               storage error of at most 2^-9 in M */
 } came_momentum_dtype;
 
+typedef enum {
+    CAME_VECTOR_ALGORITHM2 = 0,   /* 1-D parameters: Algorithm 2 on the n x 1 matrix (unfactored v and s) */
+    CAME_VECTOR_MOMENTUM_ONLY = 1 /* 1-D parameters move by -eta M_t (Algorithm 1's update: no instability,
+                                     no confidence; their s stays zero); matrices are unaffected.  A
+                                     convention of some trainers, not the paper's */
+} came_vector_rule;
+
 /* One parameter tensor.  ndim == 2: rows x cols matrix (factored statistics).
  * ndim == 1: vector of `rows` entries, cols must be 1 (unfactored statistics).
  * Parameters (theta) and the factored statistics are binary32; the gradient dtype is
@@ -104,6 +111,10 @@ typedef struct {
     double eps1;   /* added to g^2 inside the row/column sums,    >= 0  */
     double eps2;   /* added to U inside the row/column sums,      >= 0  */
     double clip_d; /* RMS clipping threshold d of Eq. 1,          > 0   */
+    double weight_decay; /* lambda >= 0 of a decoupled weight decay (not in the paper): theta
+                            shrinks by eta*lambda*theta before the update, i.e.
+                            theta_t = (1 - eta lambda) theta_{t-1} - eta M_t / sqrt(S_t);
+                            0 = Algorithm 2 as printed */
 } came_hyper;
 
 /* Planner knobs; pass NULL for defaults.  Zero in a field means "default". */
@@ -117,7 +128,8 @@ typedef struct {
                                 group's gradient and momentum can stay in the on-package cache
                                 between phases */
     int32_t momentum_dtype;  /* came_momentum_dtype, for every tensor of the context */
-    int32_t reserved[3];     /* must be zero */
+    int32_t vector_rule;     /* came_vector_rule */
+    int32_t reserved[2];     /* must be zero */
 } came_options;
 
 /* Device addresses of one tensor's state inside the caller's state blob.

@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_PKG, "libcame_hip.so")
 GRAD_F32, GRAD_BF16 = 0, 1
 ALGO_CAME, ALGO_ADAFACTOR = 0, 1
 MOMENTUM_F32, MOMENTUM_BF16 = 0, 1
+VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY = 0, 1
 
 EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_step_bf16_copy", "came_state_view_get",
            "came_plan_query", "came_algorithmic_bytes_per_param", "came_algorithmic_bytes", "came_probe_placement", "came_profile_enable",
@@ -36,13 +37,13 @@ class _Desc(ctypes.Structure):
 
 
 class _Hyper(ctypes.Structure):
-    _fields_ = [(k, ctypes.c_double) for k in ("beta1", "beta2", "beta3", "eps1", "eps2", "clip_d")]
+    _fields_ = [(k, ctypes.c_double) for k in ("beta1", "beta2", "beta3", "eps1", "eps2", "clip_d", "weight_decay")]
 
 
 class _Options(ctypes.Structure):
     _fields_ = [("tile_rows", ctypes.c_int32), ("algo", ctypes.c_int32),
                 ("group_elements", ctypes.c_int64), ("momentum_dtype", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 3)]
+                ("vector_rule", ctypes.c_int32), ("reserved", ctypes.c_int32 * 2)]
 
 
 class _View(ctypes.Structure):
@@ -58,9 +59,10 @@ class CameHyper:
     eps1: float = 1e-30
     eps2: float = 1e-16
     clip_d: float = 1.0
+    weight_decay: float = 0.0  # decoupled weight decay (not in the paper); 0 = Algorithm 2 as printed
 
     def _c(self) -> _Hyper:
-        return _Hyper(self.beta1, self.beta2, self.beta3, self.eps1, self.eps2, self.clip_d)
+        return _Hyper(self.beta1, self.beta2, self.beta3, self.eps1, self.eps2, self.clip_d, self.weight_decay)
 
 
 _lib = None
@@ -139,10 +141,10 @@ def _descs(shapes: Sequence[Sequence[int]], grad_dtypes: Sequence[int]):
 
 
 def _options(tile_rows: int = 0, algo: int = ALGO_CAME, group_elements: int = 0,
-             momentum_dtype: int = MOMENTUM_F32):
+             momentum_dtype: int = MOMENTUM_F32, vector_rule: int = VECTOR_ALGORITHM2):
     o = _Options()
     o.tile_rows, o.algo, o.group_elements = int(tile_rows), int(algo), int(group_elements)
-    o.momentum_dtype = int(momentum_dtype)
+    o.momentum_dtype, o.vector_rule = int(momentum_dtype), int(vector_rule)
     return o
 
 
@@ -190,7 +192,8 @@ class CameStep:
     """
 
     def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
-                 group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32, place_against=None, placement_candidates: int = 6,
+                 group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32,
+                 vector_rule: int = VECTOR_ALGORITHM2, place_against=None, placement_candidates: int = 6,
                  placement_spacer_bytes: int = 8 << 30, placement_accept_gbs: float = 5750.0):
         """place_against: the parameter tensors the context will be stepped with.  When given,
         the state blob is allocated at up to `placement_candidates` different addresses
@@ -207,7 +210,7 @@ class CameStep:
         self.grad_dtypes = [int(d) for d in grad_dtypes]
         self.device = torch.device(device)
         self._d = _descs(self.shapes, self.grad_dtypes)
-        self._o = _options(tile_rows, algo, group_elements, momentum_dtype)
+        self._o = _options(tile_rows, algo, group_elements, momentum_dtype, vector_rule)
         self.momentum_dtype = int(momentum_dtype)
         n = len(self.shapes)
         sb, wb = ctypes.c_size_t(), ctypes.c_size_t()

@@ -310,6 +310,7 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
     sh.eps1 = static_cast<float>(hyper->eps1);
     sh.eps2 = static_cast<float>(hyper->eps2);
     sh.lr = static_cast<float>(lr);
+    sh.decay = static_cast<float>(1.0 - lr * hyper->weight_decay);
     sh.algo = p.algo;
     FinalizeHyper fh{};
     fh.beta1 = hyper->beta1;

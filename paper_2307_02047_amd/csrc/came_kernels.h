@@ -14,6 +14,7 @@ struct SweepHyper {
     float beta3, one_minus_beta3;
     float eps1, eps2;
     float lr;
+    float decay;  // 1 - eta * lambda (decoupled weight decay; 1 when there is none)
     int32_t algo;
 };
 

@@ -337,6 +337,7 @@ __device__ void vector_update(const TensorMeta& tm, const void* __restrict__ g, 
     float* __restrict__ s = state + tm.off_R;
     const int64_t n = tm.n;
     const bool mb16 = tm.flags & kFlagBf16Momentum;
+    const bool came = h.algo == CAME_ALGO_CAME && !(tm.flags & kFlagMomentumOnly);
     double acc = 0.0;
 #pragma unroll 4
     for (int64_t i = threadIdx.x; i < n; i += kWorkgroup) {
@@ -361,13 +362,13 @@ __device__ void vector_update(const TensorMeta& tm, const void* __restrict__ g, 
         const float Mi = fmaf(h.beta1, load_mom1(M, i, mb16), h.one_minus_beta1 * uh);
         store_mom1(M, i, mb16, Mi);
         float tn;
-        if (h.algo == CAME_ALGO_CAME) {
+        if (came) {
             const float dU = uh - Mi;
             const float si = h.beta3 * s[i] + h.one_minus_beta3 * (dU * dU + h.eps2);
             s[i] = si;
-            tn = theta[i] - h.lr * Mi * rsqrtf(si);
+            tn = fmaf(theta[i], h.decay, -(h.lr * Mi * rsqrtf(si)));
         } else {
-            tn = theta[i] - h.lr * Mi;
+            tn = fmaf(theta[i], h.decay, -(h.lr * Mi));
         }
         theta[i] = tn;
         if (theta16) theta16[i] = static_cast<uint16_t>(bf16_bits(tn));
@@ -405,6 +406,7 @@ __device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, flo
     const float* v = state + tm.off_r;
     float* s = state + tm.off_R;
     const bool mb16 = tm.flags & kFlagBf16Momentum;
+    const bool came = h.algo == CAME_ALGO_CAME && !(tm.flags & kFlagMomentumOnly);
     const double* part = reinterpret_cast<const double*>(scratch + tm.off_tileP);
     double p = 0.0;
     for (int k = threadIdx.x; k < tm.ntiles; k += kWorkgroup) p += part[k];
@@ -423,13 +425,13 @@ __device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, flo
         const float Mi = fmaf(h.beta1, load_mom1(M, i, mb16), h.one_minus_beta1 * uh);
         store_mom1(M, i, mb16, Mi);
         float tn;
-        if (h.algo == CAME_ALGO_CAME) {
+        if (came) {
             const float dU = uh - Mi;
             const float si = h.beta3 * s[i] + h.one_minus_beta3 * (dU * dU + h.eps2);
             s[i] = si;
-            tn = theta[i] - h.lr * Mi * rsqrtf(si);
+            tn = fmaf(theta[i], h.decay, -(h.lr * Mi * rsqrtf(si)));
         } else {
-            tn = theta[i] - h.lr * Mi;
+            tn = fmaf(theta[i], h.decay, -(h.lr * Mi));
         }
         theta[i] = tn;
         if (theta16) theta16[i] = static_cast<uint16_t>(bf16_bits(tn));
@@ -967,7 +969,8 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
 constexpr int kRows3 = CAME_ROWS3;
 
 // u^ = kappa g / sqrt(v);  M_t = beta1 M_{t-1} + (1-beta1) u^;
-// theta_t = theta_{t-1} - eta M_t / sqrt(S_t)      (Algorithm 1: theta_t = theta_{t-1} - eta M_t)
+// theta_t = theta_{t-1} - eta M_t / sqrt(S_t)      (Algorithm 1: theta_t = theta_{t-1} - eta M_t);
+// with a decoupled weight decay theta_{t-1} is first scaled by h.decay = 1 - eta lambda.
 // COPY16: also write theta_t as bfloat16 to theta16 (came_step_bf16_copy).
 // MB16: M is stored as bfloat16; theta_t is formed from the unrounded M_t.
 template <bool BF16, bool ALIGNED, bool FULL, bool COPY16, bool MB16>
@@ -1046,7 +1049,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         for (int e = 0; e < 8; ++e) {
             const float uh = (x[e] * a) * b[e];
             mn[e] = fmaf(h.beta1, mo[e], h.one_minus_beta1 * uh);
-            tn[e] = th[e] - (mn[e] * Ar) * Bc[e];
+            tn[e] = fmaf(th[e], h.decay, -((mn[e] * Ar) * Bc[e]));
         }
         const int64_t idx = (t.row0 + i) * m + t.col;
         if constexpr (ALIGNED && FULL) {

@@ -46,6 +46,7 @@ int validate_hyper(const came_hyper* h, double lr, int64_t step)
     if (!(h->eps1 >= 0.0) || !std::isfinite(h->eps1)) return CAME_EINVAL;
     if (!(h->eps2 >= 0.0) || !std::isfinite(h->eps2)) return CAME_EINVAL;
     if (!(h->clip_d > 0.0) || !std::isfinite(h->clip_d)) return CAME_EINVAL;
+    if (!(h->weight_decay >= 0.0) || !std::isfinite(h->weight_decay)) return CAME_EINVAL;
     if (!std::isfinite(lr)) return CAME_EINVAL;
     if (step < 1) return CAME_EINVAL;
     return CAME_OK;
@@ -63,6 +64,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         return CAME_EINVAL;
     if (o.group_elements < 0) return CAME_EINVAL;
     if (o.momentum_dtype != CAME_MOMENTUM_F32 && o.momentum_dtype != CAME_MOMENTUM_BF16) return CAME_EINVAL;
+    if (o.vector_rule != CAME_VECTOR_ALGORITHM2 && o.vector_rule != CAME_VECTOR_MOMENTUM_ONLY) return CAME_EINVAL;
 
     for (int32_t t = 0; t < count; ++t) {
         const came_tensor_desc& d = descs[t];
@@ -112,6 +114,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         } else {
             tm.off_C = -1;
             tm.flags |= kFlagVector;
+            if (o.vector_rule == CAME_VECTOR_MOMENTUM_ONLY) tm.flags |= kFlagMomentumOnly;
             ++p.n_vectors;
         }
     }

@@ -25,6 +25,7 @@ enum TensorFlags : int32_t {
     kFlagVector = 2,    // 1-D parameter: unfactored update, one workgroup
     kFlagAligned = 4,   // cols % 8 == 0: every row starts 16-byte aligned -> vector loads
     kFlagBf16Momentum = 8,  // M stored as bfloat16 (off_M still counts floats from the blob's start)
+    kFlagMomentumOnly = 16, // vector updated by -eta M (no instability / confidence statistics)
 };
 
 // Per-tensor descriptor in device memory (scratch blob).

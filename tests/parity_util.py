@@ -37,7 +37,8 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
 class SideBySide:
     """GPU library on every tensor of `shapes`; oracle on the tensors in `check`."""
 
-    def __init__(self, w: W.Workload, indices=None, check=None, hyper=None, device="cuda:0", algo=0, **opts):
+    def __init__(self, w: W.Workload, indices=None, check=None, hyper=None, device="cuda:0", algo=0,
+                 vector_confidence=True, **opts):
         self.w = w
         self.gen = W.Generator(w, device=device)
         self.idx = list(range(len(w.shapes))) if indices is None else list(indices)
@@ -45,7 +46,9 @@ class SideBySide:
         self.shapes = [w.shapes[i] for i in self.idx]
         self.hyper = hyper or P.CameHyper()
         self.algo = algo  # 0: Algorithm 2 (CAME), 1: Algorithm 1 (Adafactor with momentum)
-        self.opt = P.CameStep(self.shapes, [w.grad_dtype] * len(self.shapes), device=device, algo=algo, **opts)
+        self.vector_confidence = vector_confidence  # False: 1-D parameters move by -eta M (option beyond the paper)
+        self.opt = P.CameStep(self.shapes, [w.grad_dtype] * len(self.shapes), device=device, algo=algo,
+                              vector_rule=P.VECTOR_ALGORITHM2 if vector_confidence else P.VECTOR_MOMENTUM_ONLY, **opts)
         self.theta = [self.gen.theta0(i) for i in self.idx]
         self.otl = O.TensorList([self.shapes[k] for k in self.check], [to_f64(self.theta[k]) for k in self.check])
         self.t = 0
@@ -59,8 +62,10 @@ class SideBySide:
                      self.hyper.clip_d, self.w.lr)
         og = [to_f64(grads[k]) for k in self.check]
         if self.algo == 0:
-            self.otl.step(og, oh, nthreads=nthreads)
+            self.otl.step(og, oh, nthreads=nthreads, weight_decay=self.hyper.weight_decay,
+                          vector_confidence=self.vector_confidence)
         else:
+            assert self.hyper.weight_decay == 0.0
             # Algorithm 1 per tensor; a vector is its n x 1 matrix (then v = r, c is a scalar)
             for pos, g in enumerate(og):
                 st, th = self.otl.state[pos], self.otl.theta[pos]
@@ -97,7 +102,7 @@ class SideBySide:
                     assert not sv["R"].any() and not sv["C"].any()
             else:
                 upd("v", rel_err_positive(to_f64(sv["r"]), st.v), k)
-                if self.algo == 0:
+                if self.algo == 0 and self.vector_confidence:
                     upd("s", rel_err_positive(to_f64(sv["R"]), st.s), k)
                 else:
                     assert not sv["R"].any()

@@ -485,3 +485,46 @@ def test_more_than_two_dimensions_are_merged_leading_dimensions():
     for k in "rcRC":
         assert torch.equal(va[k], vb[k])
     a.close(); b.close()
+
+
+def test_decoupled_weight_decay():
+    """theta_t = (1 - eta lambda) theta_{t-1} - eta M_t / sqrt(S_t) on matrices and vectors, against the
+    oracle (decay, then Algorithm 2); lambda = 0 is bit-identical to a context stepped without the field."""
+    w = W.Workload("wd", [(130, 520), (64, 1024), (33, 77), (700,), (20000,)], W.GRAD_BF16, seed=71, steps=20,
+                   grad_kind="normal", scale_range=(1e-3, 1e-1))
+    _run(w, 20, TOL_100, check_every=5, hyper=P.CameHyper(weight_decay=0.1), tile_rows=32)
+    gen = W.Generator(w, device="cuda:0")
+    a, b = P.CameStep(w.shapes, [1] * 5, tile_rows=32), P.CameStep(w.shapes, [1] * 5, tile_rows=32)
+    ta, tb = [gen.theta0(i) for i in range(5)], [gen.theta0(i) for i in range(5)]
+    for t in range(1, 4):
+        g = [gen.grad(i, t) for i in range(5)]
+        a.step(ta, g, P.CameHyper(), 1e-2, t)
+        b.step(tb, g, P.CameHyper(weight_decay=0.5 if t == 3 else 0.0), 1e-2, t)
+    torch.cuda.synchronize()
+    for k in range(5):
+        assert torch.equal(a.state_view(k)["M"], b.state_view(k)["M"])   # the decay does not enter the statistics
+        assert not torch.equal(ta[k], tb[k])
+    with pytest.raises(P.CameError) as e:
+        a.step(ta, g, P.CameHyper(weight_decay=-0.1), 1e-2, 4)
+    assert e.value.status == -1
+    a.close(); b.close()
+
+
+@pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["f32", "bf16"])
+def test_vectors_updated_by_momentum_only(dtype):
+    """Option CAME_VECTOR_MOMENTUM_ONLY: 1-D parameters (short and long) move by -eta M_t and keep s = 0,
+    matrices follow Algorithm 2 as before."""
+    w = W.Workload("vmo", [(130, 520), (700,), (5,), (40000,), (64, 64)], dtype, seed=72, steps=12,
+                   grad_kind="normal", scale_range=(1e-3, 1e-1))
+    sbs = SideBySide(w, vector_confidence=False, tile_rows=32)
+    try:
+        for t in range(1, 13):
+            sbs.step()
+            sbs.assert_within(TOL_1 if t == 1 else TOL_100)
+        for k, s in enumerate(w.shapes):
+            if len(s) == 1:
+                assert not sbs.opt.state_view(k)["R"].any()
+            else:
+                assert sbs.opt.state_view(k)["R"].all()
+    finally:
+        sbs.close()
