@@ -925,7 +925,7 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
                 sP += rowpart[base]; sQ += rowpart[base + tm.n]; sW += rowpart[base + 2 * tm.n];
             }
             double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
-            U = fmax(U, 0.0);
+            U = U < 0.0 ? 0.0 : U;  // rounding of the three-term sum; a NaN stays a NaN
             U += static_cast<double>(tm.m) * h.eps2;
             const float Rn = static_cast<float>(h.beta3 * static_cast<double>(R[idx]) + h.one_minus_beta3 * U);
             R[idx] = Rn;
@@ -954,7 +954,7 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
             sQ = (colsum[1][0][l] + colsum[1][1][l]) + (colsum[1][2][l] + colsum[1][3][l]);
             sW = (colsum[2][0][l] + colsum[2][1][l]) + (colsum[2][2][l] + colsum[2][3][l]);
             double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
-            U = fmax(U, 0.0);
+            U = U < 0.0 ? 0.0 : U;  // rounding of the three-term sum; a NaN stays a NaN
             U += static_cast<double>(tm.n) * h.eps2;
             C[fc.col] = static_cast<float>(h.beta3 * static_cast<double>(C[fc.col]) + h.one_minus_beta3 * U);
         }

@@ -528,3 +528,48 @@ def test_vectors_updated_by_momentum_only(dtype):
                 assert sbs.opt.state_view(k)["R"].all()
     finally:
         sbs.close()
+
+
+def test_non_finite_gradient_stays_in_its_tensor():
+    """A NaN or Inf in one tensor's gradient propagates through that tensor exactly as Algorithm 2's
+    arithmetic does in the oracle (same entries non-finite, the finite ones within tolerance) and
+    leaves every other tensor of the grouped launches bit-identical to a clean run."""
+    from oracle import came_oracle as O
+    from parity_util import to_f64
+    shapes = [(70, 520), (64, 1024), (600,), (33, 40), (20000,)]
+    w = W.Workload("nonfinite", shapes, W.GRAD_F32, seed=81, steps=2, grad_kind="normal", scale_range=(1e-2, 1e-1))
+    gen = W.Generator(w, device="cuda:0")
+    clean, dirty = P.CameStep(shapes, [0] * 5, tile_rows=32), P.CameStep(shapes, [0] * 5, tile_rows=32)
+    tc, td = [gen.theta0(i) for i in range(5)], [gen.theta0(i) for i in range(5)]
+    otl = O.TensorList(shapes, [to_f64(t) for t in td])
+    oh = O.Hyper(lr=w.lr)
+    for t in (1, 2):
+        g = [gen.grad(i, t) for i in range(5)]
+        gd = [x.clone() for x in g]
+        if t == 2:
+            gd[1][5, 700] = float("nan")
+            gd[2][17] = float("inf")
+        clean.step(tc, g, P.CameHyper(), w.lr, t)
+        dirty.step(td, gd, P.CameHyper(), w.lr, t)
+        otl.step([to_f64(x) for x in gd], oh)
+    torch.cuda.synchronize()
+    for k in (0, 3, 4):
+        assert torch.equal(tc[k], td[k])
+        for q, a in clean.state_view(k).items():
+            assert a is None or torch.equal(a, dirty.state_view(k)[q])
+    for k in (1, 2):
+        sv, st = dirty.state_view(k), otl.state[k]
+        pairs = [("theta", to_f64(td[k]), otl.theta[k]), ("M", to_f64(sv["M"]), st.M)]
+        if k == 1:
+            pairs += [(q, to_f64(sv[q]), getattr(st, q)) for q in "rcRC"]
+        else:
+            pairs += [("v", to_f64(sv["r"]), st.v), ("s", to_f64(sv["R"]), st.s)]
+        for name, got, ref in pairs:
+            assert np.array_equal(np.isfinite(got), np.isfinite(ref)), f"tensor {k} {name}: different entries are non-finite"
+            fin = np.isfinite(ref)
+            if fin.any():
+                scale = np.abs(ref[fin]) + np.sqrt(np.mean(ref[fin] ** 2))
+                assert np.max(np.abs(got[fin] - ref[fin]) / scale) <= 1e-5, f"tensor {k} {name}"
+    assert not torch.isfinite(td[1]).any()            # one NaN reaches the whole matrix through the sum of r
+    assert torch.isfinite(td[2]).sum().item() == 599  # the vector loses only the entry that was Inf
+    clean.close(); dirty.close()

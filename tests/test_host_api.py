@@ -158,3 +158,38 @@ def test_init_rejects_short_or_misaligned_blobs_before_touching_the_device():
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(ImportError):
         P.load_library(str(tmp_path / "nope.so"))
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """include/came.h compiles as strict C99 and a C program can call the host-only entry points."""
+    import subprocess
+    src = tmp_path / "use_came.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "came.h"
+int main(void)
+{
+    came_tensor_desc d[2] = {{4096, 4096, 2, CAME_GRAD_BF16}, {4096, 1, 1, CAME_GRAD_BF16}};
+    came_options o = {0};
+    size_t state = 0, scratch = 0;
+    int rc = came_state_size(d, 2, &o, &state, &scratch);
+    if (rc != CAME_OK) { printf("error %s\n", came_strerror(rc)); return 1; }
+    o.momentum_dtype = CAME_MOMENTUM_BF16;
+    size_t state16 = 0;
+    rc = came_state_size(d, 2, &o, &state16, &scratch);
+    if (rc != CAME_OK) return 2;
+    d[0].ndim = 3;
+    if (came_state_size(d, 2, NULL, &state, &scratch) != CAME_EINVAL) return 3;
+    printf("%zu %zu %.0f %s\n", state, state16, came_algorithmic_bytes(2, 4, CAME_ALGO_CAME, 0), came_strerror(CAME_EALIGN));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_came"
+    libdir = os.path.dirname(B._LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-lcame_hip", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    f32_state = 4 * (4096 * 4096 + 4 * 4096 + 3 * 4096)
+    assert int(out[0]) == f32_state and int(out[1]) == f32_state - 2 * (4096 * 4096 + 4096)
+    assert out[2] == "26"
