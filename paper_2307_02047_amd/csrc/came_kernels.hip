@@ -486,6 +486,26 @@ __device__ __forceinline__ int64_t load_col(const TileGeom& t, int cb)
     else return t.ncol > 0 ? t.col : static_cast<int64_t>(cb) * kTileCols;
 }
 
+// Which work item a workgroup of a sweep launch takes.  The dispatcher deals consecutive
+// workgroups round-robin to the 8 XCDs (workgroup b runs on XCD b % 8), each with its own L2
+// and translation cache.  Taking items in launch order would spread every 8 neighbouring
+// tiles over all XCDs; instead XCD x works through the chunks x, x+8, x+16, ... of kXcdChunk
+// consecutive tiles, so that each XCD streams through compact address ranges (measured on the
+// Llama-shaped list: sweep 2 3 % faster, sweep 3 1 %; one contiguous eighth per XCD is as good
+// there but unbalances short launches).  A bijection on [0, n) whatever the hardware does.
+#ifndef CAME_XCD_CHUNK
+#define CAME_XCD_CHUNK 64
+#endif
+constexpr int32_t kXcds = 8, kXcdChunk = CAME_XCD_CHUNK;
+
+__device__ __forceinline__ int32_t xcd_item(int32_t b, int32_t n)
+{
+    const int32_t whole = n / (kXcds * kXcdChunk) * (kXcds * kXcdChunk);
+    if (b >= whole) return b;  // the launch's ragged end keeps launch order
+    const int32_t x = b % kXcds, j = b / kXcds;
+    return ((j / kXcdChunk) * kXcds + x) * kXcdChunk + j % kXcdChunk;
+}
+
 // ---------------------------------------------------------------- sweep 1
 
 #ifndef CAME_ROWS1
@@ -586,7 +606,7 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             vector_item(tb, vec_begin + (blockIdx.x - ntile), h, fh, reinterpret_cast<double*>(lds)); \
             return;                                                                                 \
         }                                                                                           \
-        const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
+        const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, ntile)];                     \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
@@ -854,7 +874,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         __shared__ double lds[kWaves * kTileCols];                                                  \
         __shared__ double lds4[4];                                                                  \
         extern __shared__ double rowbuf_f64[];                                                      \
-        const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
+        const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];                 \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
         float* rowfac = reinterpret_cast<float*>(rowbuf_f64 + 3 * tm.tile_rows);                    \
@@ -1090,7 +1110,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     void NAME(DeviceTables tb, int32_t item_begin, SweepHyper h)                                    \
     {                                                                                               \
         extern __shared__ float rowfac_f32[];                                                       \
-        const WorkItem it = tb.items[item_begin + blockIdx.x];                                      \
+        const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];                 \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
