@@ -95,6 +95,9 @@ def main() -> int:
     ap.add_argument("--momentum-dtype", choices=("f32", "bf16"), default="f32",
                     help="storage type of the momentum M between steps (f32: the configuration the metric is "
                          "quoted on; bf16: the reduced-precision-momentum variant, 6 bytes per parameter less)")
+    ap.add_argument("--grad-dtype", choices=("workload", "f32", "bf16"), default="workload",
+                    help="gradient storage type: the workload's own (default), or overridden to see the other "
+                         "kernel variants at the same shapes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0)
     ap.add_argument("--no-placement", action="store_true",
@@ -128,6 +131,9 @@ def main() -> int:
                           "launches": 4}), flush=True)
         return 0
     w = W.by_name(args.workload)
+    if args.grad_dtype != "workload":
+        import dataclasses
+        w = dataclasses.replace(w, grad_dtype=W.GRAD_F32 if args.grad_dtype == "f32" else W.GRAD_BF16)
     gen = W.Generator(w, device=dev)
     n = len(w.shapes)
     hyper = P.CameHyper()
@@ -193,7 +199,8 @@ def main() -> int:
         "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS,
         "traffic": read_traffic(os.path.join(
-            ROOT, "profiles", f"sweep3_{args.workload}{'_bf16_momentum' if mbytes == 2 else ''}_traffic.txt")),
+            ROOT, "profiles", f"sweep3_{args.workload}{'_bf16_momentum' if mbytes == 2 else ''}_traffic.txt"))
+        if args.grad_dtype == "workload" else None,
         "bytes_per_launch": s3_bytes,
         "avg_launch_ms": s3_avg_ms,
         "whole_step": {
