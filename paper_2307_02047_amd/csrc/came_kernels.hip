@@ -42,15 +42,29 @@ using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bits_to_float(uint32_t b) { return __uint_as_float(b); }
 
+// The caller's parameter and gradient addresses reach the kernels through a pointer table in
+// device memory, so the compiler cannot know they are global-memory addresses and would use
+// FLAT loads and stores for them.  Those count against the LDS counter as well and may
+// complete out of order, so every wait on one of them (and every wait for an LDS read while
+// one is in flight) becomes a wait for ALL outstanding memory operations -- which undoes the
+// software prefetch of the sweeps.  Every access to a caller's buffer therefore goes through a
+// pointer in the global address space (what the host guarantees anyway: device memory).
+#define CAME_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ CAME_GLOBAL T* glob(T* p)
+{
+    return (CAME_GLOBAL T*)p;
+}
+
 // ---------------------------------------------------------------- loads / stores
 
 template <bool BF16>
 __device__ __forceinline__ float load_grad1(const void* g, int64_t idx)
 {
     if constexpr (BF16)
-        return bits_to_float(static_cast<uint32_t>(static_cast<const uint16_t*>(g)[idx]) << 16);
+        return bits_to_float(static_cast<uint32_t>(glob(static_cast<const uint16_t*>(g))[idx]) << 16);
     else
-        return static_cast<const float*>(g)[idx];
+        return glob(static_cast<const float*>(g))[idx];
 }
 
 // A lane's 8 consecutive entries of one row, as they sit in memory.  Kept packed
@@ -62,7 +76,9 @@ template <> struct GradRaw<false> { f32x4 a, b; };   // 8 binary32
 struct F32Raw { f32x4 a, b; };
 
 // ALIGNED: every row starts 16-byte aligned (m % 8 == 0) and ncol is 0 or 8: vector
-// accesses.  Otherwise element-wise accesses with per-column bounds.
+// accesses.  Otherwise the address is only element-aligned: lanes whose 8 columns all exist
+// copy them in one go (the compiler chooses the access width the alignment allows), the lane
+// at the matrix's right edge goes element by element with bounds.
 // NT: non-temporal (streaming) loads, for data read once per sweep and never written.
 template <bool BF16, bool ALIGNED, bool NT = true>
 __device__ __forceinline__ GradRaw<BF16> load_grad_raw(const void* g, int64_t idx, int ncol)
@@ -70,14 +86,18 @@ __device__ __forceinline__ GradRaw<BF16> load_grad_raw(const void* g, int64_t id
     GradRaw<BF16> r;
     if constexpr (BF16) {
         r.v = u32x4{0u, 0u, 0u, 0u};
-        const uint16_t* p = static_cast<const uint16_t*>(g) + idx;
+        const CAME_GLOBAL uint16_t* p = glob(static_cast<const uint16_t*>(g)) + idx;
         if constexpr (ALIGNED) {
             // gradients are read once per sweep and never written: stream them (measured: sweep 2
             // 6 % faster; the same hint on the M / theta loads or on the stores is slower)
             if (ncol > 0) {
-                if constexpr (NT) r.v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-                else r.v = *reinterpret_cast<const u32x4*>(p);
+                if constexpr (NT) r.v = __builtin_nontemporal_load((const CAME_GLOBAL u32x4*)p);
+                else r.v = *(const CAME_GLOBAL u32x4*)p;
             }
+        } else if (ncol == kLaneCols) {
+            // all 8 entries exist but the address is only element-aligned: a plain copy lets the
+            // compiler pick the widest access the target allows for that alignment
+            __builtin_memcpy(&r.v, (const void*)p, sizeof(r.v));
         } else {
             uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -88,17 +108,20 @@ __device__ __forceinline__ GradRaw<BF16> load_grad_raw(const void* g, int64_t id
     } else {
         r.a = f32x4{0.f, 0.f, 0.f, 0.f};
         r.b = r.a;
-        const float* p = static_cast<const float*>(g) + idx;
+        const CAME_GLOBAL float* p = glob(static_cast<const float*>(g)) + idx;
         if constexpr (ALIGNED) {
             if (ncol > 0) {
                 if constexpr (NT) {
-                    r.a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-                    r.b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + 1);
+                    r.a = __builtin_nontemporal_load((const CAME_GLOBAL f32x4*)p);
+                    r.b = __builtin_nontemporal_load((const CAME_GLOBAL f32x4*)p + 1);
                 } else {
-                    r.a = reinterpret_cast<const f32x4*>(p)[0];
-                    r.b = reinterpret_cast<const f32x4*>(p)[1];
+                    r.a = ((const CAME_GLOBAL f32x4*)p)[0];
+                    r.b = ((const CAME_GLOBAL f32x4*)p)[1];
                 }
             }
+        } else if (ncol == kLaneCols) {
+            __builtin_memcpy(&r.a, (const void*)p, sizeof(r.a));
+            __builtin_memcpy(&r.b, (const void*)(p + 4), sizeof(r.b));
         } else {
             float w[8];
 #pragma unroll
@@ -136,12 +159,15 @@ __device__ __forceinline__ F32Raw load_f32_raw(const float* base, int64_t idx, i
     F32Raw r;
     r.a = f32x4{0.f, 0.f, 0.f, 0.f};
     r.b = r.a;
-    const float* p = base + idx;
+    const CAME_GLOBAL float* p = glob(base) + idx;
     if constexpr (ALIGNED) {
         if (ncol > 0) {
-            r.a = reinterpret_cast<const f32x4*>(p)[0];
-            r.b = reinterpret_cast<const f32x4*>(p)[1];
+            r.a = ((const CAME_GLOBAL f32x4*)p)[0];
+            r.b = ((const CAME_GLOBAL f32x4*)p)[1];
         }
+    } else if (ncol == kLaneCols) {
+        __builtin_memcpy(&r.a, (const void*)p, sizeof(r.a));
+        __builtin_memcpy(&r.b, (const void*)(p + 4), sizeof(r.b));
     } else {
         float w[8];
 #pragma unroll
@@ -155,12 +181,16 @@ __device__ __forceinline__ F32Raw load_f32_raw(const float* base, int64_t idx, i
 template <bool ALIGNED>
 __device__ __forceinline__ void store_f32x8(float* base, int64_t idx, int ncol, const float (&x)[8])
 {
-    float* p = base + idx;
+    CAME_GLOBAL float* p = glob(base) + idx;
     if constexpr (ALIGNED) {
         if (ncol > 0) {
-            reinterpret_cast<f32x4*>(p)[0] = f32x4{x[0], x[1], x[2], x[3]};
-            reinterpret_cast<f32x4*>(p)[1] = f32x4{x[4], x[5], x[6], x[7]};
+            ((CAME_GLOBAL f32x4*)p)[0] = f32x4{x[0], x[1], x[2], x[3]};
+            ((CAME_GLOBAL f32x4*)p)[1] = f32x4{x[4], x[5], x[6], x[7]};
         }
+    } else if (ncol == kLaneCols) {
+        const f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
+        __builtin_memcpy((void*)p, &a, sizeof(a));
+        __builtin_memcpy((void*)(p + 4), &b, sizeof(b));
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -181,7 +211,7 @@ __device__ __forceinline__ uint32_t bf16_bits(float x)
 template <bool ALIGNED>
 __device__ __forceinline__ void store_bf16x8(void* base, int64_t idx, int ncol, const float (&x)[8])
 {
-    uint16_t* p = static_cast<uint16_t*>(base) + idx;
+    CAME_GLOBAL uint16_t* p = glob(static_cast<uint16_t*>(base)) + idx;
     if constexpr (ALIGNED) {
         if (ncol > 0) {
             u32x4 v;
@@ -189,8 +219,15 @@ __device__ __forceinline__ void store_bf16x8(void* base, int64_t idx, int ncol, 
             v.y = bf16_bits(x[2]) | (bf16_bits(x[3]) << 16);
             v.z = bf16_bits(x[4]) | (bf16_bits(x[5]) << 16);
             v.w = bf16_bits(x[6]) | (bf16_bits(x[7]) << 16);
-            *reinterpret_cast<u32x4*>(p) = v;
+            *(CAME_GLOBAL u32x4*)p = v;
         }
+    } else if (ncol == kLaneCols) {
+        u32x4 v;
+        v.x = bf16_bits(x[0]) | (bf16_bits(x[1]) << 16);
+        v.y = bf16_bits(x[2]) | (bf16_bits(x[3]) << 16);
+        v.z = bf16_bits(x[4]) | (bf16_bits(x[5]) << 16);
+        v.w = bf16_bits(x[6]) | (bf16_bits(x[7]) << 16);
+        __builtin_memcpy((void*)p, &v, sizeof(v));
     } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -216,13 +253,13 @@ __device__ __forceinline__ void store_mom(float* M, int64_t idx, int ncol, const
 
 __device__ __forceinline__ float load_mom1(const float* M, int64_t i, bool mb16)
 {
-    return mb16 ? bits_to_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(M)[i]) << 16) : M[i];
+    return mb16 ? bits_to_float(static_cast<uint32_t>(glob(reinterpret_cast<const uint16_t*>(M))[i]) << 16) : glob(M)[i];
 }
 
 __device__ __forceinline__ void store_mom1(float* M, int64_t i, bool mb16, float x)
 {
-    if (mb16) reinterpret_cast<uint16_t*>(M)[i] = static_cast<uint16_t>(bf16_bits(x));
-    else M[i] = x;
+    if (mb16) glob(reinterpret_cast<uint16_t*>(M))[i] = static_cast<uint16_t>(bf16_bits(x));
+    else glob(M)[i] = x;
 }
 
 // ---------------------------------------------------------------- reductions
@@ -366,12 +403,12 @@ __device__ void vector_update(const TensorMeta& tm, const void* __restrict__ g, 
             const float dU = uh - Mi;
             const float si = h.beta3 * s[i] + h.one_minus_beta3 * (dU * dU + h.eps2);
             s[i] = si;
-            tn = fmaf(theta[i], h.decay, -(h.lr * Mi * rsqrtf(si)));
+            tn = fmaf(glob(theta)[i], h.decay, -(h.lr * Mi * rsqrtf(si)));
         } else {
-            tn = fmaf(theta[i], h.decay, -(h.lr * Mi));
+            tn = fmaf(glob(theta)[i], h.decay, -(h.lr * Mi));
         }
-        theta[i] = tn;
-        if (theta16) theta16[i] = static_cast<uint16_t>(bf16_bits(tn));
+        glob(theta)[i] = tn;
+        if (theta16) glob(theta16)[i] = static_cast<uint16_t>(bf16_bits(tn));
     }
 }
 
@@ -429,12 +466,12 @@ __device__ void vector_pass2(const TensorMeta& tm, int chunk, const void* g, flo
             const float dU = uh - Mi;
             const float si = h.beta3 * s[i] + h.one_minus_beta3 * (dU * dU + h.eps2);
             s[i] = si;
-            tn = fmaf(theta[i], h.decay, -(h.lr * Mi * rsqrtf(si)));
+            tn = fmaf(glob(theta)[i], h.decay, -(h.lr * Mi * rsqrtf(si)));
         } else {
-            tn = fmaf(theta[i], h.decay, -(h.lr * Mi));
+            tn = fmaf(glob(theta)[i], h.decay, -(h.lr * Mi));
         }
-        theta[i] = tn;
-        if (theta16) theta16[i] = static_cast<uint16_t>(bf16_bits(tn));
+        glob(theta)[i] = tn;
+        if (theta16) glob(theta16)[i] = static_cast<uint16_t>(bf16_bits(tn));
     }
 }
 
@@ -609,11 +646,12 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, ntile)];                     \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
+        const void* g = tb.grad[it.tensor];                    \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
         if (!ALIGNED || full)                                                                       \
-            sweep1_tile<BF16, ALIGNED, true>(tm, it, t, tb.grad[it.tensor], tb.scratch, lds, rowbuf_f32); \
+            sweep1_tile<BF16, ALIGNED, true>(tm, it, t, g, tb.scratch, lds, rowbuf_f32);            \
         else                                                                                        \
-            sweep1_tile<BF16, ALIGNED, false>(tm, it, t, tb.grad[it.tensor], tb.scratch, lds, rowbuf_f32); \
+            sweep1_tile<BF16, ALIGNED, false>(tm, it, t, g, tb.scratch, lds, rowbuf_f32);           \
     }
 CAME_SWEEP1_KERNEL(sweep1_bf16_kernel, true, true, CAME_WAVES1)
 CAME_SWEEP1_KERNEL(sweep1_f32_kernel, false, true, 4)
@@ -751,11 +789,12 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         if constexpr (CAME_STATS) x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         return x;
     };
-    const WaveRows wr = wave_rows<kRows2>(t);
-    Row A[kRows2], B[kRows2];
+    constexpr int U = ALIGNED ? kRows2 : 1;  // element-wise loads: one row per batch (address registers)
+    const WaveRows wr = wave_rows<U>(t);
+    Row A[U], B[U];
     if (wr.nfull > 0) {
 #pragma unroll
-        for (int u = 0; u < kRows2; ++u) A[u] = load_row(u);
+        for (int u = 0; u < U; ++u) A[u] = load_row(u);
     }
 
     // 1^T r_t from the per-workgroup sums finalize 1 left (every wave, same order, same bits)
@@ -816,19 +855,19 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         for (int k = 0;; k += 2) {
             const int kb = min(k + 1, wr.nfull - 1);
 #pragma unroll
-            for (int u = 0; u < kRows2; ++u) B[u] = load_row(kb * kRows2 + u);
+            for (int u = 0; u < U; ++u) B[u] = load_row(kb * U + u);
 #pragma unroll
-            for (int u = 0; u < kRows2; ++u) consume_row(A[u], k * kRows2 + u);
+            for (int u = 0; u < U; ++u) consume_row(A[u], k * U + u);
             if (k + 1 >= wr.nfull) break;
             const int ka = min(k + 2, wr.nfull - 1);
 #pragma unroll
-            for (int u = 0; u < kRows2; ++u) A[u] = load_row(ka * kRows2 + u);
+            for (int u = 0; u < U; ++u) A[u] = load_row(ka * U + u);
 #pragma unroll
-            for (int u = 0; u < kRows2; ++u) consume_row(B[u], (k + 1) * kRows2 + u);
+            for (int u = 0; u < U; ++u) consume_row(B[u], (k + 1) * U + u);
             if (k + 2 >= wr.nfull) break;
         }
     }
-    for (int j = wr.nfull * kRows2; j < wr.cnt; ++j) consume_row(load_row(j), j);
+    for (int j = wr.nfull * U; j < wr.cnt; ++j) consume_row(load_row(j), j);
 
     // column sums across the 4 waves, one statistic at a time through 16 KB of LDS
     if constexpr (!CAME_STATS) __syncthreads();
@@ -878,22 +917,23 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
         float* rowfac = reinterpret_cast<float*>(rowbuf_f64 + 3 * tm.tile_rows);                    \
+        const void* g = tb.grad[it.tensor];                    \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
         if (!ALIGNED || full)                                                                       \
-            sweep2_tile<BF16, ALIGNED, true, STATS, MB16>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch, \
+            sweep2_tile<BF16, ALIGNED, true, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch,       \
                                              tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
         else                                                                                        \
-            sweep2_tile<BF16, ALIGNED, false, STATS, MB16>(tm, it, t, tb.grad[it.tensor], tb.state, tb.scratch, \
+            sweep2_tile<BF16, ALIGNED, false, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch,      \
                                               tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
     }
 CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, true, false, CAME_WAVES2)
 CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, true, false, 2)
-CAME_SWEEP2_KERNEL(sweep2_bf16_unaligned_kernel, true, false, true, false, 2)
-CAME_SWEEP2_KERNEL(sweep2_f32_unaligned_kernel, false, false, true, false, 2)
+CAME_SWEEP2_KERNEL(sweep2_bf16_unaligned_kernel, true, false, true, false, 3)
+CAME_SWEEP2_KERNEL(sweep2_f32_unaligned_kernel, false, false, true, false, 3)
 CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_kernel, true, true, true, true, CAME_WAVES2)
 CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_kernel, false, true, true, true, 2)
-CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_unaligned_kernel, true, false, true, true, 2)
-CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_unaligned_kernel, false, false, true, true, 2)
+CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_unaligned_kernel, true, false, true, true, 3)
+CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_unaligned_kernel, false, false, true, true, 3)
 // Algorithm 1: M is not read, so its storage type does not matter here
 CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_kernel, true, true, false, false, 8)
 CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_kernel, false, true, false, false, 8)
@@ -1018,11 +1058,14 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         x.th = load_f32_raw<ALIGNED>(theta, idx, lncol);
         return x;
     };
-    const WaveRows wr = wave_rows<kRows3>(t);
-    Row A[kRows3], B[kRows3];
+    // element-wise loads (unaligned rows) need far more address registers per row in flight:
+    // one row per batch there
+    constexpr int U = ALIGNED ? kRows3 : 1;
+    const WaveRows wr = wave_rows<U>(t);
+    Row A[U], B[U];
     if (wr.nfull > 0) {
 #pragma unroll
-        for (int u = 0; u < kRows3; ++u) A[u] = load_row(u);
+        for (int u = 0; u < U; ++u) A[u] = load_row(u);
     }
 
     // 1^T R_t from the per-workgroup sums finalize 2 left (every wave, same order, same bits)
@@ -1087,19 +1130,19 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         for (int k = 0;; k += 2) {
             const int kb = min(k + 1, wr.nfull - 1);
 #pragma unroll
-            for (int u = 0; u < kRows3; ++u) B[u] = load_row(kb * kRows3 + u);
+            for (int u = 0; u < U; ++u) B[u] = load_row(kb * U + u);
 #pragma unroll
-            for (int u = 0; u < kRows3; ++u) consume_row(A[u], k * kRows3 + u);
+            for (int u = 0; u < U; ++u) consume_row(A[u], k * U + u);
             if (k + 1 >= wr.nfull) break;
             const int ka = min(k + 2, wr.nfull - 1);
 #pragma unroll
-            for (int u = 0; u < kRows3; ++u) A[u] = load_row(ka * kRows3 + u);
+            for (int u = 0; u < U; ++u) A[u] = load_row(ka * U + u);
 #pragma unroll
-            for (int u = 0; u < kRows3; ++u) consume_row(B[u], (k + 1) * kRows3 + u);
+            for (int u = 0; u < U; ++u) consume_row(B[u], (k + 1) * U + u);
             if (k + 2 >= wr.nfull) break;
         }
     }
-    for (int j = wr.nfull * kRows3; j < wr.cnt; ++j) consume_row(load_row(j), j);
+    for (int j = wr.nfull * U; j < wr.cnt; ++j) consume_row(load_row(j), j);
 }
 
 #ifndef CAME_WAVES3
@@ -1114,9 +1157,9 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
-        float* theta = static_cast<float*>(tb.theta[it.tensor]);                                    \
-        void* theta16 = tb.theta16[it.tensor];                                                      \
-        const void* g = tb.grad[it.tensor];                                                         \
+        float* theta = static_cast<float*>(tb.theta[it.tensor]);                         \
+        void* theta16 = tb.theta16[it.tensor];                       \
+        const void* g = tb.grad[it.tensor];                    \
         const TensorScalars* sc = tb.scalars + it.tensor;                                           \
         if (!ALIGNED || full) {                                                                     \
             if (theta16) sweep3_tile<BF16, ALIGNED, true, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
@@ -1128,15 +1171,15 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     }
 CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, false, CAME_WAVES3)
 CAME_SWEEP3_KERNEL(sweep3_f32_kernel, false, true, false, 3)
-CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, false, 2)
-CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, false, 2)
+CAME_SWEEP3_KERNEL(sweep3_bf16_unaligned_kernel, true, false, false, 4)
+CAME_SWEEP3_KERNEL(sweep3_f32_unaligned_kernel, false, false, false, 4)
 #ifndef CAME_WAVES3M
 #define CAME_WAVES3M CAME_WAVES3
 #endif
 CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_kernel, true, true, true, CAME_WAVES3M)
 CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_kernel, false, true, true, 3)
-CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_unaligned_kernel, true, false, true, 2)
-CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_unaligned_kernel, false, false, true, 2)
+CAME_SWEEP3_KERNEL(sweep3_bf16_mbf16_unaligned_kernel, true, false, true, 4)
+CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_unaligned_kernel, false, false, true, 4)
 
 // ---------------------------------------------------------------- placement probe
 
@@ -1156,8 +1199,8 @@ __global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTable
     if (tm.flags & kFlagBf16Momentum) {
         for (int i = t.wave; i < t.nrows; i += kWaves) {
             const int64_t idx = (t.row0 + i) * tm.m + t.col;
-            u32x4* pm = reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(M) + idx);
-            f32x4* pt = reinterpret_cast<f32x4*>(theta + idx);
+            CAME_GLOBAL u32x4* pm = (CAME_GLOBAL u32x4*)(glob(reinterpret_cast<uint16_t*>(M)) + idx);
+            CAME_GLOBAL f32x4* pt = (CAME_GLOBAL f32x4*)(glob(theta) + idx);
             u32x4 m0 = pm[0];
             f32x4 t0 = pt[0], t1 = pt[1];
             asm volatile("" : "+v"(m0), "+v"(t0), "+v"(t1));
@@ -1167,8 +1210,8 @@ __global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTable
     }
     for (int i = t.wave; i < t.nrows; i += kWaves) {
         const int64_t idx = (t.row0 + i) * tm.m + t.col;
-        f32x4* pm = reinterpret_cast<f32x4*>(M + idx);
-        f32x4* pt = reinterpret_cast<f32x4*>(theta + idx);
+        CAME_GLOBAL f32x4* pm = (CAME_GLOBAL f32x4*)(glob(M) + idx);
+        CAME_GLOBAL f32x4* pt = (CAME_GLOBAL f32x4*)(glob(theta) + idx);
         f32x4 m0 = pm[0], m1 = pm[1], t0 = pt[0], t1 = pt[1];
         // opaque to the optimiser, so that the stores of just-loaded values are kept
         asm volatile("" : "+v"(m0), "+v"(m1), "+v"(t0), "+v"(t1));
