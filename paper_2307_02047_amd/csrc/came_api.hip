@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -158,6 +159,20 @@ int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* gr
     return CAME_OK;
 }
 
+// Host allocations inside the library (std::vector, new) may throw; nothing may leave through
+// the C boundary.
+template <class F>
+int guarded(F body) noexcept
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return CAME_ENOMEM;
+    } catch (...) {
+        return CAME_EINVAL;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -165,32 +180,36 @@ extern "C" {
 int came_state_size(const came_tensor_desc* descs, int32_t count, const came_options* opts,
                     size_t* state_bytes, size_t* scratch_bytes)
 {
-    if (!state_bytes || !scratch_bytes) return CAME_EINVAL;
-    Plan plan;
-    const int rc = build_plan(descs, count, opts, &plan);
-    if (rc != CAME_OK) return rc;
-    *state_bytes = plan.state_bytes;
-    *scratch_bytes = plan.scratch_bytes;
-    return CAME_OK;
+    return guarded([&]() -> int {
+        if (!state_bytes || !scratch_bytes) return CAME_EINVAL;
+        Plan plan;
+        const int rc = build_plan(descs, count, opts, &plan);
+        if (rc != CAME_OK) return rc;
+        *state_bytes = plan.state_bytes;
+        *scratch_bytes = plan.scratch_bytes;
+        return CAME_OK;
+    });
 }
 
 int came_plan_query(const came_tensor_desc* descs, int32_t count, const came_options* opts,
                     int64_t out[8])
 {
-    if (!out) return CAME_EINVAL;
-    Plan plan;
-    const int rc = build_plan(descs, count, opts, &plan);
-    if (rc != CAME_OK) return rc;
-    const int64_t tiles = static_cast<int64_t>(plan.items.size());
-    out[0] = plan.tile_rows;
-    out[1] = kTileCols;
-    out[2] = tiles;
-    out[3] = static_cast<int64_t>(plan.fins.size());
-    out[4] = static_cast<int64_t>(plan.groups.size());
-    out[5] = plan.n_matrices;
-    out[6] = plan.n_vectors;
-    out[7] = plan.total_elements;
-    return CAME_OK;
+    return guarded([&]() -> int {
+        if (!out) return CAME_EINVAL;
+        Plan plan;
+        const int rc = build_plan(descs, count, opts, &plan);
+        if (rc != CAME_OK) return rc;
+        const int64_t tiles = static_cast<int64_t>(plan.items.size());
+        out[0] = plan.tile_rows;
+        out[1] = kTileCols;
+        out[2] = tiles;
+        out[3] = static_cast<int64_t>(plan.fins.size());
+        out[4] = static_cast<int64_t>(plan.groups.size());
+        out[5] = plan.n_matrices;
+        out[6] = plan.n_vectors;
+        out[7] = plan.total_elements;
+        return CAME_OK;
+    });
 }
 
 double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which)
@@ -226,55 +245,51 @@ int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count
                     const came_options* opts, void* state_dev, size_t state_bytes,
                     void* scratch_dev, size_t scratch_bytes, void* hip_stream)
 {
-    if (!out) return CAME_EINVAL;
-    *out = nullptr;
-    if (!state_dev || !scratch_dev) return CAME_EINVAL;
-    came_ctx* ctx = new (std::nothrow) came_ctx();
-    if (!ctx) return CAME_ENOMEM;
-    int rc = build_plan(descs, count, opts, &ctx->plan);
-    if (rc != CAME_OK) { delete ctx; return rc; }
-    const Plan& p = ctx->plan;
-    if (state_bytes < p.state_bytes || scratch_bytes < p.scratch_bytes) { delete ctx; return CAME_ESIZE; }
-    if (!aligned_to(state_dev, 256) || !aligned_to(scratch_dev, 256)) { delete ctx; return CAME_EALIGN; }
-    ctx->state = static_cast<float*>(state_dev);
-    ctx->scratch = static_cast<char*>(scratch_dev);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return guarded([&]() -> int {
+        if (!out) return CAME_EINVAL;
+        *out = nullptr;
+        if (!state_dev || !scratch_dev) return CAME_EINVAL;
+        // owned here until handed over: every early return (and a throwing allocation) releases
+        // the events, the pinned staging memory and the context itself through came_destroy
+        std::unique_ptr<came_ctx, void (*)(came_ctx*)> owner(new (std::nothrow) came_ctx(), came_destroy);
+        came_ctx* ctx = owner.get();
+        if (!ctx) return CAME_ENOMEM;
+        int rc = build_plan(descs, count, opts, &ctx->plan);
+        if (rc != CAME_OK) return rc;
+        const Plan& p = ctx->plan;
+        if (state_bytes < p.state_bytes || scratch_bytes < p.scratch_bytes) return CAME_ESIZE;
+        if (!aligned_to(state_dev, 256) || !aligned_to(scratch_dev, 256)) return CAME_EALIGN;
+        ctx->state = static_cast<float*>(state_dev);
+        ctx->scratch = static_cast<char*>(scratch_dev);
+        hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-    hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), p.ptr_slot_bytes * kPtrSlots, hipHostMallocDefault);
-    if (e != hipSuccess) { delete ctx; return CAME_EHIP; }
-    for (int k = 0; k < kPtrSlots; ++k) {
-        e = hipEventCreateWithFlags(&ctx->slot_event[k], hipEventDisableTiming);
-        if (e != hipSuccess) {
-            for (int j = 0; j < k; ++j) (void)hipEventDestroy(ctx->slot_event[j]);
-            (void)hipHostFree(ctx->pinned);
-            delete ctx;
-            return CAME_EHIP;
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), p.ptr_slot_bytes * kPtrSlots, hipHostMallocDefault);
+        if (e != hipSuccess) { ctx->pinned = nullptr; return CAME_EHIP; }
+        for (int k = 0; k < kPtrSlots; ++k) {
+            e = hipEventCreateWithFlags(&ctx->slot_event[k], hipEventDisableTiming);
+            if (e != hipSuccess) { ctx->slot_event[k] = nullptr; return CAME_EHIP; }
         }
-    }
 
-    // plan tables -> scratch (synchronous copies from pageable memory), then zero the
-    // per-tensor scalars/counters and the optimizer state with fill kernels
-    auto fail = [&](hipError_t err) {
-        const int code = hip_fail(ctx, err);
-        came_destroy(ctx);
-        return code;
-    };
-    e = hipMemcpy(ctx->scratch + p.off_metas, p.metas.data(), sizeof(TensorMeta) * p.metas.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return fail(e);
-    if (!p.items.empty()) {
-        e = hipMemcpy(ctx->scratch + p.off_items, p.items.data(), sizeof(WorkItem) * p.items.size(), hipMemcpyHostToDevice);
-        if (e != hipSuccess) return fail(e);
-    }
-    if (!p.fins.empty()) {
-        e = hipMemcpy(ctx->scratch + p.off_fins, p.fins.data(), sizeof(FinalizeItem) * p.fins.size(), hipMemcpyHostToDevice);
-        if (e != hipSuccess) return fail(e);
-    }
-    e = launch_fill_zero_bytes(ctx->scratch + p.off_scalars, sizeof(TensorScalars) * p.descs.size(), s);
-    if (e != hipSuccess) return fail(e);
-    e = launch_fill_zero(ctx->state, p.state_bytes / sizeof(float), s);
-    if (e != hipSuccess) return fail(e);
-    *out = ctx;
-    return CAME_OK;
+        // plan tables -> scratch (synchronous copies from pageable memory), then zero the
+        // per-tensor scalars/counters and the optimizer state with fill kernels
+        e = hipMemcpy(ctx->scratch + p.off_metas, p.metas.data(), sizeof(TensorMeta) * p.metas.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return CAME_EHIP;
+        if (!p.items.empty()) {
+            e = hipMemcpy(ctx->scratch + p.off_items, p.items.data(), sizeof(WorkItem) * p.items.size(), hipMemcpyHostToDevice);
+            if (e != hipSuccess) return CAME_EHIP;
+        }
+        if (!p.fins.empty()) {
+            e = hipMemcpy(ctx->scratch + p.off_fins, p.fins.data(), sizeof(FinalizeItem) * p.fins.size(), hipMemcpyHostToDevice);
+            if (e != hipSuccess) return CAME_EHIP;
+        }
+        e = launch_fill_zero_bytes(ctx->scratch + p.off_scalars, sizeof(TensorScalars) * p.descs.size(), s);
+        if (e != hipSuccess) return CAME_EHIP;
+        e = launch_fill_zero(ctx->state, p.state_bytes / sizeof(float), s);
+        if (e != hipSuccess) return CAME_EHIP;
+        owner.release();
+        *out = ctx;
+        return CAME_OK;
+    });
 }
 
 static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
@@ -365,15 +380,19 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
 int came_step(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
               const came_hyper* hyper, double lr, int64_t step, void* hip_stream)
 {
-    return step_impl(ctx, theta_dev, grad_dev, nullptr, hyper, lr, step, hip_stream);
+    return guarded([&]() -> int {
+        return step_impl(ctx, theta_dev, grad_dev, nullptr, hyper, lr, step, hip_stream);
+    });
 }
 
 int came_step_bf16_copy(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
                         void* const* theta_bf16_dev, const came_hyper* hyper, double lr, int64_t step,
                         void* hip_stream)
 {
-    if (!theta_bf16_dev) return CAME_EINVAL;
-    return step_impl(ctx, theta_dev, grad_dev, theta_bf16_dev, hyper, lr, step, hip_stream);
+    return guarded([&]() -> int {
+        if (!theta_bf16_dev) return CAME_EINVAL;
+        return step_impl(ctx, theta_dev, grad_dev, theta_bf16_dev, hyper, lr, step, hip_stream);
+    });
 }
 
 int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
@@ -392,61 +411,63 @@ int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
 int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream, int32_t repeats,
                          double* gbytes_per_s)
 {
-    if (!ctx || !theta_dev || !gbytes_per_s || repeats < 1 || repeats > 1000) return CAME_EINVAL;
-    const Plan& p = ctx->plan;
-    const size_t count = p.descs.size();
-    for (size_t t = 0; t < count; ++t) {
-        if (!theta_dev[t]) return CAME_EINVAL;
-        if (!aligned_to(theta_dev[t], 16)) return CAME_EALIGN;
-    }
-    *gbytes_per_s = 0.0;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    // the probe reads no gradients: the pointer table's gradient half just repeats theta
-    std::vector<const void*> fake(theta_dev, theta_dev + count);
-    int rc = upload_pointers(ctx, theta_dev, fake.data(), nullptr, s, false);
-    if (rc != CAME_OK) return rc;
-    ctx->cached.clear();  // force a fresh table at the next came_step
-    const int used_slot = ctx->slot;
-    double bytes = 0.0;
-    for (const Group& g : p.groups)
-        for (int v = 0; v < kVariants; ++v) {
-            if (v & 2) continue;  // aligned variants only
-            for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
-                const TensorMeta& tm = p.metas[p.items[k].tensor];
-                const int64_t rows = std::min<int64_t>(tm.tile_rows, tm.n - int64_t(p.items[k].rb) * tm.tile_rows);
-                const int64_t cols = std::min<int64_t>(kTileCols, tm.m - int64_t(p.items[k].cb) * kTileCols);
-                // theta and M, read and written
-                bytes += ((tm.flags & kFlagBf16Momentum) ? 12.0 : 16.0) * static_cast<double>(rows * cols);
-            }
+    return guarded([&]() -> int {
+        if (!ctx || !theta_dev || !gbytes_per_s || repeats < 1 || repeats > 1000) return CAME_EINVAL;
+        const Plan& p = ctx->plan;
+        const size_t count = p.descs.size();
+        for (size_t t = 0; t < count; ++t) {
+            if (!theta_dev[t]) return CAME_EINVAL;
+            if (!aligned_to(theta_dev[t], 16)) return CAME_EALIGN;
         }
-    if (bytes == 0.0) return CAME_OK;
-    const DeviceTables tb = tables_for(ctx, used_slot);
-    hipEvent_t e0, e1;
-    hipError_t e = hipEventCreate(&e0);
-    if (e != hipSuccess) return hip_fail(ctx, e);
-    e = hipEventCreate(&e1);
-    if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(ctx, e); }
-    auto run_once = [&]() -> hipError_t {
+        *gbytes_per_s = 0.0;
+        hipStream_t s = static_cast<hipStream_t>(hip_stream);
+        // the probe reads no gradients: the pointer table's gradient half just repeats theta
+        std::vector<const void*> fake(theta_dev, theta_dev + count);
+        int rc = upload_pointers(ctx, theta_dev, fake.data(), nullptr, s, false);
+        if (rc != CAME_OK) return rc;
+        ctx->cached.clear();  // force a fresh table at the next came_step
+        const int used_slot = ctx->slot;
+        double bytes = 0.0;
         for (const Group& g : p.groups)
             for (int v = 0; v < kVariants; ++v) {
-                if (v & 2) continue;
-                const hipError_t le = launch_placement_probe(tb, g.var_begin[v], g.var_end[v], s);
-                if (le != hipSuccess) return le;
+                if (v & 2) continue;  // aligned variants only
+                for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
+                    const TensorMeta& tm = p.metas[p.items[k].tensor];
+                    const int64_t rows = std::min<int64_t>(tm.tile_rows, tm.n - int64_t(p.items[k].rb) * tm.tile_rows);
+                    const int64_t cols = std::min<int64_t>(kTileCols, tm.m - int64_t(p.items[k].cb) * kTileCols);
+                    // theta and M, read and written
+                    bytes += ((tm.flags & kFlagBf16Momentum) ? 12.0 : 16.0) * static_cast<double>(rows * cols);
+                }
             }
-        return hipSuccess;
-    };
-    e = run_once();  // warm-up
-    if (e == hipSuccess) e = hipEventRecord(e0, s);
-    for (int r = 0; r < repeats && e == hipSuccess; ++r) e = run_once();
-    if (e == hipSuccess) e = hipEventRecord(e1, s);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    if (e != hipSuccess) return hip_fail(ctx, e);
-    if (ms > 0.f) *gbytes_per_s = bytes * repeats / (static_cast<double>(ms) * 1e-3) / 1e9;
-    return CAME_OK;
+        if (bytes == 0.0) return CAME_OK;
+        const DeviceTables tb = tables_for(ctx, used_slot);
+        hipEvent_t e0, e1;
+        hipError_t e = hipEventCreate(&e0);
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        e = hipEventCreate(&e1);
+        if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(ctx, e); }
+        auto run_once = [&]() -> hipError_t {
+            for (const Group& g : p.groups)
+                for (int v = 0; v < kVariants; ++v) {
+                    if (v & 2) continue;
+                    const hipError_t le = launch_placement_probe(tb, g.var_begin[v], g.var_end[v], s);
+                    if (le != hipSuccess) return le;
+                }
+            return hipSuccess;
+        };
+        e = run_once();  // warm-up
+        if (e == hipSuccess) e = hipEventRecord(e0, s);
+        for (int r = 0; r < repeats && e == hipSuccess; ++r) e = run_once();
+        if (e == hipSuccess) e = hipEventRecord(e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+        if (e != hipSuccess) return hip_fail(ctx, e);
+        if (ms > 0.f) *gbytes_per_s = bytes * repeats / (static_cast<double>(ms) * 1e-3) / 1e9;
+        return CAME_OK;
+    });
 }
 
 int came_profile_enable(came_ctx* ctx, int32_t on)
@@ -458,24 +479,26 @@ int came_profile_enable(came_ctx* ctx, int32_t on)
 
 int came_profile_read(came_ctx* ctx, double phase_ms[6], int64_t phase_launches[6])
 {
-    if (!ctx || !phase_ms || !phase_launches) return CAME_EINVAL;
-    for (int k = 0; k < 6; ++k) { phase_ms[k] = 0.0; phase_launches[k] = 0; }
-    int rc = CAME_OK;
-    for (const came_ctx::Timed& t : ctx->timed) {
-        hipError_t e = hipEventSynchronize(t.stop);
-        float ms = 0.f;
-        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.start, t.stop);
-        if (e == hipSuccess) {
-            phase_ms[t.phase] += static_cast<double>(ms);
-            phase_launches[t.phase] += 1;
-        } else {
-            rc = hip_fail(ctx, e);
+    return guarded([&]() -> int {
+        if (!ctx || !phase_ms || !phase_launches) return CAME_EINVAL;
+        for (int k = 0; k < 6; ++k) { phase_ms[k] = 0.0; phase_launches[k] = 0; }
+        int rc = CAME_OK;
+        for (const came_ctx::Timed& t : ctx->timed) {
+            hipError_t e = hipEventSynchronize(t.stop);
+            float ms = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.start, t.stop);
+            if (e == hipSuccess) {
+                phase_ms[t.phase] += static_cast<double>(ms);
+                phase_launches[t.phase] += 1;
+            } else {
+                rc = hip_fail(ctx, e);
+            }
+            (void)hipEventDestroy(t.start);
+            (void)hipEventDestroy(t.stop);
         }
-        (void)hipEventDestroy(t.start);
-        (void)hipEventDestroy(t.stop);
-    }
-    ctx->timed.clear();
-    return rc;
+        ctx->timed.clear();
+        return rc;
+    });
 }
 
 int came_last_hip_error(const came_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
