@@ -223,7 +223,8 @@ class CameStep:
         if place_against is None:
             self.state, self.scratch, self._ctx = self._create()
             return
-        assert len(place_against) == n
+        if len(place_against) != n:
+            raise ValueError(f"place_against must hold the {n} parameter tensors, got {len(place_against)}")
         # Every candidate and spacer stays allocated until the search ends, so that each new
         # candidate really lies at a new place (a freed block would be handed out again).
         tried, spacers, best = [], [], None
@@ -288,7 +289,8 @@ class CameStep:
         a bfloat16 tensor of the parameter's shape or None)."""
         torch = self._torch
         n = len(self.shapes)
-        assert len(thetas) == n and len(grads) == n
+        if len(thetas) != n or len(grads) != n:
+            raise ValueError(f"expected {n} parameters and {n} gradients, got {len(thetas)} and {len(grads)}")
         for i in range(n):
             self._theta_arr[i] = thetas[i].data_ptr()
             self._grad_arr[i] = grads[i].data_ptr()
@@ -300,7 +302,8 @@ class CameStep:
                                         int(step), s)
                 what = "came_step"
             else:
-                assert len(bf16_copies) == n
+                if len(bf16_copies) != n:
+                    raise ValueError(f"expected {n} bf16 copy entries (tensor or None), got {len(bf16_copies)}")
                 arr = (ctypes.c_void_p * n)()
                 for i, c in enumerate(bf16_copies):
                     if c is not None:
