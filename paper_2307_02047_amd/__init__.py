@@ -7,3 +7,11 @@ memory and streams.
 from .binding import (CameHyper, CameStep, GRAD_BF16, GRAD_F32, ALGO_CAME, ALGO_ADAFACTOR,  # noqa: F401
                       MOMENTUM_F32, MOMENTUM_BF16, VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY, CameError, algorithmic_bytes, algorithmic_bytes_per_param,
                       load_library, plan_query, state_size)
+
+
+def __getattr__(name):
+    # torch is only needed for the optimizer front end; the C-ABI binding imports without it
+    if name == "CAME":
+        from .optim import CAME
+        return CAME
+    raise AttributeError(name)
