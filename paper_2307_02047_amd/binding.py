@@ -193,13 +193,15 @@ class CameStep:
 
     def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
                  group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32,
-                 vector_rule: int = VECTOR_ALGORITHM2, place_against=None, placement_candidates: int = 6,
-                 placement_spacer_bytes: int = 8 << 30, placement_accept_gbs: float = 5750.0):
+                 vector_rule: int = VECTOR_ALGORITHM2, place_against=None, placement_candidates: int = 8,
+                 placement_spacer_bytes: int = 16 << 30, placement_accept_gbs: float = 5750.0,
+                 placement_accept_ratio: float = 1.15):
         """place_against: the parameter tensors the context will be stepped with.  When given,
         the state blob is allocated at up to `placement_candidates` different addresses
         (separated by temporary spacer allocations), each is measured with
         came_probe_placement against the parameters, and the fastest is kept (the search stops
-        at the first candidate that reaches placement_accept_gbs): on MI355X the
+        at the first candidate that reaches placement_accept_gbs, or placement_accept_ratio times
+        the first candidate's rate): on MI355X the
         read+write sweep is ~15 % faster when theta and the state sit in different 96 GB
         regions of the HBM address space.  Memory is only allocated and measured here;
         nothing about the arithmetic changes."""
@@ -239,10 +241,16 @@ class CameStep:
             self.placement_log.append((k, gbs))
             if best is None or gbs > best[0]:
                 best = (gbs, cand)
-            if gbs >= placement_accept_gbs:
+            if gbs >= placement_accept_gbs or gbs >= placement_accept_ratio * self.placement_log[0][1]:
                 break
             try:
-                spacers.append(torch.empty(int(placement_spacer_bytes), dtype=torch.uint8, device=self.device))
+                # in pieces of at most 1 GiB: the allocator lays small allocations out one after the
+                # other, whereas a single huge spacer may be put somewhere else entirely
+                left = int(placement_spacer_bytes)
+                while left > 0:
+                    piece = min(left, 1 << 30)
+                    spacers.append(torch.empty(piece, dtype=torch.uint8, device=self.device))
+                    left -= piece
             except RuntimeError:
                 break
         if best is None:
