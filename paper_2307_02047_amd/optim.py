@@ -27,11 +27,13 @@ class CAME(torch.optim.Optimizer):
     momentum_dtype: "f32" or "bf16" (M stored as bfloat16 between steps).
     vector_confidence: False updates 1-D parameters by -eta*M (no confidence statistics).
     All of these are per parameter group.
+    place_state: search for a fast address of the state blob relative to the parameters at the
+    first step (see CameStep's place_against; temporarily allocates a lot of device memory).
     """
 
     def __init__(self, params, lr: float = 2e-4, betas=(0.9, 0.999, 0.9999), eps=(1e-30, 1e-16),
                  clip_threshold: float = 1.0, weight_decay: float = 0.0, algorithm: str = "came",
-                 momentum_dtype: str = "f32", vector_confidence: bool = True):
+                 momentum_dtype: str = "f32", vector_confidence: bool = True, place_state: bool = False):
         if algorithm not in ("came", "adafactor"):
             raise ValueError(f"algorithm must be 'came' or 'adafactor', got {algorithm!r}")
         if momentum_dtype not in ("f32", "bf16"):
@@ -40,6 +42,7 @@ class CAME(torch.optim.Optimizer):
                         weight_decay=weight_decay, algorithm=algorithm, momentum_dtype=momentum_dtype,
                         vector_confidence=vector_confidence)
         super().__init__(params, defaults)
+        self._place_state = bool(place_state)
         self._engines = {}  # index of the parameter group -> (CameStep, [params], step count)
 
     # ------------------------------------------------------------------ engine per group
@@ -63,7 +66,8 @@ class CAME(torch.optim.Optimizer):
         eng = CameStep([tuple(p.shape) if p.dim() > 0 else (1,) for p in ps], dts, device=ps[0].device,
                        algo=ALGO_CAME if group["algorithm"] == "came" else ALGO_ADAFACTOR,
                        momentum_dtype=MOMENTUM_BF16 if group["momentum_dtype"] == "bf16" else MOMENTUM_F32,
-                       vector_rule=VECTOR_ALGORITHM2 if group["vector_confidence"] else VECTOR_MOMENTUM_ONLY)
+                       vector_rule=VECTOR_ALGORITHM2 if group["vector_confidence"] else VECTOR_MOMENTUM_ONLY,
+                       place_against=[p.data for p in ps] if self._place_state else None)
         self._engines[gi] = [eng, list(ps), 0]
         for k, p in enumerate(ps):
             self.state[p] = self._views(eng, k, p, 0)

@@ -53,7 +53,7 @@ def test_training_loop_follows_the_oracle():
 
 def test_it_learns_a_fixed_batch():
     model = make_model(4)
-    opt = P.CAME(model.parameters(), lr=2e-3)
+    opt = P.CAME(model.parameters(), lr=2e-3, place_state=True)
     x, y = batch(0)
     losses = []
     for _ in range(60):
