@@ -194,7 +194,7 @@ class CameStep:
     def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
                  group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32,
                  vector_rule: int = VECTOR_ALGORITHM2, place_against=None, placement_candidates: int = 8,
-                 placement_spacer_bytes: int = 16 << 30, placement_accept_gbs: float = 5750.0,
+                 placement_spacer_bytes: int = 16 << 30, placement_accept_gbs: float = 5850.0,
                  placement_accept_ratio: float = 1.15):
         """place_against: the parameter tensors the context will be stepped with.  When given,
         the state blob is allocated at up to `placement_candidates` different addresses

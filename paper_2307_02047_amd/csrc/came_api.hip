@@ -362,7 +362,7 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
         if (e != hipSuccess) return hip_fail(ctx, e);
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, p.algo, p.tile_rows, g.var_begin[v], g.var_end[v], s); });
+            e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, p.algo, p.tile_rows, g.var_begin[v], g.var_end[v], p.reverse_sweep2, s); });
             if (e != hipSuccess) return hip_fail(ctx, e);
         }
         e = timed_launch(ctx, 3, s, [&] { return launch_finalize2(tb, g.fin_begin, g.fin_end, fh, s); });

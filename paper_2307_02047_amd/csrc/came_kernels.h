@@ -68,8 +68,9 @@ hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, 
 hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);
 // Sweep 2: row/column sums of u^2, u*M, M^2 and the per-tile sum of u^2 (Algorithm 1: the latter only).
+// reverse: take the tiles last to first (same results; see Plan::reverse_sweep2).
 hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t tile_rows,
-                         int32_t item_begin, int32_t item_end, hipStream_t s);
+                         int32_t item_begin, int32_t item_end, bool reverse, hipStream_t s);
 // Finalize 2: kappa (Eq. 1), R, C and the per-workgroup sums of R.
 hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);

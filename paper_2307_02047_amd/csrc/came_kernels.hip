@@ -908,12 +908,13 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #endif
 #define CAME_SWEEP2_KERNEL(NAME, BF16, ALIGNED, STATS, MB16, WAVES)                                             \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
-    void NAME(DeviceTables tb, int32_t item_begin)                                                  \
+    void NAME(DeviceTables tb, int32_t item_begin, int32_t reverse)                                 \
     {                                                                                               \
         __shared__ double lds[kWaves * kTileCols];                                                  \
         __shared__ double lds4[4];                                                                  \
         extern __shared__ double rowbuf_f64[];                                                      \
-        const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];                 \
+        const int32_t ord = xcd_item(blockIdx.x, gridDim.x);                                        \
+        const WorkItem it = tb.items[item_begin + (reverse ? static_cast<int32_t>(gridDim.x) - 1 - ord : ord)]; \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it);                                                       \
         float* rowfac = reinterpret_cast<float*>(rowbuf_f64 + 3 * tm.tile_rows);                    \
@@ -1302,29 +1303,30 @@ hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fi
 }
 
 hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t tile_rows,
-                         int32_t item_begin, int32_t item_end, hipStream_t s)
+                         int32_t item_begin, int32_t item_end, bool reverse, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const dim3 grid(item_end - item_begin), block(kWorkgroup);
     // three row statistics (double) and one row factor (float) per row of a tile
     const size_t dyn = (sizeof(double) * 3 + sizeof(float)) * static_cast<size_t>(tile_rows);
+    const int32_t rev = reverse ? 1 : 0;
     if (algo == CAME_ALGO_CAME) {
         switch (variant) {
-            case 0: sweep2_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 1: sweep2_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 2: sweep2_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 3: sweep2_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 4: sweep2_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 5: sweep2_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 6: sweep2_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            default: sweep2_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+            case 0: sweep2_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 1: sweep2_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 2: sweep2_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 3: sweep2_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 4: sweep2_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 5: sweep2_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 6: sweep2_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            default: sweep2_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
         }
     } else {
         switch (variant & 3) {
-            case 0: sweep2_adafactor_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 1: sweep2_adafactor_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            case 2: sweep2_adafactor_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
-            default: sweep2_adafactor_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+            case 0: sweep2_adafactor_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 1: sweep2_adafactor_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 2: sweep2_adafactor_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            default: sweep2_adafactor_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
         }
     }
     return hipGetLastError();

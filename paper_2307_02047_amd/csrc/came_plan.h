@@ -110,6 +110,11 @@ struct Plan {
     int32_t tile_rows = 0;
     int32_t algo = 0;
     int32_t momentum_dtype = 0;
+    // Sweep 2 walks the tiles backwards when the whole list is only a few times the 256 MB
+    // on-package cache: it then starts on the gradients sweep 1 read last and ends on the
+    // momenta sweep 3 reads first, both still cached (measured: -4 % per step on a
+    // 109M-parameter list, nothing on lists beyond 300M parameters, +0.3 % at 6.7B).
+    bool reverse_sweep2 = false;
     int64_t n_matrices = 0, n_vectors = 0, total_elements = 0;
     // state blob
     size_t state_bytes = 0;
