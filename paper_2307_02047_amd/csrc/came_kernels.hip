@@ -1,11 +1,13 @@
 // gfx950 kernels of the CAME step (Algorithm 2 of the CAME paper).
 //
-// One step is six grouped launches over ALL tensors of a group (the sweeps once per
+// One step is five grouped launches over ALL tensors of a group (the sweeps once per
 // kernel variant present: gradient dtype x aligned/unaligned rows x momentum dtype):
 //
-//   vectors    g, state     -> complete update of the 1-D parameters (one workgroup each;
-//                              vectors too long for that: two passes over chunks)
-//   sweep 1    g            -> row/column partial sums of g^2          (r_t, c_t lines)
+//   sweep 1    g            -> row/column partial sums of g^2          (r_t, c_t lines);
+//                              its last workgroups do the complete update of the 1-D
+//                              parameters, one workgroup each (a group without matrices
+//                              launches them alone; vectors too long for one workgroup
+//                              take two extra launches over chunks)
 //   finalize 1 partials     -> r_t, c_t, sqrt(1^T r_t)
 //   sweep 2    g, M_{t-1}   -> row/column partial sums of u^2, u M, M^2 with u = g / sqrt(v_t)
 //   finalize 2 partials     -> kappa = 1/max(1, RMS(u_t)/d) (Eq. 1), R_t, C_t, sqrt(1^T R_t)
