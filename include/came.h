@@ -179,6 +179,12 @@ int came_init_state(came_ctx **out, const came_tensor_desc *descs, int32_t count
  * lr is the learning rate eta; step is the 1-based iteration number t, which
  * is validated (must be >= 1) and recorded but, as in Algorithm 2, never used
  * in the arithmetic.  Asynchronous on hip_stream.
+ * Stream capture: a call whose parameter/gradient addresses are those of the previous call
+ * on this context only enqueues kernels and may be captured into a HIP graph (no memset
+ * nodes).  A call with a changed address has to wait for a free slot of the pointer table
+ * and copy from host staging memory; issued while hip_stream is capturing it is refused
+ * with CAME_EINVAL and nothing is recorded -- make one eager call with the final
+ * addresses first.  The phase timer must be off during capture.
  */
 int came_step(came_ctx *ctx, void *const *theta_dev, const void *const *grad_dev,
               const came_hyper *hyper, double lr, int64_t step, void *hip_stream);
@@ -196,7 +202,9 @@ int came_step_bf16_copy(came_ctx *ctx, void *const *theta_dev, const void *const
                         void *const *theta_bf16_dev, const came_hyper *hyper, double lr,
                         int64_t step, void *hip_stream);
 
-/* Device addresses of tensor i's state arrays (for checkpointing and tests). */
+/* Device addresses of tensor i's state arrays, for checkpointing and tests: the quantities
+ * Algorithm 2 carries from one iteration to the next -- m, r, c of its input list and the
+ * confidence statistics R, C of its last lines (both start at zero like r, c). */
 int came_state_view_get(const came_ctx *ctx, int32_t i, came_state_view *view);
 
 /*
@@ -209,37 +217,40 @@ int came_plan_query(const came_tensor_desc *descs, int32_t count, const came_opt
                     int64_t out[8]);
 
 /*
- * Algorithmic HBM bytes per parameter of the shipped three-sweep design for a
- * gradient element of `grad_bytes` bytes: sweep 1 reads g; sweep 2 reads g and
- * M; sweep 3 reads g, M, theta and writes M, theta  ->  20 + 3*grad_bytes.
- * which: 0 = whole step, 1/2/3 = that sweep alone.
- */
-double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which);
-
-/*
- * The same count for any mode: momentum_bytes 4 or 2 (came_momentum_dtype), algo a
+ * Algorithmic HBM bytes per parameter of the shipped three-sweep design (the count the
+ * roofline fraction is priced with; derived from the dependency chain of Algorithm 2:
+ * r_t, c_t complete before any u_t, RMS(u_t) of Eq. 1 complete before any u^_t, m_t).
+ * grad_bytes 4 or 2 (came_grad_dtype), momentum_bytes 4 or 2 (came_momentum_dtype), algo a
  * came_algo (Algorithm 1's sweep 2 does not read M).  Sweep 1 reads g; sweep 2 reads g
  * and M; sweep 3 reads g, M, theta and writes M, theta:
- *   8 + 3*grad_bytes + 3*momentum_bytes   (Algorithm 1: ... + 2*momentum_bytes).
- * Returns 0 for arguments out of range.
+ *   8 + 3*grad_bytes + 3*momentum_bytes   (Algorithm 1: ... + 2*momentum_bytes),
+ * i.e. 20 + 3*grad_bytes with a binary32 momentum.
+ * which: 0 = whole step, 1/2/3 = that sweep alone.  Returns 0 for arguments out of range.
  */
 double came_algorithmic_bytes(int32_t grad_bytes, int32_t momentum_bytes, int32_t algo, int32_t which);
 
 /*
- * Placement probe.  On MI355X the time of the one sweep that both reads and writes
- * (sweep 3: theta and M in place) depends on WHERE the caller's buffers sit physically:
- * when theta and the state blob share one of the HBM's three 96 GB address regions the
- * mixed read/write stream runs at about 5.2 TB/s, when they sit in different regions at
- * about 6.0 TB/s (pure reads and pure writes do not care).  The library owns no memory,
- * so it can only measure: this call rewrites every matrix's theta and M with their own
- * contents (sweep 3's traffic, no arithmetic, nothing changes) `repeats` times on
- * hip_stream, waits, and reports the achieved GB/s (0 if the list has no matrix).  A
- * caller can allocate its state blob at several addresses, probe each against its
- * parameters and keep the fastest.  theta_dev: host array of `count` device pointers
- * as for came_step.  Synchronises the stream.  Valid any time after came_init_state.
+ * Placement probe.  On MI355X the time of a sweep that streams from two or three arrays at
+ * once -- above all the one sweep that both reads and writes (sweep 3: theta and M in
+ * place) -- depends on WHERE the caller's buffers sit physically: when theta and the state
+ * blob share one of the HBM's three 96 GB address regions the mixed read/write stream runs
+ * at about 5.0-5.2 TB/s, when they sit in different regions at about 6.0 TB/s (pure reads
+ * of one array and pure writes do not care; sweep 2's two read streams g and M gain 2.5-5 %).
+ * Measured cost of not caring, state blob wherever a fresh allocator puts it (directly behind
+ * the parameters and gradients): a whole step takes about 15 % longer on a
+ * 6.7-billion-parameter list and 10-13 % longer on lists of 0.1-0.4 billion parameters.
+ * The library owns no memory, so it can only measure: this call runs the memory traffic of
+ * sweep 3 over every matrix (theta and M read and written back with their own bits; nothing
+ * changes) and, when grad_dev is given, also reads g in that pass and first runs the traffic
+ * of sweep 2 (g and M read), `repeats` times on hip_stream, waits, and reports the achieved
+ * GB/s over all of it (0 if the list has no matrix).  A caller can allocate its state blob at
+ * several addresses, probe each against its parameters (and gradient buffers, if those are
+ * long-lived) and keep the fastest.  theta_dev: host array of `count` device pointers as for
+ * came_step; grad_dev: the same for the gradients, or NULL.  Synchronises the stream; must
+ * not be called while the stream is capturing.  Valid any time after came_init_state.
  */
-int came_probe_placement(came_ctx *ctx, void *const *theta_dev, void *hip_stream, int32_t repeats,
-                         double *gbytes_per_s);
+int came_probe_placement(came_ctx *ctx, void *const *theta_dev, const void *const *grad_dev,
+                         void *hip_stream, int32_t repeats, double *gbytes_per_s);
 
 /*
  * Built-in phase timer.  While enabled, came_step brackets each of its

@@ -5,7 +5,7 @@ libcame_hip.so; Python only marshals arguments.  PyTorch is used for device
 memory and streams.
 """
 from .binding import (CameHyper, CameStep, GRAD_BF16, GRAD_F32, ALGO_CAME, ALGO_ADAFACTOR,  # noqa: F401
-                      MOMENTUM_F32, MOMENTUM_BF16, VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY, CameError, algorithmic_bytes, algorithmic_bytes_per_param,
+                      MOMENTUM_F32, MOMENTUM_BF16, VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY, CameError, algorithmic_bytes,
                       load_library, plan_query, state_size)
 
 

@@ -19,7 +19,7 @@ MOMENTUM_F32, MOMENTUM_BF16 = 0, 1
 VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY = 0, 1
 
 EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_step_bf16_copy", "came_state_view_get",
-           "came_plan_query", "came_algorithmic_bytes_per_param", "came_algorithmic_bytes", "came_probe_placement", "came_profile_enable",
+           "came_plan_query", "came_algorithmic_bytes", "came_probe_placement", "came_profile_enable",
            "came_profile_read", "came_last_hip_error",
            "came_destroy", "came_strerror")
 
@@ -93,11 +93,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.came_state_view_get.restype = ctypes.c_int
     lib.came_plan_query.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), ctypes.POINTER(i64)]
     lib.came_plan_query.restype = ctypes.c_int
-    lib.came_algorithmic_bytes_per_param.argtypes = [i32, i32]
-    lib.came_algorithmic_bytes_per_param.restype = dbl
     lib.came_algorithmic_bytes.argtypes = [i32, i32, i32, i32]
     lib.came_algorithmic_bytes.restype = dbl
-    lib.came_probe_placement.argtypes = [vp, ctypes.POINTER(vp), vp, i32, ctypes.POINTER(dbl)]
+    lib.came_probe_placement.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, ctypes.POINTER(dbl)]
     lib.came_probe_placement.restype = ctypes.c_int
     lib.came_profile_enable.argtypes = [vp, i32]
     lib.came_profile_enable.restype = ctypes.c_int
@@ -176,10 +174,6 @@ def plan_query(shapes, grad_dtypes, **opts) -> dict:
     return dict(zip(keys, [int(x) for x in out]))
 
 
-def algorithmic_bytes_per_param(grad_bytes: int, which: int = 0) -> float:
-    return float(load_library().came_algorithmic_bytes_per_param(int(grad_bytes), int(which)))
-
-
 def algorithmic_bytes(grad_bytes: int, momentum_bytes: int = 4, algo: int = ALGO_CAME, which: int = 0) -> float:
     return float(load_library().came_algorithmic_bytes(int(grad_bytes), int(momentum_bytes), int(algo), int(which)))
 
@@ -193,18 +187,23 @@ class CameStep:
 
     def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
                  group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32,
-                 vector_rule: int = VECTOR_ALGORITHM2, place_against=None, placement_candidates: int = 8,
-                 placement_spacer_bytes: int = 16 << 30, placement_accept_gbs: float = 5850.0,
-                 placement_accept_ratio: float = 1.15):
-        """place_against: the parameter tensors the context will be stepped with.  When given,
-        the state blob is allocated at up to `placement_candidates` different addresses
-        (separated by temporary spacer allocations), each is measured with
-        came_probe_placement against the parameters, and the fastest is kept (the search stops
-        at the first candidate that reaches placement_accept_gbs, or placement_accept_ratio times
-        the first candidate's rate): on MI355X the
-        read+write sweep is ~15 % faster when theta and the state sit in different 96 GB
-        regions of the HBM address space.  Memory is only allocated and measured here;
-        nothing about the arithmetic changes."""
+                 vector_rule: int = VECTOR_ALGORITHM2, place_against=None, place_against_grads=None,
+                 placement_candidates: int = 8, placement_spacer_bytes: int = 16 << 30,
+                 placement_accept_ratio: float = 1.12, placement_reserve_bytes: int = 2 << 30, blobs=None):
+        """blobs: (state, scratch), two uint8 tensors on `device` of at least state_size()'s bytes
+        at 256-byte aligned addresses, when the caller wants to place them itself; by default
+        both are allocated here.
+        place_against: the parameter tensors the context will be stepped with (and, in
+        place_against_grads, the gradient buffers if they are long-lived).  When given, the
+        state blob is allocated at up to `placement_candidates` different addresses, each
+        followed by `placement_spacer_bytes` of temporary spacers; each is measured with
+        came_probe_placement against the parameters and the fastest is kept.  The search is
+        bounded by what torch.cuda.mem_get_info reports as free (a candidate is only tried if it,
+        its spacers and placement_reserve_bytes fit) and stops early at the first candidate
+        that is placement_accept_ratio times faster than the first one, i.e. than the place the
+        allocator chose by itself: on MI355X the read+write sweep is ~15 % faster when theta
+        and the state sit in different 96 GB regions of the HBM address space.  Memory is
+        only allocated and measured here; nothing about the arithmetic changes."""
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -222,28 +221,23 @@ class CameStep:
         self._theta_arr = (ctypes.c_void_p * n)()
         self._grad_arr = (ctypes.c_void_p * n)()
         self.placement_log = []  # (candidate index, probe GB/s)
+        self._blobs = blobs
+        if blobs is not None and place_against is not None:
+            raise ValueError("blobs and place_against exclude each other")
         if place_against is None:
             self.state, self.scratch, self._ctx = self._create()
             return
-        if len(place_against) != n:
-            raise ValueError(f"place_against must hold the {n} parameter tensors, got {len(place_against)}")
+        if len(place_against) != n or (place_against_grads is not None and len(place_against_grads) != n):
+            raise ValueError(f"place_against(_grads) must hold the {n} parameter (gradient) tensors")
         # Every candidate and spacer stays allocated until the search ends, so that each new
         # candidate really lies at a new place (a freed block would be handed out again).
         tried, spacers, best = [], [], None
+        need = self.state_bytes + self.scratch_bytes + int(placement_reserve_bytes)
         for k in range(max(1, placement_candidates)):
-            try:
-                cand = self._create()
-            except (RuntimeError, CameError):
-                break  # out of memory for another candidate: keep what we have
-            tried.append(cand)
-            self.state, self.scratch, self._ctx = cand
-            gbs = self.probe_placement(place_against)
-            self.placement_log.append((k, gbs))
-            if best is None or gbs > best[0]:
-                best = (gbs, cand)
-            if gbs >= placement_accept_gbs or gbs >= placement_accept_ratio * self.placement_log[0][1]:
-                break
-            try:
+            if k > 0:
+                free_bytes, _ = torch.cuda.mem_get_info(self.device)
+                if free_bytes < need + int(placement_spacer_bytes):
+                    break  # no room for another candidate behind a spacer: keep the best so far
                 # in pieces of at most 1 GiB: the allocator lays small allocations out one after the
                 # other, whereas a single huge spacer may be put somewhere else entirely
                 left = int(placement_spacer_bytes)
@@ -251,10 +245,15 @@ class CameStep:
                     piece = min(left, 1 << 30)
                     spacers.append(torch.empty(piece, dtype=torch.uint8, device=self.device))
                     left -= piece
-            except RuntimeError:
+            cand = self._create()
+            tried.append(cand)
+            self.state, self.scratch, self._ctx = cand
+            gbs = self.probe_placement(place_against, place_against_grads)
+            self.placement_log.append((k, gbs))
+            if best is None or gbs > best[0]:
+                best = (gbs, cand)
+            if k > 0 and gbs >= placement_accept_ratio * self.placement_log[0][1]:
                 break
-        if best is None:
-            raise CameError(-5, "no memory for the optimizer state")
         for cand in tried:
             if cand is not best[1]:
                 self._destroy(cand)
@@ -266,13 +265,18 @@ class CameStep:
         torch = self._torch
         n = len(self.shapes)
         with torch.cuda.device(self.device):
-            state = torch.empty(self.state_bytes, dtype=torch.uint8, device=self.device)
-            scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=self.device)
+            if self._blobs is not None:
+                state, scratch = self._blobs
+                if state.dtype != torch.uint8 or scratch.dtype != torch.uint8 or not (state.is_contiguous() and scratch.is_contiguous()):
+                    raise ValueError("blobs must be contiguous uint8 tensors")
+            else:
+                state = torch.empty(self.state_bytes, dtype=torch.uint8, device=self.device)
+                scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=self.device)
             ctx = ctypes.c_void_p()
             stream = torch.cuda.current_stream(self.device).cuda_stream
             st = self.lib.came_init_state(ctypes.byref(ctx), self._d, n, ctypes.byref(self._o),
-                                          state.data_ptr(), self.state_bytes,
-                                          scratch.data_ptr(), self.scratch_bytes, stream)
+                                          state.data_ptr(), state.numel(),
+                                          scratch.data_ptr(), scratch.numel(), stream)
         _check(self.lib, st, "came_init_state")
         return state, scratch, ctx
 
@@ -280,15 +284,17 @@ class CameStep:
         self._torch.cuda.synchronize(self.device)
         self.lib.came_destroy(cand[2])
 
-    def probe_placement(self, thetas, repeats: int = 2) -> float:
-        """came_probe_placement: GB/s of rewriting theta and M in place (contents unchanged)."""
+    def probe_placement(self, thetas, grads=None, repeats: int = 2) -> float:
+        """came_probe_placement: GB/s of sweep 3's memory traffic (theta and M rewritten in place,
+        contents unchanged) and, when the gradient buffers are given, of sweep 2's as well."""
         torch = self._torch
         n = len(self.shapes)
         arr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in thetas])
+        garr = None if grads is None else (ctypes.c_void_p * n)(*[g.data_ptr() for g in grads])
         out = ctypes.c_double()
         with torch.cuda.device(self.device):
             s = torch.cuda.current_stream(self.device).cuda_stream
-            st = self.lib.came_probe_placement(self._ctx, arr, s, int(repeats), ctypes.byref(out))
+            st = self.lib.came_probe_placement(self._ctx, arr, garr, s, int(repeats), ctypes.byref(out))
         _check(self.lib, st, "came_probe_placement", self._ctx)
         return float(out.value)
 

@@ -50,7 +50,7 @@ constexpr size_t kMaxTimed = 65536;
 template <class F>
 hipError_t timed_launch(came_ctx* ctx, int phase, hipStream_t s, F launch)
 {
-    if (!ctx->profiling || ctx->timed.size() >= kMaxTimed) return launch();
+    if (!ctx || !ctx->profiling || ctx->timed.size() >= kMaxTimed) return launch();
     came_ctx::Timed t{};
     t.phase = phase;
     hipError_t e = hipEventCreate(&t.start);
@@ -65,31 +65,35 @@ hipError_t timed_launch(came_ctx* ctx, int phase, hipStream_t s, F launch)
     return hipSuccess;
 }
 
-DeviceTables tables_for(const came_ctx* ctx, int slot)
+// Device-side views of a plan's tables inside a scratch blob, with pointer-table slot `slot`.
+DeviceTables tables_in(const Plan& p, char* scratch, float* state, int slot)
 {
-    const Plan& p = ctx->plan;
     DeviceTables t{};
-    t.metas = reinterpret_cast<const TensorMeta*>(ctx->scratch + p.off_metas);
-    t.items = reinterpret_cast<const WorkItem*>(ctx->scratch + p.off_items);
-    t.fins = reinterpret_cast<const FinalizeItem*>(ctx->scratch + p.off_fins);
-    t.scalars = reinterpret_cast<TensorScalars*>(ctx->scratch + p.off_scalars);
-    char* slot_base = ctx->scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot);
+    t.metas = reinterpret_cast<const TensorMeta*>(scratch + p.off_metas);
+    t.items = reinterpret_cast<const WorkItem*>(scratch + p.off_items);
+    t.fins = reinterpret_cast<const FinalizeItem*>(scratch + p.off_fins);
+    t.scalars = reinterpret_cast<TensorScalars*>(scratch + p.off_scalars);
+    char* slot_base = scratch + p.off_ptrs + p.ptr_slot_bytes * static_cast<size_t>(slot);
     t.theta = reinterpret_cast<void* const*>(slot_base);
     t.grad = reinterpret_cast<const void* const*>(slot_base + sizeof(void*) * p.descs.size());
     t.theta16 = reinterpret_cast<void* const*>(slot_base + sizeof(void*) * 2 * p.descs.size());
-    t.state = ctx->state;
-    t.scratch = ctx->scratch;
+    t.state = state;
+    t.scratch = scratch;
     return t;
+}
+
+DeviceTables tables_for(const came_ctx* ctx, int slot)
+{
+    return tables_in(ctx->plan, ctx->scratch, ctx->state, slot);
 }
 
 // The caller's buffers must not overlap anything that is written: a parameter (or its
 // bfloat16 copy) may overlap no other buffer and neither blob; gradients are only read,
 // so two tensors may share one.  Sorted sweep over the address ranges.
-int check_overlaps(const came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
-                   void* const* theta16_dev)
+int check_overlaps(const Plan& p, const void* state, const void* scratch, size_t scratch_bytes,
+                   void* const* theta_dev, const void* const* grad_dev, void* const* theta16_dev)
 {
     struct Range { uintptr_t lo, hi; bool written; };
-    const Plan& p = ctx->plan;
     const size_t count = p.descs.size();
     std::vector<Range> r;
     r.reserve(3 * count + 2);
@@ -103,8 +107,8 @@ int check_overlaps(const came_ctx* ctx, void* const* theta_dev, const void* cons
         if (grad_dev) add(grad_dev[t], nm * ((p.metas[t].flags & kFlagBf16Grad) ? 2 : 4), false);
         if (theta16_dev && theta16_dev[t]) add(theta16_dev[t], nm * 2, true);
     }
-    add(ctx->state, p.state_bytes, true);
-    add(ctx->scratch, p.scratch_bytes, true);
+    add(state, p.state_bytes, true);
+    add(scratch, scratch_bytes, true);
     std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
     uintptr_t end_written = 0, end_any = 0;  // furthest end among the ranges already passed
     for (const Range& x : r) {
@@ -132,7 +136,14 @@ int upload_pointers(came_ctx* ctx, void* const* theta_dev, const void* const* gr
                       ctx->cached[2 * count + t] != copy_of(t);
     }
     if (changed) {
-        const int rc = check_overlaps(ctx, theta_dev, check_grads ? grad_dev : nullptr, theta16_dev);
+        // A new table means a host wait for a free slot and a copy out of a staging buffer that
+        // later calls overwrite: neither may be recorded into a graph.
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        const hipError_t ce = hipStreamIsCapturing(s, &capturing);
+        if (ce != hipSuccess) return hip_fail(ctx, ce);
+        if (capturing != hipStreamCaptureStatusNone) return CAME_EINVAL;
+        const int rc = check_overlaps(ctx->plan, ctx->state, ctx->scratch, ctx->plan.scratch_bytes, theta_dev,
+                                      check_grads ? grad_dev : nullptr, theta16_dev);
         if (rc != CAME_OK) return rc;
         const int slot = (ctx->slot + 1) % kPtrSlots;
         if (ctx->slot_used[slot]) {
@@ -212,18 +223,6 @@ int came_plan_query(const came_tensor_desc* descs, int32_t count, const came_opt
     });
 }
 
-double came_algorithmic_bytes_per_param(int32_t grad_bytes, int32_t which)
-{
-    const double g = static_cast<double>(grad_bytes);
-    switch (which) {
-        case 0: return 20.0 + 3.0 * g;  // whole step
-        case 1: return g;               // sweep 1: read g
-        case 2: return g + 4.0;         // sweep 2: read g, M
-        case 3: return g + 16.0;        // sweep 3: read g, M, theta; write M, theta
-        default: return 0.0;
-    }
-}
-
 double came_algorithmic_bytes(int32_t grad_bytes, int32_t momentum_bytes, int32_t algo, int32_t which)
 {
     if ((grad_bytes != 2 && grad_bytes != 4) || (momentum_bytes != 2 && momentum_bytes != 4)) return 0.0;
@@ -292,14 +291,13 @@ int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count
     });
 }
 
-static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
-                     void* const* theta16_dev, const came_hyper* hyper, double lr, int64_t step,
-                     void* hip_stream)
+// Argument checks shared by every step entry point: hyper-parameters, pointers, alignment.
+static int check_step_arguments(const Plan& p, void* const* theta_dev, const void* const* grad_dev,
+                                void* const* theta16_dev, const came_hyper* hyper, double lr, int64_t step)
 {
-    if (!ctx || !theta_dev || !grad_dev) return CAME_EINVAL;
-    int rc = validate_hyper(hyper, lr, step);
+    if (!theta_dev || !grad_dev) return CAME_EINVAL;
+    const int rc = validate_hyper(hyper, lr, step);
     if (rc != CAME_OK) return rc;
-    const Plan& p = ctx->plan;
     const size_t count = p.descs.size();
     for (size_t t = 0; t < count; ++t) {
         if (!theta_dev[t] || !grad_dev[t]) return CAME_EINVAL;
@@ -310,11 +308,18 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
             if (theta16_dev[t] == theta_dev[t] || theta16_dev[t] == grad_dev[t]) return CAME_EINVAL;
         }
     }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    return CAME_OK;
+}
 
-    rc = upload_pointers(ctx, theta_dev, grad_dev, theta16_dev, s);
-    if (rc != CAME_OK) return rc;
-
+// The launch sequence of one step over the plan's groups, on tables that are already in device
+// memory.  ctx (may be null) only serves the phase timer and the record of a failed HIP call.
+static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, const came_hyper* hyper,
+                        double lr, hipStream_t s, int* hip_error)
+{
+    auto failed = [&](hipError_t e) {
+        if (hip_error) *hip_error = static_cast<int>(e);
+        return hip_fail(ctx, e);
+    };
     SweepHyper sh{};
     sh.beta1 = static_cast<float>(hyper->beta1);
     sh.one_minus_beta1 = static_cast<float>(1.0 - hyper->beta1);
@@ -338,16 +343,15 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
     fh.clip_d = hyper->clip_d;
     fh.algo = p.algo;
 
-    const DeviceTables tb = tables_for(ctx, ctx->slot);
     for (const Group& g : p.groups) {
         hipError_t e = hipSuccess;
         if (g.lvec_end > g.lvec_begin) {
             e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
-            if (e != hipSuccess) return hip_fail(ctx, e);
+            if (e != hipSuccess) return failed(e);
         }
         if (g.fin_end == g.fin_begin) {  // vectors only
             e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
-            if (e != hipSuccess) return hip_fail(ctx, e);
+            if (e != hipSuccess) return failed(e);
             continue;
         }
         bool vectors_pending = g.vec_end > g.vec_begin;  // they ride along with the first sweep-1 launch
@@ -355,24 +359,39 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
             if (g.var_end[v] == g.var_begin[v]) continue;
             const int32_t vb = vectors_pending ? g.vec_begin : 0, ve = vectors_pending ? g.vec_end : 0;
             e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], vb, ve, sh, fh, s); });
-            if (e != hipSuccess) return hip_fail(ctx, e);
+            if (e != hipSuccess) return failed(e);
             vectors_pending = false;
         }
         e = timed_launch(ctx, 1, s, [&] { return launch_finalize1(tb, g.fin_begin, g.fin_end, fh, s); });
-        if (e != hipSuccess) return hip_fail(ctx, e);
+        if (e != hipSuccess) return failed(e);
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
             e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, p.algo, p.tile_rows, g.var_begin[v], g.var_end[v], p.reverse_sweep2, s); });
-            if (e != hipSuccess) return hip_fail(ctx, e);
+            if (e != hipSuccess) return failed(e);
         }
         e = timed_launch(ctx, 3, s, [&] { return launch_finalize2(tb, g.fin_begin, g.fin_end, fh, s); });
-        if (e != hipSuccess) return hip_fail(ctx, e);
+        if (e != hipSuccess) return failed(e);
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
             e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], sh, s); });
-            if (e != hipSuccess) return hip_fail(ctx, e);
+            if (e != hipSuccess) return failed(e);
         }
     }
+    return CAME_OK;
+}
+
+static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+                     void* const* theta16_dev, const came_hyper* hyper, double lr, int64_t step,
+                     void* hip_stream)
+{
+    if (!ctx) return CAME_EINVAL;
+    int rc = check_step_arguments(ctx->plan, theta_dev, grad_dev, theta16_dev, hyper, lr, step);
+    if (rc != CAME_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    rc = upload_pointers(ctx, theta_dev, grad_dev, theta16_dev, s);
+    if (rc != CAME_OK) return rc;
+    rc = enqueue_step(ctx, ctx->plan, tables_for(ctx, ctx->slot), hyper, lr, s, nullptr);
+    if (rc != CAME_OK) return rc;
     ctx->last_step = step;
     return CAME_OK;
 }
@@ -408,8 +427,8 @@ int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
     return CAME_OK;
 }
 
-int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream, int32_t repeats,
-                         double* gbytes_per_s)
+int came_probe_placement(came_ctx* ctx, void* const* theta_dev, const void* const* grad_dev,
+                         void* hip_stream, int32_t repeats, double* gbytes_per_s)
 {
     return guarded([&]() -> int {
         if (!ctx || !theta_dev || !gbytes_per_s || repeats < 1 || repeats > 1000) return CAME_EINVAL;
@@ -418,15 +437,20 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream
         for (size_t t = 0; t < count; ++t) {
             if (!theta_dev[t]) return CAME_EINVAL;
             if (!aligned_to(theta_dev[t], 16)) return CAME_EALIGN;
+            if (grad_dev) {
+                if (!grad_dev[t]) return CAME_EINVAL;
+                if (!aligned_to(grad_dev[t], 16)) return CAME_EALIGN;
+            }
         }
         *gbytes_per_s = 0.0;
         hipStream_t s = static_cast<hipStream_t>(hip_stream);
-        // the probe reads no gradients: the pointer table's gradient half just repeats theta
+        // without gradients the pointer table's gradient half just repeats theta (never read)
         std::vector<const void*> fake(theta_dev, theta_dev + count);
-        int rc = upload_pointers(ctx, theta_dev, fake.data(), nullptr, s, false);
+        int rc = upload_pointers(ctx, theta_dev, grad_dev ? grad_dev : fake.data(), nullptr, s, grad_dev != nullptr);
         if (rc != CAME_OK) return rc;
         ctx->cached.clear();  // force a fresh table at the next came_step
         const int used_slot = ctx->slot;
+        const bool with_g = grad_dev != nullptr;
         double bytes = 0.0;
         for (const Group& g : p.groups)
             for (int v = 0; v < kVariants; ++v) {
@@ -435,8 +459,13 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream
                     const TensorMeta& tm = p.metas[p.items[k].tensor];
                     const int64_t rows = std::min<int64_t>(tm.tile_rows, tm.n - int64_t(p.items[k].rb) * tm.tile_rows);
                     const int64_t cols = std::min<int64_t>(kTileCols, tm.m - int64_t(p.items[k].cb) * kTileCols);
-                    // theta and M, read and written
-                    bytes += ((tm.flags & kFlagBf16Momentum) ? 12.0 : 16.0) * static_cast<double>(rows * cols);
+                    const double mb = (tm.flags & kFlagBf16Momentum) ? 2.0 : 4.0;
+                    const double gb = (tm.flags & kFlagBf16Grad) ? 2.0 : 4.0;
+                    // sweep 3's streams: theta and M read and written (g read);
+                    // with gradients also sweep 2's: g and M read
+                    double per = 8.0 + 2.0 * mb;
+                    if (with_g) per += gb + (gb + mb);
+                    bytes += per * static_cast<double>(rows * cols);
                 }
             }
         if (bytes == 0.0) return CAME_OK;
@@ -447,12 +476,13 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, void* hip_stream
         e = hipEventCreate(&e1);
         if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(ctx, e); }
         auto run_once = [&]() -> hipError_t {
-            for (const Group& g : p.groups)
-                for (int v = 0; v < kVariants; ++v) {
-                    if (v & 2) continue;
-                    const hipError_t le = launch_placement_probe(tb, g.var_begin[v], g.var_end[v], s);
-                    if (le != hipSuccess) return le;
-                }
+            for (int mode = with_g ? 1 : 0; mode >= 0; --mode)
+                for (const Group& g : p.groups)
+                    for (int v = 0; v < kVariants; ++v) {
+                        if (v & 2) continue;
+                        const hipError_t le = launch_placement_probe(tb, g.var_begin[v], g.var_end[v], mode, with_g, s);
+                        if (le != hipSuccess) return le;
+                    }
             return hipSuccess;
         };
         e = run_once();  // warm-up

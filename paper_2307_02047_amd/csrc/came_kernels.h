@@ -47,9 +47,11 @@ hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s);
 // `variant` (see variant_of) selects the kernel instantiation; all work items in
 // [item_begin, item_end) must be matrix tiles of tensors of that variant.
 
-// Rewrites theta and M of the matrix tiles [item_begin, item_end) with their own contents
-// (sweep 3's memory traffic, no arithmetic).
-hipError_t launch_placement_probe(const DeviceTables& t, int32_t item_begin, int32_t item_end, hipStream_t s);
+// Memory traffic of a sweep over the matrix tiles [item_begin, item_end) without its arithmetic,
+// contents unchanged.  mode 0: theta and M read and rewritten with their own bits (sweep 3),
+// g read as well when with_g; mode 1: g and M read only (sweep 2; needs with_g).
+hipError_t launch_placement_probe(const DeviceTables& t, int32_t item_begin, int32_t item_end, int mode,
+                                  bool with_g, hipStream_t s);
 
 // Complete Algorithm-2 update of the vectors [item_begin, item_end), one workgroup each.
 hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,

@@ -535,7 +535,7 @@ __device__ __forceinline__ int64_t load_col(const TileGeom& t, int cb)
 #ifndef CAME_XCD_CHUNK
 #define CAME_XCD_CHUNK 64
 #endif
-constexpr int32_t kXcds = 8, kXcdChunk = CAME_XCD_CHUNK;
+constexpr int32_t kXcds = kNumXcds, kXcdChunk = CAME_XCD_CHUNK;
 
 __device__ __forceinline__ int32_t xcd_item(int32_t b, int32_t n)
 {
@@ -1186,40 +1186,56 @@ CAME_SWEEP3_KERNEL(sweep3_f32_mbf16_unaligned_kernel, false, false, true, 4)
 
 // ---------------------------------------------------------------- placement probe
 
-// Reads every theta and M entry of the matrix tiles and writes the same bits back, in
-// sweep 3's tile order: the memory traffic of sweep 3 without its arithmetic, contents
-// unchanged.  Used to find out how well the caller's placement of theta and of the state
-// blob suits the memory system before any state exists (see came_probe_placement).
-__global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTables tb, int32_t item_begin)
+// The memory traffic of sweep 2 or sweep 3 without their arithmetic, in the sweeps' tile
+// order, contents unchanged.  Used to find out how well the caller's placement of theta, g
+// and of the state blob suits the memory system before any state exists (see
+// came_probe_placement).
+//   mode 0: read every theta and M entry of the matrix tiles (and g when with_g) and write the
+//           same theta and M bits back: sweep 3's streams;
+//   mode 1: read g and M, write nothing: sweep 2's streams.
+// Loaded gradient bits are folded into a word that is stored only if it equals a value it
+// cannot take, so that the loads stay.
+__global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTables tb, int32_t item_begin,
+                                                                     int32_t mode, int32_t with_g)
 {
-    const WorkItem it = tb.items[item_begin + blockIdx.x];
+    const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];
     const TensorMeta& tm = tb.metas[it.tensor];
     if (!(tm.flags & kFlagAligned)) return;
     const TileGeom t = tile_geom(tm, it);
     if (t.ncol == 0) return;
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
     float* M = tb.state + tm.off_M;
-    if (tm.flags & kFlagBf16Momentum) {
-        for (int i = t.wave; i < t.nrows; i += kWaves) {
-            const int64_t idx = (t.row0 + i) * tm.m + t.col;
-            CAME_GLOBAL u32x4* pm = (CAME_GLOBAL u32x4*)(glob(reinterpret_cast<uint16_t*>(M)) + idx);
-            CAME_GLOBAL f32x4* pt = (CAME_GLOBAL f32x4*)(glob(theta) + idx);
-            u32x4 m0 = pm[0];
-            f32x4 t0 = pt[0], t1 = pt[1];
-            asm volatile("" : "+v"(m0), "+v"(t0), "+v"(t1));
-            pm[0] = m0; pt[0] = t0; pt[1] = t1;
-        }
-        return;
-    }
+    const bool mb16 = tm.flags & kFlagBf16Momentum, gb16 = tm.flags & kFlagBf16Grad;
+    const CAME_GLOBAL uint16_t* g16 = glob(static_cast<const uint16_t*>(tb.grad[it.tensor]));
+    uint32_t sink = 0u;
     for (int i = t.wave; i < t.nrows; i += kWaves) {
         const int64_t idx = (t.row0 + i) * tm.m + t.col;
-        CAME_GLOBAL f32x4* pm = (CAME_GLOBAL f32x4*)(glob(M) + idx);
+        if (with_g) {
+            const CAME_GLOBAL u32x4* pg = (const CAME_GLOBAL u32x4*)(g16 + (gb16 ? idx : 2 * idx));
+            u32x4 a = __builtin_nontemporal_load(pg);
+            sink ^= a.x ^ a.y ^ a.z ^ a.w;
+            if (!gb16) {
+                a = __builtin_nontemporal_load(pg + 1);
+                sink ^= a.x ^ a.y ^ a.z ^ a.w;
+            }
+        }
+        CAME_GLOBAL u32x4* pm = (CAME_GLOBAL u32x4*)(glob(reinterpret_cast<uint16_t*>(M)) + (mb16 ? idx : 2 * idx));
         CAME_GLOBAL f32x4* pt = (CAME_GLOBAL f32x4*)(glob(theta) + idx);
-        f32x4 m0 = pm[0], m1 = pm[1], t0 = pt[0], t1 = pt[1];
-        // opaque to the optimiser, so that the stores of just-loaded values are kept
-        asm volatile("" : "+v"(m0), "+v"(m1), "+v"(t0), "+v"(t1));
-        pm[0] = m0; pm[1] = m1; pt[0] = t0; pt[1] = t1;
+        u32x4 m0 = pm[0], m1 = m0;
+        if (!mb16) m1 = pm[1];
+        if (mode == 0) {
+            f32x4 t0 = pt[0], t1 = pt[1];
+            // opaque to the optimiser, so that the stores of just-loaded values are kept
+            asm volatile("" : "+v"(m0), "+v"(m1), "+v"(t0), "+v"(t1));
+            pm[0] = m0;
+            if (!mb16) pm[1] = m1;
+            pt[0] = t0; pt[1] = t1;
+        } else {
+            sink ^= m0.x ^ m0.y ^ m0.z ^ m0.w ^ m1.x ^ m1.y ^ m1.z ^ m1.w;
+        }
     }
+    // never true: the per-workgroup scalars hold four floats and four zero words per tensor
+    if (sink == 0x7fc12345u && tb.scalars[it.tensor].pad_[0] == 0xffffffffu) tb.scalars[it.tensor].pad_[1] = sink;
 }
 
 // ---------------------------------------------------------------- fill
@@ -1240,7 +1256,7 @@ hipError_t launch_fill_zero(float* p, size_t count, hipStream_t s)
     const size_t n4 = count / 4;
     const size_t ntail = count % 4;
     size_t blocks = (n4 + kWorkgroup - 1) / kWorkgroup;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks > kNumCus * 32) blocks = kNumCus * 32;
     if (blocks == 0) blocks = 1;
     fill_zero_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kWorkgroup), 0, s>>>(
         reinterpret_cast<f32x4*>(p), n4, p + n4 * 4, ntail);
@@ -1252,10 +1268,11 @@ hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s)
     return launch_fill_zero(static_cast<float*>(p), bytes / sizeof(float), s);
 }
 
-hipError_t launch_placement_probe(const DeviceTables& t, int32_t item_begin, int32_t item_end, hipStream_t s)
+hipError_t launch_placement_probe(const DeviceTables& t, int32_t item_begin, int32_t item_end, int mode,
+                                  bool with_g, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
-    placement_probe_kernel<<<dim3(item_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin);
+    placement_probe_kernel<<<dim3(item_end - item_begin), dim3(kWorkgroup), 0, s>>>(t, item_begin, mode, with_g ? 1 : 0);
     return hipGetLastError();
 }
 

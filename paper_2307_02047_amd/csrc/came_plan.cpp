@@ -11,6 +11,10 @@ namespace came {
 namespace {
 
 constexpr int64_t kAlignFloats = 64;  // 256-byte alignment of every state array
+// Most work items (and finalize items) a plan may have: they are indexed with 32-bit integers on
+// the device and a launch takes one workgroup per item.  2^26 is twenty times what a
+// 6.7-billion-parameter list needs at the smallest tile height.
+constexpr int64_t kMaxItems = int64_t(1) << 26;
 constexpr size_t kAlignBytes = 256;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -24,7 +28,7 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // larger ones leave compute units idle in the last round of a launch.
 int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count)
 {
-    const int64_t want = 256 * 12;
+    const int64_t want = kNumCus * 12;
     int32_t best = 16;
     for (int32_t tr = 512; tr >= 16; tr -= 16) {
         int64_t tiles = 0;
@@ -74,7 +78,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         if (d.grad_dtype != CAME_GRAD_F32 && d.grad_dtype != CAME_GRAD_BF16) return CAME_EINVAL;
         if (d.rows > (int64_t(1) << 40) || d.cols > (int64_t(1) << 40)) return CAME_EINVAL;
         if (d.ndim == 1 && d.rows > (int64_t(1) << 38)) return CAME_EINVAL;  // chunk size must fit int32
-        if (d.rows * d.cols > (int64_t(1) << 46)) return CAME_EINVAL;
+        if (d.rows > (int64_t(1) << 46) / d.cols) return CAME_EINVAL;  // rows*cols <= 2^46, without forming an overflowing product
     }
 
     Plan& p = *plan;
@@ -83,6 +87,22 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     p.algo = o.algo;
     p.momentum_dtype = o.momentum_dtype;
     p.tile_rows = o.tile_rows ? o.tile_rows : auto_tile_rows(descs, count);
+    {
+        // counted in 64 bits before anything 32-bit is derived from them
+        int64_t items = 0, fins = 0;
+        for (int32_t t = 0; t < count; ++t) {
+            const came_tensor_desc& d = descs[t];
+            if (d.ndim == 2) {
+                const int64_t RB = ceil_div(d.rows, p.tile_rows), CB = ceil_div(d.cols, kTileCols);
+                if (RB > kMaxItems || CB > kMaxItems || RB * CB > kMaxItems) return CAME_EINVAL;
+                items += RB * CB;
+                fins += ceil_div(d.rows, kWorkgroup) + ceil_div(d.cols, kFinalizeCols);
+            } else {
+                items += d.rows <= kFusedVectorMax ? 1 : kMaxVectorChunks;
+            }
+            if (items > kMaxItems || fins > kMaxItems) return CAME_EINVAL;
+        }
+    }
     p.metas.resize(count);
 
     // ---- state blob: per tensor M | r | c | R | C, every array 256-byte aligned

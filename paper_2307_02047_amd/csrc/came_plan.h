@@ -15,6 +15,12 @@ namespace came {
 // Geometry of a sweep tile.  A workgroup of 4 wave64s sweeps `tile_rows` rows
 // of a 512-column stripe: each lane owns 8 consecutive columns (one 16-byte
 // bf16 load or two 16-byte f32 loads), each wave takes every 4th row.
+// The one machine this library is written for, MI355X (gfx950): 8 accelerator dies (XCDs), each
+// with its own L2, to which the dispatcher deals consecutive workgroups round-robin; 32 compute
+// units per die.  Everything that is tuned to the chip's shape refers to these two numbers.
+constexpr int kNumXcds = 8;
+constexpr int kNumCus = 256;
+
 constexpr int kWorkgroup = 256;
 constexpr int kWaves = 4;
 constexpr int kLaneCols = 8;

@@ -8,6 +8,12 @@ Error measure (stated bar: max relative error 1e-5 after 1 step, 1e-4 after
   * theta and M are signed and individual entries can cancel to ~0, where an
     elementwise relative error is meaningless; they use
     |x - ref| / (|ref| + RMS(ref over the tensor)).
+  * theta_0 ~ 0.02 is ten times larger than the first step's move, so an error in the last
+    line of Algorithm 2 (theta_t = theta_{t-1} - eta m_t / sqrt(S_t)) shows in theta diluted
+    ten to twenty times.  After step 1 the move itself, theta_1 - theta_0, is therefore
+    compared as well ("dtheta", same measure, same bar).
+The strict elementwise figure max |x - ref| / |ref| of theta and M is printed beside these
+(not asserted: it is unbounded wherever an entry passes through zero).
 """
 from __future__ import annotations
 
@@ -28,6 +34,14 @@ def rel_err_signed(x: np.ndarray, ref: np.ndarray) -> float:
     if rms == 0.0:
         return float(np.max(np.abs(x - ref)))
     return float(np.max(np.abs(x - ref) / (np.abs(ref) + rms)))
+
+
+def rel_err_strict(x: np.ndarray, ref: np.ndarray) -> float:
+    """max |x - ref| / |ref| over the entries with ref != 0 (0 if there is none)."""
+    nz = ref != 0.0
+    if not nz.any():
+        return 0.0
+    return float(np.max(np.abs(x[nz] - ref[nz]) / np.abs(ref[nz])))
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:
@@ -51,6 +65,8 @@ class SideBySide:
                               vector_rule=P.VECTOR_ALGORITHM2 if vector_confidence else P.VECTOR_MOMENTUM_ONLY, **opts)
         self.theta = [self.gen.theta0(i) for i in self.idx]
         self.otl = O.TensorList([self.shapes[k] for k in self.check], [to_f64(self.theta[k]) for k in self.check])
+        self.theta0 = [to_f64(self.theta[k]) for k in self.check]  # for the undiluted check of the first move
+        self.strict = {}
         self.t = 0
 
     def step(self, nthreads: int = 0):
@@ -91,7 +107,12 @@ class SideBySide:
             th = to_f64(self.theta[k])
             assert np.all(np.isfinite(th)), f"non-finite theta in tensor {self.idx[k]} {self.shapes[k]}"
             upd("theta", rel_err_signed(th, self.otl.theta[pos]), k)
-            upd("M", rel_err_signed(to_f64(sv["M"]), st.M), k)
+            if self.t == 1:  # the first move itself, not diluted by theta_0
+                upd("dtheta", rel_err_signed(th - self.theta0[pos], self.otl.theta[pos] - self.theta0[pos]), k)
+            Mg = to_f64(sv["M"])
+            upd("M", rel_err_signed(Mg, st.M), k)
+            self.strict["theta"] = max(self.strict.get("theta", 0.0), rel_err_strict(th, self.otl.theta[pos]))
+            self.strict["M"] = max(self.strict.get("M", 0.0), rel_err_strict(Mg, st.M))
             if len(self.shapes[k]) == 2:
                 upd("r", rel_err_positive(to_f64(sv["r"]), st.r), k)
                 upd("c", rel_err_positive(to_f64(sv["c"]), st.c), k)
@@ -109,10 +130,12 @@ class SideBySide:
         return worst
 
     def assert_within(self, tol: float, label: str = ""):
+        self.strict = {}
         errs = self.errors()
         bad = {k: v for k, v in errs.items() if not (v[0] <= tol)}
         summary = ", ".join(f"{k}={v[0]:.2e}" for k, v in errs.items())
-        print(f"[parity] {self.w.name} {label} step {self.t}: {summary}", flush=True)
+        strict = ", ".join(f"{k}={v:.2e}" for k, v in self.strict.items())
+        print(f"[parity] {self.w.name} {label} step {self.t}: {summary}; strict elementwise: {strict}", flush=True)
         assert not bad, f"{self.w.name} step {self.t}: over tolerance {tol:g}: {bad}"
         return errs
 

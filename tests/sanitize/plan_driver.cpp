@@ -1,0 +1,163 @@
+// Host-only driver for the launch planner, built with -fsanitize=address,undefined by
+// tests/test_sanitizers.py.  Reads tensor descriptors ("rows cols ndim grad_dtype" per line)
+// from the file named on the command line, builds the plan and re-checks on the host what the
+// kernels assume about it: every work item and finalize item names a tensor and a block that
+// exist, every state array and every scratch region lies inside its blob, none overlap.
+//
+//   plan_driver <descs.txt> <tile_rows> <algo> <group_elements> <momentum_dtype> <vector_rule>
+//
+// Prints "rc state_bytes scratch_bytes items fins groups" and exits 0, or exits 3 with a message
+// when an invariant is broken.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "came_plan.h"
+
+using namespace came;
+
+namespace {
+
+struct Range { long long lo, hi; const char* what; int tensor; };
+
+int fail(const char* what, long long a, long long b)
+{
+    std::fprintf(stderr, "plan invariant broken: %s (%lld, %lld)\n", what, a, b);
+    return 3;
+}
+
+int check_disjoint(std::vector<Range>& r, long long limit, const char* blob)
+{
+    std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
+    long long end = 0;
+    for (const Range& x : r) {
+        if (x.lo < end) { std::fprintf(stderr, "%s: %s of tensor %d overlaps its predecessor\n", blob, x.what, x.tensor); return 3; }
+        if (x.hi > limit) { std::fprintf(stderr, "%s: %s of tensor %d leaves the blob\n", blob, x.what, x.tensor); return 3; }
+        end = x.hi;
+    }
+    return 0;
+}
+
+}  // namespace
+
+int main(int argc, char** argv)
+{
+    if (argc != 7) return 2;
+    std::vector<came_tensor_desc> descs;
+    if (FILE* f = std::fopen(argv[1], "r")) {
+        long long rows, cols;
+        int ndim, dt;
+        while (std::fscanf(f, "%lld %lld %d %d", &rows, &cols, &ndim, &dt) == 4)
+            descs.push_back(came_tensor_desc{rows, cols, ndim, dt});
+        std::fclose(f);
+    } else {
+        return 2;
+    }
+    came_options o{};
+    o.tile_rows = std::atoi(argv[2]);
+    o.algo = std::atoi(argv[3]);
+    o.group_elements = std::atoll(argv[4]);
+    o.momentum_dtype = std::atoi(argv[5]);
+    o.vector_rule = std::atoi(argv[6]);
+    Plan p;
+    const int rc = build_plan(descs.empty() ? nullptr : descs.data(), static_cast<int32_t>(descs.size()), &o, &p);
+    if (rc != CAME_OK) {
+        std::printf("%d 0 0 0 0 0\n", rc);
+        return 0;
+    }
+    const long long count = static_cast<long long>(descs.size());
+    const bool mb16 = o.momentum_dtype == CAME_MOMENTUM_BF16;
+
+    // state blob: M | r | c | R | C per tensor, in floats
+    std::vector<Range> st;
+    for (int t = 0; t < count; ++t) {
+        const TensorMeta& tm = p.metas[t];
+        const long long nm = tm.n * tm.m;
+        st.push_back(Range{tm.off_M, tm.off_M + (mb16 ? (nm + 1) / 2 : nm), "M", t});
+        st.push_back(Range{tm.off_r, tm.off_r + tm.n, "r", t});
+        st.push_back(Range{tm.off_R, tm.off_R + tm.n, "R", t});
+        if (!(tm.flags & kFlagVector)) {
+            st.push_back(Range{tm.off_c, tm.off_c + tm.m, "c", t});
+            st.push_back(Range{tm.off_C, tm.off_C + tm.m, "C", t});
+        } else if (tm.off_c != -1 || tm.off_C != -1 || tm.m != 1) {
+            return fail("vector with column statistics", t, tm.m);
+        }
+    }
+    if (int e = check_disjoint(st, static_cast<long long>(p.state_bytes / sizeof(float)), "state")) return e;
+
+    // scratch blob: tables, pointer slots, partial sums (bytes)
+    std::vector<Range> sc;
+    auto add = [&](size_t off, size_t bytes, const char* what, int t) {
+        sc.push_back(Range{static_cast<long long>(off), static_cast<long long>(off + bytes), what, t});
+    };
+    add(p.off_metas, sizeof(TensorMeta) * count, "metas", -1);
+    add(p.off_items, sizeof(WorkItem) * p.items.size(), "items", -1);
+    add(p.off_fins, sizeof(FinalizeItem) * p.fins.size(), "fins", -1);
+    add(p.off_scalars, sizeof(TensorScalars) * count, "scalars", -1);
+    add(p.off_ptrs, p.ptr_slot_bytes * kPtrSlots, "pointer slots", -1);
+    if (p.ptr_slot_bytes < sizeof(void*) * kPtrArrays * count) return fail("pointer slot too small", p.ptr_slot_bytes, count);
+    for (int t = 0; t < count; ++t) {
+        const TensorMeta& tm = p.metas[t];
+        if (tm.flags & kFlagVector) {
+            if (tm.ntiles > 0) {
+                add(tm.off_tileP, sizeof(double) * tm.ntiles, "chunk sums", t);
+                if (static_cast<long long>(tm.ntiles) * tm.tile_rows < tm.n) return fail("long vector not covered", t, tm.n);
+                if (tm.ntiles > kMaxVectorChunks || tm.tile_rows % kWorkgroup) return fail("long vector chunking", tm.ntiles, tm.tile_rows);
+            } else if (tm.n > kFusedVectorMax) {
+                return fail("long vector without chunks", t, tm.n);
+            }
+            continue;
+        }
+        if (static_cast<long long>(tm.RB) * tm.tile_rows < tm.n || static_cast<long long>(tm.RB - 1) * tm.tile_rows >= tm.n)
+            return fail("row blocks", tm.RB, tm.n);
+        if (static_cast<long long>(tm.CB) * kTileCols < tm.m || static_cast<long long>(tm.CB - 1) * kTileCols >= tm.m)
+            return fail("column blocks", tm.CB, tm.m);
+        if (tm.ntiles != tm.RB * tm.CB) return fail("tile count", tm.ntiles, t);
+        if (static_cast<long long>(tm.f_row_wgs) * kWorkgroup < tm.n || static_cast<long long>(tm.f_col_wgs) * kFinalizeCols < tm.m)
+            return fail("finalize coverage", tm.f_row_wgs, tm.f_col_wgs);
+        add(tm.off_rowpart, sizeof(double) * 3 * tm.n * tm.CB, "row partials", t);
+        add(tm.off_colpart, sizeof(double) * 3 * tm.RB * tm.m, "column partials", t);
+        add(tm.off_tileP, sizeof(double) * tm.ntiles, "tile sums", t);
+        add(tm.off_fpart, sizeof(double) * 2 * tm.f_row_wgs, "finalize sums", t);
+    }
+    if (int e = check_disjoint(sc, static_cast<long long>(p.scratch_bytes), "scratch")) return e;
+
+    // work items: each matrix tile exactly once, inside its group's variant range; vectors once
+    std::vector<long long> seen(count, 0);
+    for (const Group& g : p.groups) {
+        for (int v = 0; v < kVariants; ++v)
+            for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
+                const WorkItem& it = p.items[k];
+                if (it.tensor < g.tensor_begin || it.tensor >= g.tensor_end || it.kind != 0) return fail("tile item", k, it.tensor);
+                const TensorMeta& tm = p.metas[it.tensor];
+                if (variant_of(tm.flags) != v || it.rb < 0 || it.rb >= tm.RB || it.cb < 0 || it.cb >= tm.CB)
+                    return fail("tile item block", it.rb, it.cb);
+                ++seen[it.tensor];
+            }
+        for (int32_t k = g.vec_begin; k < g.vec_end; ++k) {
+            const WorkItem& it = p.items[k];
+            if (it.kind != 1 || !(p.metas[it.tensor].flags & kFlagVector) || p.metas[it.tensor].n > kFusedVectorMax)
+                return fail("vector item", k, it.tensor);
+            ++seen[it.tensor];
+        }
+        for (int32_t k = g.lvec_begin; k < g.lvec_end; ++k) {
+            const WorkItem& it = p.items[k];
+            if (it.kind != 2 || it.rb < 0 || it.rb >= p.metas[it.tensor].ntiles) return fail("chunk item", k, it.tensor);
+            ++seen[it.tensor];
+        }
+        for (int32_t k = g.fin_begin; k < g.fin_end; ++k) {
+            const FinalizeItem& fi = p.fins[k];
+            const TensorMeta& tm = p.metas[fi.tensor];
+            if (fi.tensor < g.tensor_begin || fi.tensor >= g.tensor_end) return fail("finalize item tensor", k, fi.tensor);
+            if (fi.chunk < 0 || fi.chunk >= (fi.kind == 0 ? tm.f_row_wgs : tm.f_col_wgs)) return fail("finalize item chunk", k, fi.chunk);
+        }
+    }
+    for (int t = 0; t < count; ++t) {
+        const TensorMeta& tm = p.metas[t];
+        const long long want = (tm.flags & kFlagVector) ? (tm.ntiles > 0 ? tm.ntiles : 1) : tm.ntiles;
+        if (seen[t] != want) return fail("tensor covered a wrong number of times", seen[t], want);
+    }
+    std::printf("%d %zu %zu %zu %zu %zu\n", rc, p.state_bytes, p.scratch_bytes, p.items.size(), p.fins.size(), p.groups.size());
+    return 0;
+}

@@ -17,8 +17,15 @@ and from then on that entry follows a different, equally valid, path.  So:
     share of entries stored differently from the oracle is printed (about 5e-5).
   * free running for many steps: everything the rounding does not reach (r, c) at the
     100-step bar 1e-4, the row/column confidence sums at 1e-4 as well (single entries
-    average out), and for theta, M and the unfactored s of vectors at least 99 % of the
-    entries at 1e-4.
+    average out), and for theta, M and the unfactored s of vectors at least 99.8 % of the
+    entries at 1e-4 (measured: 99.95 %).  The entries beyond that are bounded in size: two
+    stored momenta that parted at a tie differ by one bfloat16 spacing (<= 2^-7 |M|) for as
+    long as they keep rounding apart (0.9 spacings apart before rounding is 0 or 1 spacing
+    after it; when M shrinks into a finer binade the gap it inherited just decays by beta1
+    per step), so M may be off by two spacings of the largest |M| that entry has had, and
+    theta by at most eta * spacing(M_t) / sqrt(S_t) per step, i.e. by no more than
+    T * eta * 2^-7 * max |M / sqrt(S)| after T steps.  An entry that is wrong for any other
+    reason breaks one of the two bounds.
 """
 import numpy as np
 import pytest
@@ -147,20 +154,40 @@ def test_free_running_100_steps():
     theta = [gen.theta0(i) for i in idx]
     otl = O.TensorList(shapes, [to_f64(t) for t in theta])
     h, oh = P.CameHyper(), O.Hyper(lr=w.lr)
+    T = 100
+    move = [0.0] * len(idx)  # per tensor: largest |M_t / sqrt(S_t)| the oracle saw (the size of a step, in units of eta)
+    peak = [np.zeros(s) for s in shapes]  # per entry: largest |M_t| so far
     try:
-        for t in range(1, 101):
+        for t in range(1, T + 1):
             grads = [gen.grad(i, t) for i in idx]
             opt.step(theta, grads, h, w.lr, t)
             otl.step([to_f64(g) for g in grads], oh, nthreads=8, momentum_bf16=True)
+            for k, st in enumerate(otl.state):
+                if isinstance(st, O.MatrixState):
+                    a = np.abs(st.M) / np.sqrt(st.R / st.R.sum())[:, None] / np.sqrt(st.C)[None, :]
+                else:
+                    a = np.abs(st.M) / np.sqrt(st.s)
+                move[k] = max(move[k], float(a.max()))
+                np.maximum(peak[k], np.abs(st.M), out=peak[k])
         torch.cuda.synchronize()
         for k, s in enumerate(shapes):
             sv, st = opt.state_view(k), otl.state[k]
             th = to_f64(theta[k])
             assert np.all(np.isfinite(th))
             e_th = signed_err(th, otl.theta[k])
-            e_M = signed_err(to_f64(sv["M"]), st.M)
-            line = f"[bf16-M free] {s}: theta >1e-4: {(e_th > 1e-4).mean():.2e}, M >1e-4: {(e_M > 1e-4).mean():.2e}"
-            assert (e_th > 1e-4).mean() <= 0.01 and (e_M > 1e-4).mean() <= 0.01
+            Mg = to_f64(sv["M"])
+            e_M = signed_err(Mg, st.M)
+            d_th = float(np.abs(th - otl.theta[k]).max())
+            bound_th = T * w.lr * 2.0 ** -7 * move[k]
+            d_M = np.abs(Mg - st.M)
+            bound_M = 2.0 * bf16_spacing(1.01 * peak[k])
+            line = (f"[bf16-M free] {s}: theta >1e-4: {(e_th > 1e-4).mean():.2e}, M >1e-4: {(e_M > 1e-4).mean():.2e}, "
+                    f"max |dtheta| {d_th:.2e} (bound {bound_th:.2e}), max |dM| in spacings of the entry's peak |M| "
+                    f"{float((d_M / bound_M).max()) * 2.0:.2f} (bound 2)")
+            print(line, flush=True)
+            assert (e_th > 1e-4).mean() <= 2e-3 and (e_M > 1e-4).mean() <= 2e-3, line
+            assert d_th <= bound_th, line
+            assert not (d_M > bound_M).any(), line
             if len(s) == 2:
                 errs = {q: rel_err_positive(to_f64(sv[q]), getattr(st, q)) for q in "rcRC"}
                 assert all(v <= 1e-4 for v in errs.values()), errs
@@ -168,8 +195,9 @@ def test_free_running_100_steps():
                 errs = {"v": rel_err_positive(to_f64(sv["r"]), st.v)}
                 assert errs["v"] <= 1e-4
                 e_s = np.abs(to_f64(sv["R"]) - st.s) / st.s
-                assert (e_s > 1e-4).mean() <= 0.01
-            print(line + " " + ", ".join(f"{q}={v:.1e}" for q, v in errs.items()), flush=True)
+                errs["s >1e-4"] = float((e_s > 1e-4).mean())
+                assert errs["s >1e-4"] <= 5e-3, errs
+            print("    " + ", ".join(f"{q}={v:.1e}" for q, v in errs.items()), flush=True)
     finally:
         opt.close()
 

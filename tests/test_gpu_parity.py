@@ -1,8 +1,6 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
 same seeded inputs.  Bar: max relative error 1e-5 after 1 step, 1e-4 after 100
 steps (measure defined in parity_util.py)."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -14,7 +12,6 @@ from parity_util import SideBySide
 pytestmark = pytest.mark.gpu
 
 TOL_1, TOL_100 = 1e-5, 1e-4
-LONG = os.environ.get("CAME_LONG_PARITY", "0") == "1"
 
 
 def _run(w, steps, tol_end, check_every=None, **kw):
@@ -41,31 +38,29 @@ def test_single_matrix_tile_rows(tile_rows):
     _run(W.single_matrix(), 3, TOL_100, check_every=1, tile_rows=tile_rows)
 
 
-def _layer_subset(w, layer_len, head):
-    """Embedding-side tensors except the large vocabulary matrix, plus the first layer."""
-    return list(range(1, head)) + list(range(head, head + layer_len))
+def _vocabulary_and_one_per_shape(w):
+    """Tensor 0 (the vocabulary matrix: the tallest column reduction of the list) plus the first
+    tensor of every other distinct shape, matrices and vectors."""
+    seen, check = set(), []
+    for k, s in enumerate(w.shapes):
+        if s not in seen:
+            seen.add(s)
+            check.append(k)
+    assert check[0] == 0
+    return check
 
 
-def test_bert_base_subset_100_steps():
-    w = W.bert_base()
-    _run(w, 100, TOL_100, check_every=25, indices=_layer_subset(w, 16, 3))
-
-
-def test_gpt2_medium_subset_100_steps_heavy_tails():
-    w = W.gpt2_medium()
-    _run(w, 100, TOL_100, check_every=25, indices=_layer_subset(w, 12, 2))
-
-
-def test_bert_large_bf16_subset_100_steps_zero_rows():
-    w = W.bert_large()
-    _run(w, 100, TOL_100, check_every=25, indices=_layer_subset(w, 16, 3))
-
-
-@pytest.mark.parametrize("make", [W.bert_base, W.gpt2_medium, W.bert_large], ids=lambda f: f.__name__)
-def test_full_list_few_steps(make):
-    """Every tensor of the list in one grouped launch, oracle on all of them."""
+@pytest.mark.parametrize("make,follow", [(W.bert_base, "all"), (W.gpt2_medium, "shapes"), (W.bert_large, "shapes")],
+                         ids=["bert_base", "gpt2_medium", "bert_large"])
+def test_full_list_100_steps(make, follow):
+    """The stated bar on the stated configurations: every tensor of the list in one grouped
+    launch, 100 steps, 1e-5 after the first (incl. the first move theta_1 - theta_0 by itself)
+    and 1e-4 at steps 25, 50, 75, 100.  The oracle follows every tensor of the BERT-base-shaped
+    list; on the two larger lists (where one oracle step of the whole list takes seconds) it
+    follows the vocabulary matrix and one tensor of every other distinct shape, while the
+    library still updates all of them together."""
     w = make()
-    _run(w, 100 if LONG else 2, TOL_100 if LONG else TOL_1 * 2, check_every=25)
+    _run(w, 100, TOL_100, check_every=25, check=None if follow == "all" else _vocabulary_and_one_per_shape(w))
 
 
 def test_llama_full_size_sampled():
@@ -251,11 +246,13 @@ def test_placement_probe_changes_nothing():
         opt = P.CameStep(w.shapes, [w.grad_dtype] * 4, tile_rows=32, place_against=th if probe else None,
                          placement_spacer_bytes=1 << 20)
         for t in range(1, 5):
-            opt.step(th, [gen.grad(i, t) for i in range(4)], P.CameHyper(), 1e-3, t)
+            grads = [gen.grad(i, t) for i in range(4)]
+            opt.step(th, grads, P.CameHyper(), 1e-3, t)
             if probe and t == 2:
                 torch.cuda.synchronize()
                 before = [x.clone() for x in th] + [opt.state_view(0)[k].clone() for k in "MrcRC"]
                 assert opt.probe_placement(th, repeats=3) > 0
+                assert opt.probe_placement(th, grads, repeats=2) > 0   # sweep 2's read streams as well
                 after = th + [opt.state_view(0)[k] for k in "MrcRC"]
                 for a, b in zip(before, after):
                     assert torch.equal(a, b)

@@ -80,8 +80,7 @@ def test_bf16_momentum_halves_the_momentum_bytes():
     assert [P.algorithmic_bytes(2, 2, P.ALGO_CAME, k) for k in (1, 2, 3)] == [2, 4, 14]
     assert P.algorithmic_bytes(3, 4) == 0 and P.algorithmic_bytes(2, 8) == 0
     for g in (2, 4):
-        for k in range(4):
-            assert P.algorithmic_bytes(g, 4, P.ALGO_CAME, k) == P.algorithmic_bytes_per_param(g, k)
+        assert [P.algorithmic_bytes(g, 4, P.ALGO_CAME, k) for k in range(4)] == [20 + 3 * g, g, g + 4, g + 16]
 
 
 def test_groups_split_the_list():
@@ -94,10 +93,10 @@ def test_groups_split_the_list():
 def test_algorithmic_bytes():
     """Three-sweep design: g read three times, M read twice and written once,
     theta read and written once -> 20 + 3 sizeof(g) bytes per parameter."""
-    assert P.algorithmic_bytes_per_param(2) == 26
-    assert P.algorithmic_bytes_per_param(4) == 32
+    assert P.algorithmic_bytes(2) == 26
+    assert P.algorithmic_bytes(4) == 32
     for gb in (2, 4):
-        assert sum(P.algorithmic_bytes_per_param(gb, k) for k in (1, 2, 3)) == P.algorithmic_bytes_per_param(gb)
+        assert sum(P.algorithmic_bytes(gb, which=k) for k in (1, 2, 3)) == P.algorithmic_bytes(gb)
 
 
 def _raw(shapes_rows_cols_ndim_dtype):
