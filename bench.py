@@ -6,7 +6,11 @@ sweep 3 over every tensor) on a synthetic Llama-6.7B-shaped parameter list
 with bf16 gradients and fp32 parameters/state, all resident in HBM before the
 timed region.  Prints ONE JSON line:
 
-  value        parameters updated per second (whole step, wall clock around K steps)
+  value        parameters updated per second (whole step, wall clock around K steps), with the
+               state blob placed by came_probe_placement
+  no_placement the same steps with the state blob where the allocator put it by itself
+  other_workloads  the BERT-Base-, GPT-2-medium- and BERT-Large-shaped lists, timed in the same
+               process after the headline (placed and unplaced)
   roofline     the dominant kernel (sweep 3: reads g, M, theta, writes M, theta) --
                algorithmic bytes per launch / mean launch time, the latter taken
                with HIP events on the step's stream inside the timed region
@@ -84,6 +88,37 @@ def cpu_baseline(w, gen, hyper, lr, budget_s: float = 12.0):
     }
 
 
+def ceilings(torch, dev) -> int:
+    """What this card's memory system gives to plain streaming kernels that are not ours
+    (PyTorch's elementwise / reduction kernels on 4 GiB buffers): the yardstick beside the 8 TB/s
+    the roofline is priced against."""
+    n = (4 << 30) // 4
+    x = torch.ones(n, dtype=torch.float32, device=dev)
+    y = torch.ones(n, dtype=torch.float32, device=dev)
+    z = torch.empty(n, dtype=torch.float32, device=dev)
+    cases = {
+        "read_only_sum": (lambda: torch.sum(x), 4 * n),
+        "write_only_fill": (lambda: z.fill_(1.0), 4 * n),
+        "read_write_in_place_mul": (lambda: x.mul_(1.0), 8 * n),
+        "copy": (lambda: z.copy_(x), 8 * n),
+        "two_reads_one_write_add": (lambda: torch.add(x, y, out=z), 12 * n),
+    }
+    out = {}
+    for name, (fn, nbytes) in cases.items():
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = {"GBs": nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, "bytes_per_launch": nbytes}
+    print(json.dumps({"ceilings": out, "buffer_bytes": 4 * n, "peak_GBs": HBM_PEAK_GBS}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +138,13 @@ def main() -> int:
     ap.add_argument("--no-placement", action="store_true",
                     help="allocate the state blob wherever the allocator puts it (default: probe several "
                          "addresses against the parameters and keep the fastest)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the BERT-Base-, GPT-2-medium- and BERT-Large-shaped lists that the default run times "
+                         "after the headline workload")
+    ap.add_argument("--other-steps", type=int, default=200)
+    ap.add_argument("--ceilings", action="store_true",
+                    help="only time PyTorch's own streaming kernels (sum, fill, in-place multiply, copy, add) on "
+                         "4 GiB buffers: what the memory system gives to kernels that are not this library's")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 4 GiB device-to-device copy a few times: the known-size kernel "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -130,96 +172,128 @@ def main() -> int:
         print(json.dumps({"calibrate_copy_bytes_read": n * 4, "calibrate_copy_bytes_written": n * 4,
                           "launches": 4}), flush=True)
         return 0
+    if args.ceilings:
+        return ceilings(torch, dev)
     w = W.by_name(args.workload)
     if args.grad_dtype != "workload":
         import dataclasses
         w = dataclasses.replace(w, grad_dtype=W.GRAD_F32 if args.grad_dtype == "f32" else W.GRAD_BF16)
-    gen = W.Generator(w, device=dev)
-    n = len(w.shapes)
     hyper = P.CameHyper()
-    lr = w.lr
-
-    theta = [gen.theta0(i) for i in range(n)]
-    # two gradient sets, alternated step by step, so that no random numbers are drawn inside the timed region
-    grad_sets = [[gen.grad(i, t) for i in range(n)] for t in (1, 2)]
     mdt = P.MOMENTUM_BF16 if args.momentum_dtype == "bf16" else P.MOMENTUM_F32
     mbytes = 2 if mdt == P.MOMENTUM_BF16 else 4
-    opt = P.CameStep(w.shapes, [w.grad_dtype] * n, device=dev, tile_rows=args.tile_rows,
-                     group_elements=args.group_elements, momentum_dtype=mdt,
-                     place_against=None if args.no_placement else theta)
-    opt.check_tensors(theta, grad_sets[0])
-    plan = P.plan_query(w.shapes, [w.grad_dtype] * n, tile_rows=args.tile_rows,
-                        group_elements=args.group_elements)
-    torch.cuda.synchronize()
 
-    step_no = 0
-    for _ in range(args.warmup):
-        step_no += 1
-        opt.step(theta, grad_sets[step_no % 2], hyper, lr, step_no)
-    torch.cuda.synchronize()
+    def run(w, steps, warmup, placement):
+        """Times `steps` came_step calls on workload w (after `warmup` untimed ones), everything
+        resident in HBM beforehand.  Returns (figures, context, generator); the caller closes the context."""
+        gen = W.Generator(w, device=dev)
+        n = len(w.shapes)
+        theta = [gen.theta0(i) for i in range(n)]
+        # two gradient sets, alternated step by step: no random numbers are drawn inside the timed region
+        grad_sets = [[gen.grad(i, t) for i in range(n)] for t in (1, 2)]
+        opt = P.CameStep(w.shapes, [w.grad_dtype] * n, device=dev, tile_rows=args.tile_rows,
+                         group_elements=args.group_elements, momentum_dtype=mdt,
+                         place_against=theta if placement else None,
+                         place_against_grads=grad_sets[0] if placement else None)
+        opt.check_tensors(theta, grad_sets[0])
+        torch.cuda.synchronize()
+        step_no = 0
+        for _ in range(warmup):
+            step_no += 1
+            opt.step(theta, grad_sets[step_no % 2], hyper, w.lr, step_no)
+        torch.cuda.synchronize()
+        # one event before each step and one after the last, on the stream the steps run on:
+        # per-step durations (median, min) beside the wall-clock mean
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        opt.profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            step_no += 1
+            marks[k].record()
+            opt.step(theta, grad_sets[step_no % 2], hyper, w.lr, step_no)
+        marks[steps].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        opt.profile_enable(False)
+        phases = opt.profile_read()
+        ms = (t1 - t0) * 1e3 / steps
+        per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+        mid = len(per_step) // 2
+        gb = w.grad_bytes
+        n_matrix = sum(s[0] * s[1] for s in w.shapes if len(s) == 2)
+        bpp = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 0)
+        bmin = 8.0 + gb + 2.0 * mbytes  # every array crosses once: g, M read, M written, theta read and written
+        s3_ms, s3_launches = phases["sweep3"]
+        s3_avg = s3_ms / max(s3_launches, 1)
+        s3_bytes = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 3) * n_matrix * (steps / max(s3_launches, 1))
+        fig = {
+            "ms_per_step": ms,
+            "step_ms": {"median": per_step[mid] if len(per_step) % 2 else 0.5 * (per_step[mid - 1] + per_step[mid]),
+                        "min": per_step[0], "max": per_step[-1]},
+            "value": w.n_params / (ms * 1e-3),
+            "bytes_per_param": bpp,
+            "whole_step_GBs": bpp * w.n_params / (ms * 1e-3) / 1e9,
+            "whole_step_frac": bpp * w.n_params / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "bmin_bytes_per_param": bmin,
+            "bmin_frac": bmin * w.n_params / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "sweep3_avg_launch_ms": s3_avg,
+            "sweep3_bytes_per_launch": s3_bytes,
+            "sweep3_GBs": s3_bytes / (s3_avg * 1e-3) / 1e9 if s3_avg > 0 else 0.0,
+            "phase_ms_per_step": {k: v[0] / steps for k, v in phases.items()},
+            "placement_probe_GBs": [round(g, 1) for _, g in opt.placement_log],
+        }
+        del grad_sets
+        return fig, opt, gen
 
-    # one event before each step and one after the last, on the stream the steps run on:
-    # per-step durations (median, min) beside the wall-clock mean
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    opt.profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step_no += 1
-        marks[k].record()
-        opt.step(theta, grad_sets[step_no % 2], hyper, lr, step_no)
-    marks[args.steps].record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    opt.profile_enable(False)
-    phases = opt.profile_read()
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
-    step_ms = {"median": per_step[len(per_step) // 2] if len(per_step) % 2 else
-               0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2]),
-               "min": per_step[0], "max": per_step[-1]}
-    n_params = w.n_params
-    n_matrix_params = sum(s[0] * s[1] for s in w.shapes if len(s) == 2)
-    value = n_params / (ms_per_step * 1e-3)
-
+    n = len(w.shapes)
+    plan = P.plan_query(w.shapes, [w.grad_dtype] * n, tile_rows=args.tile_rows, group_elements=args.group_elements)
     gb = w.grad_bytes
-    s3_ms, s3_launches = phases["sweep3"]
-    s3_avg_ms = s3_ms / max(s3_launches, 1)
-    # one sweep-3 launch covers every matrix element of a launch group
-    units_per_launch = n_matrix_params * (args.steps / max(s3_launches, 1))
-    step_bpp = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 0)
-    s3_bytes = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 3) * units_per_launch
-    achieved = s3_bytes / (s3_avg_ms * 1e-3) / 1e9 if s3_avg_ms > 0 else 0.0
+
+    # The state blob where the allocator puts it by itself (what a caller gets who does not use
+    # came_probe_placement), then -- unless switched off -- the placed one, which is the headline.
+    plain, plain_opt, gen = run(w, args.steps, args.warmup, placement=False)
+    if args.no_placement:
+        fig, opt = plain, plain_opt
+    else:
+        fig, opt, gen = run(w, args.steps, args.warmup, placement=True)  # the plain blob stays allocated meanwhile
+        plain_opt.close()
+    del plain_opt
+
+    ms_per_step = fig["ms_per_step"]
     roofline = {
         "bound": "hbm",
         "kernel": "sweep3_kernel",
-        "achieved": achieved,
+        "achieved": fig["sweep3_GBs"],
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBS,
+        "frac": fig["sweep3_GBs"] / HBM_PEAK_GBS,
         "traffic": read_traffic(os.path.join(
             ROOT, "profiles", f"sweep3_{args.workload}{'_bf16_momentum' if mbytes == 2 else ''}_traffic.txt"))
         if args.grad_dtype == "workload" else None,
-        "bytes_per_launch": s3_bytes,
-        "avg_launch_ms": s3_avg_ms,
+        "traffic_source": "replayed from the committed rocprofv3 --pmc summary under profiles/ (FETCH_SIZE and "
+                          "WRITE_SIZE need runs of their own); not measured in this run",
+        "bytes_per_launch": fig["sweep3_bytes_per_launch"],
+        "avg_launch_ms": fig["sweep3_avg_launch_ms"],
         "whole_step": {
-            "algorithmic_bytes_per_param": step_bpp,
-            "achieved_GBs": step_bpp * n_params / (ms_per_step * 1e-3) / 1e9,
-            "frac": step_bpp * n_params / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_param": fig["bytes_per_param"],
+            "achieved_GBs": fig["whole_step_GBs"],
+            "frac": fig["whole_step_frac"],
+            # the conservative figure: priced as if every array crossed the memory bus only once
+            "bmin_bytes_per_param": fig["bmin_bytes_per_param"],
+            "bmin_frac": fig["bmin_frac"],
         },
-        "phase_ms_per_step": {k: v[0] / args.steps for k, v in phases.items()},
+        "phase_ms_per_step": fig["phase_ms_per_step"],
     }
 
     out = {
         "metric": "CAME step params updated/sec and achieved HBM GB/s (% of peak), 1 MI355X",
-        "value": value,
+        "value": fig["value"],
         "unit": "params/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "step_ms": step_ms,
+        "step_ms": fig["step_ms"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -227,20 +301,45 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": w.name,
-            "params": n_params,
+            "params": w.n_params,
             "tensors": n,
             "grad_dtype": "bf16" if gb == 2 else "f32",
             "param_state_dtype": "f32",
             "momentum_dtype": args.momentum_dtype,
             "tile_rows": plan["tile_rows"],
             "launch_groups": plan["groups"],
-            "state_placement_probe_GBs": [round(g, 1) for _, g in opt.placement_log],
+            "state_placement_probe_GBs": fig["placement_probe_GBs"],
         },
         "roofline": roofline,
+        # the same list, same steps, with the state blob where the allocator put it (no search)
+        "no_placement": {k: plain[k] for k in ("ms_per_step", "value", "whole_step_frac", "bmin_frac", "sweep3_GBs",
+                                               "phase_ms_per_step")},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, gen, hyper, lr, args.cpu_budget)
+        out["cpu_baseline"] = cpu_baseline(w, gen, hyper, w.lr, args.cpu_budget)
     opt.close()
+    del opt, gen
+    torch.cuda.empty_cache()
+
+    # The lists shaped like the paper's own models (BERT-Base, GPT-2 medium, BERT-Large), timed in
+    # the same process: 200 steps each, placed and unplaced.
+    if args.workload == "llama_7b" and not args.no_other_workloads:
+        others = {}
+        for name in ("bert_base", "gpt2_medium", "bert_large"):
+            ow = W.by_name(name)
+            res = {}
+            for label, placed in (("no_placement", False), ("placed", True)):
+                f, o, _ = run(ow, args.other_steps, 20, placement=placed)
+                o.close()
+                del o
+                torch.cuda.empty_cache()
+                res[label] = {k: f[k] for k in ("ms_per_step", "value", "bytes_per_param", "whole_step_frac", "bmin_frac",
+                                                "sweep3_GBs", "phase_ms_per_step", "placement_probe_GBs")}
+            res["params"] = ow.n_params
+            res["grad_dtype"] = "bf16" if ow.grad_bytes == 2 else "f32"
+            res["steps"] = args.other_steps
+            others[ow.name] = res
+        out["other_workloads"] = others
     print(json.dumps(out), flush=True)
     return 0
 

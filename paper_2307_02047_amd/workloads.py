@@ -102,7 +102,17 @@ def llama_7b() -> Workload:
 CONFIGS = [single_matrix, bert_base, gpt2_medium, bert_large, llama_7b]
 
 
+def square_matrices(k: int, side: int = 4096) -> Workload:
+    """k square bf16-gradient matrices: a list whose size is a chosen multiple of one matrix
+    (used to see what staying inside the on-package cache is worth)."""
+    return Workload(f"square{side}x{k}", [(side, side)] * k, GRAD_BF16, seed=6, steps=2, grad_kind="normal",
+                    scale_range=(1e-4, 1e-2))
+
+
 def by_name(name: str) -> Workload:
+    if name.startswith("square"):  # "square4096x32": 32 matrices of 4096 x 4096
+        side, k = name[len("square"):].split("x")
+        return square_matrices(int(k), int(side))
     for f in CONFIGS:
         w = f()
         if w.name == name or f.__name__ == name:

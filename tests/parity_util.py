@@ -11,7 +11,11 @@ Error measure (stated bar: max relative error 1e-5 after 1 step, 1e-4 after
   * theta_0 ~ 0.02 is ten times larger than the first step's move, so an error in the last
     line of Algorithm 2 (theta_t = theta_{t-1} - eta m_t / sqrt(S_t)) shows in theta diluted
     ten to twenty times.  After step 1 the move itself, theta_1 - theta_0, is therefore
-    compared as well ("dtheta", same measure, same bar).
+    compared as well ("dtheta", same measure, same bar).  theta is stored in binary32, so the
+    library's theta_1 cannot lie closer to the oracle's than half a binary32 spacing of theta_1
+    (up to 3.7e-9 for |theta| < 0.125, which is 2e-6 of a CAME move at eta = 2e-4 and 4e-5 of
+    an Algorithm-1 move at eta = 1e-3): that storage rounding is taken off the difference
+    before it is divided, so that what is left is the error of the update itself.
 The strict elementwise figure max |x - ref| / |ref| of theta and M is printed beside these
 (not asserted: it is unbounded wherever an entry passes through zero).
 """
@@ -34,6 +38,19 @@ def rel_err_signed(x: np.ndarray, ref: np.ndarray) -> float:
     if rms == 0.0:
         return float(np.max(np.abs(x - ref)))
     return float(np.max(np.abs(x - ref) / (np.abs(ref) + rms)))
+
+
+def rel_err_move(th: np.ndarray, th_ref: np.ndarray, th0: np.ndarray) -> float:
+    """Error of the move theta - theta_0 against the oracle's, beyond the binary32 storage
+    rounding of theta: max(0, |d - d_ref| - spacing32(theta)/2) / (|d_ref| + RMS(d_ref))."""
+    d, dref = th - th0, th_ref - th0
+    big = np.maximum(np.abs(th), np.abs(th_ref)).astype(np.float32)
+    half_spacing = 0.5 * np.spacing(big).astype(np.float64)
+    excess = np.maximum(np.abs(d - dref) - half_spacing, 0.0)
+    rms = float(np.sqrt(np.mean(dref * dref)))
+    if rms == 0.0:
+        return float(np.max(excess))
+    return float(np.max(excess / (np.abs(dref) + rms)))
 
 
 def rel_err_strict(x: np.ndarray, ref: np.ndarray) -> float:
@@ -108,7 +125,7 @@ class SideBySide:
             assert np.all(np.isfinite(th)), f"non-finite theta in tensor {self.idx[k]} {self.shapes[k]}"
             upd("theta", rel_err_signed(th, self.otl.theta[pos]), k)
             if self.t == 1:  # the first move itself, not diluted by theta_0
-                upd("dtheta", rel_err_signed(th - self.theta0[pos], self.otl.theta[pos] - self.theta0[pos]), k)
+                upd("dtheta", rel_err_move(th, self.otl.theta[pos], self.theta0[pos]), k)
             Mg = to_f64(sv["M"])
             upd("M", rel_err_signed(Mg, st.M), k)
             self.strict["theta"] = max(self.strict.get("theta", 0.0), rel_err_strict(th, self.otl.theta[pos]))

@@ -185,7 +185,8 @@ def test_free_running_100_steps():
                     f"max |dtheta| {d_th:.2e} (bound {bound_th:.2e}), max |dM| in spacings of the entry's peak |M| "
                     f"{float((d_M / bound_M).max()) * 2.0:.2f} (bound 2)")
             print(line, flush=True)
-            assert (e_th > 1e-4).mean() <= 2e-3 and (e_M > 1e-4).mean() <= 2e-3, line
+            few = max(2e-3, 4.0 / th.size)  # 0.2 % of the entries; a 1024-entry vector may have 4
+            assert (e_th > 1e-4).mean() <= few and (e_M > 1e-4).mean() <= few, line
             assert d_th <= bound_th, line
             assert not (d_M > bound_M).any(), line
             if len(s) == 2:
@@ -196,7 +197,7 @@ def test_free_running_100_steps():
                 assert errs["v"] <= 1e-4
                 e_s = np.abs(to_f64(sv["R"]) - st.s) / st.s
                 errs["s >1e-4"] = float((e_s > 1e-4).mean())
-                assert errs["s >1e-4"] <= 5e-3, errs
+                assert errs["s >1e-4"] <= few, errs
             print("    " + ", ".join(f"{q}={v:.1e}" for q, v in errs.items()), flush=True)
     finally:
         opt.close()
