@@ -202,6 +202,38 @@ int came_step_bf16_copy(came_ctx *ctx, void *const *theta_dev, const void *const
                         void *const *theta_bf16_dev, const came_hyper *hyper, double lr,
                         int64_t step, void *hip_stream);
 
+/*
+ * came_step for callers that cannot allocate device memory or keep a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  One call does what
+ * came_init_state + came_step do, with the library's OWN scratch: a 16 MiB array that is part
+ * of the loaded code object (one copy per GPU, held until the process ends) takes the place
+ * of the caller's scratch blob.  The call allocates and frees no device or pinned memory,
+ * creates no event and copies nothing with a copy engine: the launch plan is rebuilt on the
+ * host (a few KB of ordinary heap) and reaches the GPU inside kernel argument blocks, then
+ * the same kernels as came_step run on hip_stream.  Results are bit-identical to
+ * came_init_state + came_step with the same options.
+ *   descs, count, opts: as for came_init_state; at most 64 tensors, and came_state_size's
+ *     scratch_bytes for them must not exceed 16 MiB (roughly: the matrices' row counts times
+ *     their number of 512-column blocks plus their column counts times their number of row
+ *     blocks, times 24 bytes) and the tile tables 256 KiB -- otherwise CAME_ESIZE and nothing
+ *     is enqueued.
+ *   state_dev, state_bytes: the caller's state blob (device, 256-byte aligned, at least
+ *     came_state_size's state_bytes), input and output; zero_state != 0 zero-fills it first
+ *     (Algorithm 2's M_0 = r_0 = c_0 = 0), which is how the first step starts.
+ *   theta_dev, grad_dev, hyper, lr, step, hip_stream: as for came_step.
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's contents:
+ * each call rewrites the tables and clears the scalars it needs, so calls of any sizes may
+ * follow each other on one stream (or on streams ordered with each other), but calls that
+ * overlap in time on one GPU race on it.  The first call on a device resolves the array's
+ * device address (which may load the code object there): make it outside stream capture.
+ * A failed HIP call gives CAME_EHIP; came_last_hip_error(NULL) then returns the hipError_t of
+ * the last such failure on the calling thread.
+ */
+int came_step_noalloc(const came_tensor_desc *descs, int32_t count, const came_options *opts,
+                      void *state_dev, size_t state_bytes, int32_t zero_state, void *const *theta_dev,
+                      const void *const *grad_dev, const came_hyper *hyper, double lr, int64_t step,
+                      void *hip_stream);
+
 /* Device addresses of tensor i's state arrays, for checkpointing and tests: the quantities
  * Algorithm 2 carries from one iteration to the next -- m, r, c of its input list and the
  * confidence statistics R, C of its last lines (both start at zero like r, c). */
@@ -266,7 +298,8 @@ int came_probe_placement(came_ctx *ctx, void *const *theta_dev, const void *cons
 int came_profile_enable(came_ctx *ctx, int32_t on);
 int came_profile_read(came_ctx *ctx, double phase_ms[6], int64_t phase_launches[6]);
 
-/* hipError_t of the last failed HIP call on this context (0 if none). */
+/* hipError_t of the last failed HIP call on this context (0 if none); with ctx == NULL, of the
+ * last failed HIP call inside came_step_noalloc on the calling thread. */
 int came_last_hip_error(const came_ctx *ctx);
 
 /* Releases the host context.  Does not touch or free any device memory and

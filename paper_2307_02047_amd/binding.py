@@ -18,7 +18,7 @@ ALGO_CAME, ALGO_ADAFACTOR = 0, 1
 MOMENTUM_F32, MOMENTUM_BF16 = 0, 1
 VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY = 0, 1
 
-EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_step_bf16_copy", "came_state_view_get",
+EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_step_bf16_copy", "came_step_noalloc", "came_state_view_get",
            "came_plan_query", "came_algorithmic_bytes", "came_probe_placement", "came_profile_enable",
            "came_profile_read", "came_last_hip_error",
            "came_destroy", "came_strerror")
@@ -89,6 +89,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.came_step_bf16_copy.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                         ctypes.POINTER(_Hyper), dbl, i64, vp]
     lib.came_step_bf16_copy.restype = ctypes.c_int
+    lib.came_step_noalloc.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), vp, ctypes.c_size_t, i32,
+                                      ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(_Hyper), dbl, i64, vp]
+    lib.came_step_noalloc.restype = ctypes.c_int
     lib.came_state_view_get.argtypes = [vp, i32, ctypes.POINTER(_View)]
     lib.came_state_view_get.restype = ctypes.c_int
     lib.came_plan_query.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), ctypes.POINTER(i64)]
@@ -176,6 +179,25 @@ def plan_query(shapes, grad_dtypes, **opts) -> dict:
 
 def algorithmic_bytes(grad_bytes: int, momentum_bytes: int = 4, algo: int = ALGO_CAME, which: int = 0) -> float:
     return float(load_library().came_algorithmic_bytes(int(grad_bytes), int(momentum_bytes), int(algo), int(which)))
+
+
+def step_noalloc(shapes, grad_dtypes, state, zero_state: bool, thetas, grads, hyper: CameHyper, lr: float, step: int,
+                 stream=None, **opts) -> None:
+    """came_step_noalloc: one step on the library's own scratch.  `state` is the caller's uint8
+    state blob (state_size()'s bytes, 256-byte aligned)."""
+    import torch
+    lib = load_library()
+    n = len(shapes)
+    d, o = _descs(shapes, grad_dtypes), _options(**opts)
+    th = (ctypes.c_void_p * n)(*[t.data_ptr() for t in thetas])
+    gr = (ctypes.c_void_p * n)(*[g.data_ptr() for g in grads])
+    h = hyper._c()
+    with torch.cuda.device(state.device):
+        s = stream if stream is not None else torch.cuda.current_stream(state.device).cuda_stream
+        st = lib.came_step_noalloc(d, n, ctypes.byref(o), state.data_ptr(), state.numel(), 1 if zero_state else 0,
+                                   th, gr, ctypes.byref(h), float(lr), int(step), s)
+    if st != 0:
+        raise CameError(st, f"came_step_noalloc: {lib.came_strerror(st).decode()}", lib.came_last_hip_error(None))
 
 
 class CameStep:

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -182,6 +183,70 @@ int guarded(F body) noexcept
     } catch (...) {
         return CAME_EINVAL;
     }
+}
+
+// ---------------------------------------------------------------- library-owned scratch
+//
+// came_step_noalloc keeps its tables and partial sums in this array instead of a scratch blob
+// of the caller's.  Every GPU that loads the library holds its own copy until the process
+// ends.  In host code the name below is only a handle for hipGetSymbolAddress: the device
+// address is resolved once per device and kept in static_scratch_ptr[]; every use on the
+// host (kernel arguments, table pointers) goes through that pointer.
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;
+constexpr int kMaxDevices = 64;
+constexpr int32_t kNoallocMaxTensors = 64;
+constexpr size_t kNoallocMaxTableBytes = size_t(256) << 10;
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+char* static_scratch_ptr[kMaxDevices] = {};
+std::mutex static_scratch_mutex;
+thread_local int noalloc_last_hip = 0;
+
+// Address of this device's copy of `scratch`, resolved at the first call on the device.
+int static_scratch_of_current_device(char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { noalloc_last_hip = static_cast<int>(e); return CAME_EHIP; }
+    if (dev < 0 || dev >= kMaxDevices) return CAME_EINVAL;
+    std::lock_guard<std::mutex> lock(static_scratch_mutex);
+    if (!static_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) { noalloc_last_hip = static_cast<int>(e); return CAME_EHIP; }
+        static_scratch_ptr[dev] = static_cast<char*>(ptr);
+    }
+    *out = static_scratch_ptr[dev];
+    return CAME_OK;
+}
+
+// Host words -> device memory without a copy engine, a staging buffer or a wait: the words
+// travel in the kernel's argument block (copied when the launch is enqueued), so the call is
+// safe while a stream is being captured and the host buffer may be reused at once.
+constexpr int kPokeWords = 768;  // 3 KiB of a 4 KiB argument block
+struct PokeWords { uint32_t w[kPokeWords]; };
+
+__global__ __launch_bounds__(256) void poke_kernel(uint32_t* dst, PokeWords words, int32_t count)
+{
+    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = words.w[i];
+}
+
+hipError_t poke(char* dst, const void* src, size_t bytes, hipStream_t s)
+{
+    const uint32_t* w = static_cast<const uint32_t*>(src);
+    size_t left = bytes / sizeof(uint32_t);  // every table is a whole number of words
+    uint32_t* d = reinterpret_cast<uint32_t*>(dst);
+    while (left > 0) {
+        const int32_t n = static_cast<int32_t>(std::min<size_t>(left, kPokeWords));
+        PokeWords pw;
+        std::memcpy(pw.w, w, sizeof(uint32_t) * n);
+        poke_kernel<<<dim3(1), dim3(256), 0, s>>>(d, pw, n);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        w += n; d += n; left -= n;
+    }
+    return hipSuccess;
 }
 
 }  // namespace
@@ -414,6 +479,54 @@ int came_step_bf16_copy(came_ctx* ctx, void* const* theta_dev, const void* const
     });
 }
 
+int came_step_noalloc(const came_tensor_desc* descs, int32_t count, const came_options* opts,
+                      void* state_dev, size_t state_bytes, int32_t zero_state, void* const* theta_dev,
+                      const void* const* grad_dev, const came_hyper* hyper, double lr, int64_t step,
+                      void* hip_stream)
+{
+    return guarded([&]() -> int {
+        if (!state_dev || count > kNoallocMaxTensors) return !state_dev ? CAME_EINVAL : CAME_ESIZE;
+        Plan p;  // host memory only
+        int rc = build_plan(descs, count, opts, &p);
+        if (rc != CAME_OK) return rc;
+        const size_t table_bytes = sizeof(TensorMeta) * p.metas.size() + sizeof(WorkItem) * p.items.size() +
+                                   sizeof(FinalizeItem) * p.fins.size() + sizeof(void*) * kPtrArrays * p.descs.size();
+        if (p.scratch_bytes > kStaticScratchBytes || table_bytes > kNoallocMaxTableBytes) return CAME_ESIZE;
+        if (state_bytes < p.state_bytes) return CAME_ESIZE;
+        if (!aligned_to(state_dev, 256)) return CAME_EALIGN;
+        rc = check_step_arguments(p, theta_dev, grad_dev, nullptr, hyper, lr, step);
+        if (rc != CAME_OK) return rc;
+        char* sp = nullptr;
+        rc = static_scratch_of_current_device(&sp);
+        if (rc != CAME_OK) return rc;
+        rc = check_overlaps(p, state_dev, sp, kStaticScratchBytes, theta_dev, grad_dev, nullptr);
+        if (rc != CAME_OK) return rc;
+
+        hipStream_t s = static_cast<hipStream_t>(hip_stream);
+        auto failed = [&](hipError_t e) { noalloc_last_hip = static_cast<int>(e); return CAME_EHIP; };
+        // tables of this call; the array still holds the previous call's
+        hipError_t e = poke(sp + p.off_metas, p.metas.data(), sizeof(TensorMeta) * p.metas.size(), s);
+        if (e == hipSuccess && !p.items.empty()) e = poke(sp + p.off_items, p.items.data(), sizeof(WorkItem) * p.items.size(), s);
+        if (e == hipSuccess && !p.fins.empty()) e = poke(sp + p.off_fins, p.fins.data(), sizeof(FinalizeItem) * p.fins.size(), s);
+        if (e != hipSuccess) return failed(e);
+        {
+            // pointer table, slot 0: theta[count], grad[count], no bfloat16 copies
+            const void* ptrs[kPtrArrays * kNoallocMaxTensors] = {};
+            for (int32_t t = 0; t < count; ++t) {
+                ptrs[t] = theta_dev[t];
+                ptrs[count + t] = grad_dev[t];
+            }
+            e = poke(sp + p.off_ptrs, ptrs, sizeof(void*) * kPtrArrays * count, s);
+            if (e != hipSuccess) return failed(e);
+        }
+        // what came_init_state clears: the per-tensor scalars, and the state when asked to
+        e = launch_fill_zero_bytes(sp + p.off_scalars, sizeof(TensorScalars) * p.descs.size(), s);
+        if (e == hipSuccess && zero_state) e = launch_fill_zero(static_cast<float*>(state_dev), p.state_bytes / sizeof(float), s);
+        if (e != hipSuccess) return failed(e);
+        return enqueue_step(nullptr, p, tables_in(p, sp, static_cast<float*>(state_dev), 0), hyper, lr, s, &noalloc_last_hip);
+    });
+}
+
 int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
 {
     if (!ctx || !view) return CAME_EINVAL;
@@ -531,7 +644,7 @@ int came_profile_read(came_ctx* ctx, double phase_ms[6], int64_t phase_launches[
     });
 }
 
-int came_last_hip_error(const came_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+int came_last_hip_error(const came_ctx* ctx) { return ctx ? ctx->last_hip : noalloc_last_hip; }
 
 void came_destroy(came_ctx* ctx)
 {

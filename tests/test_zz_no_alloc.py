@@ -1,0 +1,75 @@
+"""came_step_noalloc (the entry point that allocates nothing and works on the library's own
+scratch array) against came_init_state + came_step on the same inputs, through the C ABI.
+
+Both run the same kernels on the same plan, so every parameter and every state array must agree
+bit for bit -- which also puts the new entry point within the parity bar of the existing one.
+Two runs in a row share the one array, the second with a smaller list, so that anything the
+first run left behind (tables, partial sums, scalars of tensors that no longer exist) would
+show; then sizes beyond the array are refused."""
+import ctypes
+
+import pytest
+import torch
+
+import paper_2307_02047_amd as P
+from paper_2307_02047_amd import binding as B
+from paper_2307_02047_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _both_ways(shapes, dtype, seed, steps, tile_rows):
+    n = len(shapes)
+    w = W.Workload("noalloc", shapes, dtype, seed=seed, steps=steps, grad_kind="normal", scale_range=(1e-3, 1e-1),
+                   zero_row_fraction=0.05)
+    gen = W.Generator(w, device="cuda:0")
+    h = P.CameHyper()
+    ref = P.CameStep(shapes, [dtype] * n, tile_rows=tile_rows)
+    th_ref = [gen.theta0(i) for i in range(n)]
+    th_new = [gen.theta0(i) for i in range(n)]
+    state_bytes, scratch_bytes = P.state_size(shapes, [dtype] * n, tile_rows=tile_rows)
+    assert scratch_bytes <= 16 << 20
+    # the state starts as garbage: the first call is asked to clear it
+    state = torch.full((state_bytes,), 0x5A, dtype=torch.uint8, device="cuda:0")
+    try:
+        for t in range(1, steps + 1):
+            g = [gen.grad(i, t) for i in range(n)]
+            ref.step(th_ref, g, h, 1e-3, t)
+            P.step_noalloc(shapes, [dtype] * n, state, t == 1, th_new, g, h, 1e-3, t, tile_rows=tile_rows)
+            torch.cuda.synchronize()
+            for i in range(n):
+                assert torch.equal(th_ref[i], th_new[i]), f"step {t}: parameter {i} {shapes[i]} differs"
+            assert torch.equal(ref.state, state), f"step {t}: state differs"
+    finally:
+        ref.close()
+
+
+def test_noalloc_matches_came_step_twice_the_second_time_smaller():
+    big = [(300, 1032), (1032,), (257, 520), (64, 2048), (40, 13), (20000,), (5, 8), (77,)]
+    _both_ways(big, W.GRAD_BF16, seed=301, steps=3, tile_rows=16)
+    small = [(33, 520), (9,), (130, 24)]
+    _both_ways(small, W.GRAD_F32, seed=302, steps=3, tile_rows=8)
+    # and a larger one again, default tile height
+    _both_ways(big[:5], W.GRAD_F32, seed=303, steps=2, tile_rows=0)
+
+
+def test_noalloc_refuses_what_does_not_fit():
+    lib = P.load_library()
+    h = P.CameHyper()._c()
+
+    def call(shapes, state_bytes_given=None, theta=None, grad=None):
+        n = len(shapes)
+        d, o = B._descs(shapes, [0] * n), B._options()
+        sb, _ = P.state_size(shapes, [0] * n) if n <= 1000 else (0, 0)
+        state = torch.zeros(min(sb, 1 << 20), dtype=torch.uint8, device="cuda:0")
+        th = theta or [torch.zeros(8, device="cuda:0") for _ in range(n)]
+        gr = grad or [torch.zeros(8, device="cuda:0") for _ in range(n)]
+        tp = (ctypes.c_void_p * n)(*[t.data_ptr() for t in th])
+        gp = (ctypes.c_void_p * n)(*[t.data_ptr() for t in gr])
+        return lib.came_step_noalloc(d, n, ctypes.byref(o), state.data_ptr(), sb if state_bytes_given is None else state_bytes_given,
+                                     1, tp, gp, ctypes.byref(h), 1e-3, 1, None)
+
+    assert call([(4096, 4096)] * 4) == -2            # partial sums beyond the 16 MiB array
+    assert call([(8,)] * 65) == -2                   # more than 64 tensors
+    assert call([(64, 64)], state_bytes_given=16) == -2   # state blob too small
+    torch.cuda.synchronize()
