@@ -58,7 +58,12 @@ typedef enum {
     CAME_ESIZE = -2,  /* state or scratch blob smaller than came_state_size reports */
     CAME_EALIGN = -3, /* a device pointer is not aligned as documented */
     CAME_EHIP = -4,   /* a HIP runtime call failed; see came_last_hip_error */
-    CAME_ENOMEM = -5  /* host allocation failed */
+    CAME_ENOMEM = -5, /* host allocation failed */
+    CAME_ETIMEOUT = -6 /* a wait inside the on-chip kernel of an earlier step ran into its time limit
+                          (came_options.resident_wait_us): the workgroups gave up waiting and ran to
+                          their end, so nothing hangs, but the state and parameters of the matrices
+                          that take the on-chip path are undefined from that step on.  Sticky until
+                          came_destroy */
 } came_status;
 
 typedef enum {
@@ -89,6 +94,19 @@ typedef enum {
                                      no confidence; their s stays zero); matrices are unaffected.  A
                                      convention of some trainers, not the paper's */
 } came_vector_rule;
+
+typedef enum {
+    CAME_RESIDENT_AUTO = 0, /* the planner's default: CAME_RESIDENT_ON, unless tile_rows or group_elements is
+                               set (a caller who shapes the streaming launches gets them) */
+    CAME_RESIDENT_OFF = 1,  /* every matrix takes the three streaming sweeps */
+    CAME_RESIDENT_ON = 2    /* matrices small enough take the on-chip path: their gradient and
+                               momentum tiles stay in LDS across the two whole-tensor
+                               dependencies of Algorithm 2 (r_t, c_t before any u_t; RMS(u_t) of
+                               Eq. 1 before any u^_t), so g, M and theta cross the memory bus once
+                               per step instead of three, two and one times.  Same arithmetic per
+                               element; the partial sums are added in a different (fixed) order, so
+                               results agree with the streaming path to rounding, not bit for bit */
+} came_resident_mode;
 
 /* One parameter tensor.  ndim == 2: rows x cols matrix (factored statistics).
  * ndim == 1: vector of `rows` entries, cols must be 1 (unfactored statistics).
@@ -129,7 +147,15 @@ typedef struct {
                                 between phases */
     int32_t momentum_dtype;  /* came_momentum_dtype, for every tensor of the context */
     int32_t vector_rule;     /* came_vector_rule */
-    int32_t reserved[2];     /* must be zero */
+    int32_t resident;        /* came_resident_mode.  A matrix takes the on-chip path when its columns
+                                are a multiple of 8, Algorithm 2 is selected and its
+                                ceil(rows/16) * ceil(cols/512) tiles fit the co-resident grid (512
+                                workgroups on MI355X); came_plan_traffic reports what was chosen */
+    int32_t resident_wait_us; /* upper bound, in microseconds, of any single wait of a workgroup of
+                                the on-chip kernel for the others of its matrix; 0 = 2 000 000.  When
+                                it runs out the kernel flags the failure, every workgroup stops
+                                waiting and the launch ends normally; the next came_step or
+                                came_device_status on the context returns CAME_ETIMEOUT */
 } came_options;
 
 /* Device addresses of one tensor's state inside the caller's state blob.
@@ -210,8 +236,10 @@ int came_step_bf16_copy(came_ctx *ctx, void *const *theta_dev, const void *const
  * of the caller's scratch blob.  The call allocates and frees no device or pinned memory,
  * creates no event and copies nothing with a copy engine: the launch plan is rebuilt on the
  * host (a few KB of ordinary heap) and reaches the GPU inside kernel argument blocks, then
- * the same kernels as came_step run on hip_stream.  Results are bit-identical to
- * came_init_state + came_step with the same options.
+ * the streaming kernels of came_step run on hip_stream (never the on-chip path of
+ * came_options.resident, which needs a context to report to: CAME_RESIDENT_ON is refused with
+ * CAME_EINVAL, CAME_RESIDENT_AUTO means off here).  Results are bit-identical to
+ * came_init_state + came_step with the same options and CAME_RESIDENT_OFF.
  *   descs, count, opts: as for came_init_state; at most 64 tensors, and came_state_size's
  *     scratch_bytes for them must not exceed 16 MiB (roughly: the matrices' row counts times
  *     their number of 512-column blocks plus their column counts times their number of row
@@ -234,6 +262,14 @@ int came_step_noalloc(const came_tensor_desc *descs, int32_t count, const came_o
                       const void *const *grad_dev, const came_hyper *hyper, double lr, int64_t step,
                       void *hip_stream);
 
+/*
+ * Waits for hip_stream and reports whether the on-chip kernel of any step so far gave up a wait
+ * (CAME_ETIMEOUT, see there), else CAME_OK.  came_step itself reports the same condition as soon
+ * as it is visible on the host, without waiting.  Must not be called while the stream is
+ * capturing.
+ */
+int came_device_status(came_ctx *ctx, void *hip_stream);
+
 /* Device addresses of tensor i's state arrays, for checkpointing and tests: the quantities
  * Algorithm 2 carries from one iteration to the next -- m, r, c of its input list and the
  * confidence statistics R, C of its last lines (both start at zero like r, c). */
@@ -249,6 +285,17 @@ int came_plan_query(const came_tensor_desc *descs, int32_t count, const came_opt
                     int64_t out[8]);
 
 /*
+ * What the planner chose for the list and what one step then moves (host only, no device):
+ * out[0] = matrices on the on-chip path, out[1] = their elements,
+ * out[2] = algorithmic HBM bytes of one step of the whole list as planned (streaming matrices
+ *          came_algorithmic_bytes(.., 0) per element, on-chip ones came_algorithmic_bytes(.., 4),
+ *          1-D parameters 24 + grad_bytes + 2*momentum_bytes),
+ * out[3] = the same if every matrix took the streaming path.
+ */
+int came_plan_traffic(const came_tensor_desc *descs, int32_t count, const came_options *opts,
+                      double out[4]);
+
+/*
  * Algorithmic HBM bytes per parameter of the shipped three-sweep design (the count the
  * roofline fraction is priced with; derived from the dependency chain of Algorithm 2:
  * r_t, c_t complete before any u_t, RMS(u_t) of Eq. 1 complete before any u^_t, m_t).
@@ -257,7 +304,10 @@ int came_plan_query(const came_tensor_desc *descs, int32_t count, const came_opt
  * and M; sweep 3 reads g, M, theta and writes M, theta:
  *   8 + 3*grad_bytes + 3*momentum_bytes   (Algorithm 1: ... + 2*momentum_bytes),
  * i.e. 20 + 3*grad_bytes with a binary32 momentum.
- * which: 0 = whole step, 1/2/3 = that sweep alone.  Returns 0 for arguments out of range.
+ * which: 0 = whole step, 1/2/3 = that sweep alone, 4 = whole step of a matrix on the on-chip
+ * path (came_options.resident): g, M and theta read once, M and theta written once,
+ *   8 + grad_bytes + 2*momentum_bytes,
+ * the compulsory count.  Returns 0 for arguments out of range.
  */
 double came_algorithmic_bytes(int32_t grad_bytes, int32_t momentum_bytes, int32_t algo, int32_t which);
 
@@ -288,15 +338,15 @@ int came_probe_placement(came_ctx *ctx, void *const *theta_dev, const void *cons
  * Built-in phase timer.  While enabled, came_step brackets each of its
  * launches with HIP events on the step's stream.  came_profile_read waits for
  * the recorded events, adds the elapsed milliseconds and launch counts per
- * phase { sweep 1, finalize 1, sweep 2, finalize 2, sweep 3, vectors } since
- * the previous read into phase_ms[6] / phase_launches[6], and forgets them.
+ * phase { sweep 1, finalize 1, sweep 2, finalize 2, sweep 3, vectors, on-chip kernel } since
+ * the previous read into phase_ms[7] / phase_launches[7], and forgets them.
  * "vectors" counts only launches of their own (long 1-D parameters, groups
  * without a matrix); ordinary 1-D parameters are updated inside the sweep-1
  * launch and count there.
  * At most 65536 launches are kept between reads; further ones go untimed.
  */
 int came_profile_enable(came_ctx *ctx, int32_t on);
-int came_profile_read(came_ctx *ctx, double phase_ms[6], int64_t phase_launches[6]);
+int came_profile_read(came_ctx *ctx, double phase_ms[7], int64_t phase_launches[7]);
 
 /* hipError_t of the last failed HIP call on this context (0 if none); with ctx == NULL, of the
  * last failed HIP call inside came_step_noalloc on the calling thread. */

@@ -6,7 +6,8 @@ memory and streams.
 """
 from .binding import (CameHyper, CameStep, GRAD_BF16, GRAD_F32, ALGO_CAME, ALGO_ADAFACTOR,  # noqa: F401
                       MOMENTUM_F32, MOMENTUM_BF16, VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY, CameError, algorithmic_bytes,
-                      load_library, plan_query, state_size, step_noalloc)
+                      RESIDENT_AUTO, RESIDENT_OFF, RESIDENT_ON, ETIMEOUT,
+                      load_library, plan_query, plan_traffic, state_size, step_noalloc)
 
 
 def __getattr__(name):

@@ -17,9 +17,11 @@ GRAD_F32, GRAD_BF16 = 0, 1
 ALGO_CAME, ALGO_ADAFACTOR = 0, 1
 MOMENTUM_F32, MOMENTUM_BF16 = 0, 1
 VECTOR_ALGORITHM2, VECTOR_MOMENTUM_ONLY = 0, 1
+RESIDENT_AUTO, RESIDENT_OFF, RESIDENT_ON = 0, 1, 2
+ETIMEOUT = -6
 
 EXPORTS = ("came_state_size", "came_init_state", "came_step", "came_step_bf16_copy", "came_step_noalloc", "came_state_view_get",
-           "came_plan_query", "came_algorithmic_bytes", "came_probe_placement", "came_profile_enable",
+           "came_plan_query", "came_plan_traffic", "came_device_status", "came_algorithmic_bytes", "came_probe_placement", "came_profile_enable",
            "came_profile_read", "came_last_hip_error",
            "came_destroy", "came_strerror")
 
@@ -43,7 +45,7 @@ class _Hyper(ctypes.Structure):
 class _Options(ctypes.Structure):
     _fields_ = [("tile_rows", ctypes.c_int32), ("algo", ctypes.c_int32),
                 ("group_elements", ctypes.c_int64), ("momentum_dtype", ctypes.c_int32),
-                ("vector_rule", ctypes.c_int32), ("reserved", ctypes.c_int32 * 2)]
+                ("vector_rule", ctypes.c_int32), ("resident", ctypes.c_int32), ("resident_wait_us", ctypes.c_int32)]
 
 
 class _View(ctypes.Structure):
@@ -96,6 +98,10 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.came_state_view_get.restype = ctypes.c_int
     lib.came_plan_query.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), ctypes.POINTER(i64)]
     lib.came_plan_query.restype = ctypes.c_int
+    lib.came_plan_traffic.argtypes = [ctypes.POINTER(_Desc), i32, ctypes.POINTER(_Options), ctypes.POINTER(dbl)]
+    lib.came_plan_traffic.restype = ctypes.c_int
+    lib.came_device_status.argtypes = [vp, vp]
+    lib.came_device_status.restype = ctypes.c_int
     lib.came_algorithmic_bytes.argtypes = [i32, i32, i32, i32]
     lib.came_algorithmic_bytes.restype = dbl
     lib.came_probe_placement.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i32, ctypes.POINTER(dbl)]
@@ -142,10 +148,12 @@ def _descs(shapes: Sequence[Sequence[int]], grad_dtypes: Sequence[int]):
 
 
 def _options(tile_rows: int = 0, algo: int = ALGO_CAME, group_elements: int = 0,
-             momentum_dtype: int = MOMENTUM_F32, vector_rule: int = VECTOR_ALGORITHM2):
+             momentum_dtype: int = MOMENTUM_F32, vector_rule: int = VECTOR_ALGORITHM2,
+             resident: int = RESIDENT_AUTO, resident_wait_us: int = 0):
     o = _Options()
     o.tile_rows, o.algo, o.group_elements = int(tile_rows), int(algo), int(group_elements)
     o.momentum_dtype, o.vector_rule = int(momentum_dtype), int(vector_rule)
+    o.resident, o.resident_wait_us = int(resident), int(resident_wait_us)
     return o
 
 
@@ -175,6 +183,16 @@ def plan_query(shapes, grad_dtypes, **opts) -> dict:
     keys = ("tile_rows", "tile_cols", "sweep_items", "finalize_items", "groups", "matrices", "vectors",
             "elements")
     return dict(zip(keys, [int(x) for x in out]))
+
+
+def plan_traffic(shapes, grad_dtypes, **opts) -> dict:
+    """came_plan_traffic as a dict.  Host only."""
+    lib = load_library()
+    d, o = _descs(shapes, grad_dtypes), _options(**opts)
+    out = (ctypes.c_double * 4)()
+    _check(lib, lib.came_plan_traffic(d, len(shapes), ctypes.byref(o), out), "came_plan_traffic")
+    return {"resident_matrices": int(out[0]), "resident_elements": int(out[1]), "bytes_per_step": float(out[2]),
+            "bytes_per_step_streaming": float(out[3])}
 
 
 def algorithmic_bytes(grad_bytes: int, momentum_bytes: int = 4, algo: int = ALGO_CAME, which: int = 0) -> float:
@@ -209,7 +227,8 @@ class CameStep:
 
     def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
                  group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32,
-                 vector_rule: int = VECTOR_ALGORITHM2, place_against=None, place_against_grads=None,
+                 vector_rule: int = VECTOR_ALGORITHM2, resident: int = RESIDENT_AUTO, resident_wait_us: int = 0,
+                 place_against=None, place_against_grads=None,
                  placement_candidates: int = 8, placement_spacer_bytes: int = 16 << 30,
                  placement_accept_ratio: float = 1.12, placement_reserve_bytes: int = 2 << 30, blobs=None):
         """blobs: (state, scratch), two uint8 tensors on `device` of at least state_size()'s bytes
@@ -233,7 +252,7 @@ class CameStep:
         self.grad_dtypes = [int(d) for d in grad_dtypes]
         self.device = torch.device(device)
         self._d = _descs(self.shapes, self.grad_dtypes)
-        self._o = _options(tile_rows, algo, group_elements, momentum_dtype, vector_rule)
+        self._o = _options(tile_rows, algo, group_elements, momentum_dtype, vector_rule, resident, resident_wait_us)
         self.momentum_dtype = int(momentum_dtype)
         n = len(self.shapes)
         sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
@@ -392,15 +411,22 @@ class CameStep:
         return {"M": M, "r": sl(v.r, n, (n,)), "c": sl(v.c, m, (m,)),
                 "R": sl(v.R, n, (n,)), "C": sl(v.C, m, (m,))}
 
-    PHASES = ("sweep1", "finalize1", "sweep2", "finalize2", "sweep3", "vectors")
+    PHASES = ("sweep1", "finalize1", "sweep2", "finalize2", "sweep3", "vectors", "resident")
+
+    def device_status(self, stream=None) -> int:
+        """came_device_status: waits for the stream; 0, or ETIMEOUT when the on-chip kernel gave up a wait."""
+        torch = self._torch
+        with torch.cuda.device(self.device):
+            s = stream if stream is not None else torch.cuda.current_stream(self.device).cuda_stream
+            return int(self.lib.came_device_status(self._ctx, s))
 
     def profile_enable(self, on: bool = True) -> None:
         _check(self.lib, self.lib.came_profile_enable(self._ctx, 1 if on else 0), "came_profile_enable")
 
     def profile_read(self) -> dict:
         """came_profile_read: {phase: (total_ms, launches)} since the previous read."""
-        ms = (ctypes.c_double * 6)()
-        cnt = (ctypes.c_int64 * 6)()
+        ms = (ctypes.c_double * 7)()
+        cnt = (ctypes.c_int64 * 7)()
         _check(self.lib, self.lib.came_profile_read(self._ctx, ms, cnt), "came_profile_read", self._ctx)
         return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(self.PHASES)}
 

@@ -23,6 +23,7 @@ struct came_ctx {
     float* state = nullptr;   // caller's state blob (device)
     // pinned host staging for the per-step pointer table, one region per slot
     char* pinned = nullptr;
+    int32_t* fail_host = nullptr;  // inside `pinned`: set by the on-chip kernel when a wait ran out
     hipEvent_t slot_event[kPtrSlots] = {};
     bool slot_used[kPtrSlots] = {};
     int slot = -1;
@@ -64,6 +65,20 @@ hipError_t timed_launch(came_ctx* ctx, int phase, hipStream_t s, F launch)
     if (e != hipSuccess) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); return e; }
     ctx->timed.push_back(t);
     return hipSuccess;
+}
+
+constexpr uint64_t kTicksPerMicrosecond = 100;  // the constant clock the on-chip kernel times its waits with
+constexpr int32_t kDefaultResidentWaitUs = 2000000;
+
+// Where the on-chip kernel reports a wait that ran out, and how long it may wait.
+ResidentCtl resident_ctl(const Plan& p, char* scratch, int32_t* fail_host)
+{
+    ResidentCtl c{};
+    c.fail_dev = reinterpret_cast<int32_t*>(scratch + p.off_sync + sizeof(ResidentSync) * p.descs.size());
+    c.fail_host = fail_host;
+    c.regions = scratch + p.off_regions;
+    c.limit_ticks = kTicksPerMicrosecond * static_cast<uint64_t>(p.resident_wait_us > 0 ? p.resident_wait_us : kDefaultResidentWaitUs);
+    return c;
 }
 
 // Device-side views of a plan's tables inside a scratch blob, with pointer-table slot `slot`.
@@ -296,6 +311,7 @@ double came_algorithmic_bytes(int32_t grad_bytes, int32_t momentum_bytes, int32_
     const double s1 = g;                                          // read g
     const double s2 = g + (algo == CAME_ALGO_CAME ? mb : 0.0);    // read g (and M)
     const double s3 = g + 2.0 * mb + 8.0;                         // read g, M, theta; write M, theta
+    if (which == 4) return algo == CAME_ALGO_CAME ? s3 : 0.0;     // on-chip path: every array crosses once
     switch (which) {
         case 0: return s1 + s2 + s3;
         case 1: return s1;
@@ -327,8 +343,32 @@ int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count
         ctx->scratch = static_cast<char*>(scratch_dev);
         hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), p.ptr_slot_bytes * kPtrSlots, hipHostMallocDefault);
+        hipError_t e = hipSuccess;
+        if (p.n_resident > 0) {
+            // the on-chip path relies on all kResidentGrid workgroups being on the chip at once: the
+            // launches are cooperative (the runtime refuses what does not fit), and the plan, made
+            // without a device, is checked here against what this device and this build give
+            int dev = -1, cus = 0, coop = 0;
+            e = hipGetDevice(&dev);
+            if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e == hipSuccess) e = hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev);
+            if (e != hipSuccess) return CAME_EHIP;
+            if (!coop) return CAME_EHIP;
+            for (int v = 0; v < kVariants; ++v) {
+                bool present = false;
+                for (const Group& g : p.groups) present = present || g.res_end[v] > g.res_begin[v];
+                if (!present) continue;
+                int per_cu = 0;
+                e = resident_occupancy(v, &per_cu);
+                if (e != hipSuccess) return CAME_EHIP;
+                if (static_cast<int64_t>(per_cu) * cus < kResidentGrid) return CAME_EHIP;
+            }
+        }
+        constexpr size_t kFlagBytes = 256;
+        e = hipHostMalloc(reinterpret_cast<void**>(&ctx->pinned), p.ptr_slot_bytes * kPtrSlots + kFlagBytes, hipHostMallocDefault);
         if (e != hipSuccess) { ctx->pinned = nullptr; return CAME_EHIP; }
+        ctx->fail_host = reinterpret_cast<int32_t*>(ctx->pinned + p.ptr_slot_bytes * kPtrSlots);
+        *ctx->fail_host = 0;
         for (int k = 0; k < kPtrSlots; ++k) {
             e = hipEventCreateWithFlags(&ctx->slot_event[k], hipEventDisableTiming);
             if (e != hipSuccess) { ctx->slot_event[k] = nullptr; return CAME_EHIP; }
@@ -346,7 +386,9 @@ int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count
             e = hipMemcpy(ctx->scratch + p.off_fins, p.fins.data(), sizeof(FinalizeItem) * p.fins.size(), hipMemcpyHostToDevice);
             if (e != hipSuccess) return CAME_EHIP;
         }
-        e = launch_fill_zero_bytes(ctx->scratch + p.off_scalars, sizeof(TensorScalars) * p.descs.size(), s);
+        // (the counters of the on-chip path and its failure flag lie directly behind the scalars)
+        e = launch_fill_zero_bytes(ctx->scratch + p.off_scalars,
+                                   p.off_sync + sizeof(ResidentSync) * (p.descs.size() + 1) - p.off_scalars, s);
         if (e != hipSuccess) return CAME_EHIP;
         e = launch_fill_zero(ctx->state, p.state_bytes / sizeof(float), s);
         if (e != hipSuccess) return CAME_EHIP;
@@ -379,7 +421,7 @@ static int check_step_arguments(const Plan& p, void* const* theta_dev, const voi
 // The launch sequence of one step over the plan's groups, on tables that are already in device
 // memory.  ctx (may be null) only serves the phase timer and the record of a failed HIP call.
 static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, const came_hyper* hyper,
-                        double lr, hipStream_t s, int* hip_error)
+                        double lr, hipStream_t s, int* hip_error, const ResidentCtl* rctl = nullptr)
 {
     auto failed = [&](hipError_t e) {
         if (hip_error) *hip_error = static_cast<int>(e);
@@ -414,9 +456,24 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
             e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
             if (e != hipSuccess) return failed(e);
         }
-        if (g.fin_end == g.fin_begin) {  // vectors only
-            e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
-            if (e != hipSuccess) return failed(e);
+        bool on_chip = false;
+        for (int v = 0; v < kVariants; ++v) on_chip = on_chip || g.res_end[v] > g.res_begin[v];
+        if (on_chip) {
+            if (!rctl) return CAME_EINVAL;  // an entry point without a failure channel planned the on-chip path
+            bool vectors_ride = g.vectors_with_resident;
+            for (int v = 0; v < kVariants; ++v) {
+                if (g.res_end[v] == g.res_begin[v]) continue;
+                const int32_t vb = vectors_ride ? g.vec_begin : 0, ve = vectors_ride ? g.vec_end : 0;
+                e = timed_launch(ctx, 6, s, [&] { return launch_resident(tb, v, g.res_begin[v], g.res_end[v], vb, ve, sh, fh, *rctl, s); });
+                if (e != hipSuccess) return failed(e);
+                vectors_ride = false;
+            }
+        }
+        if (g.fin_end == g.fin_begin) {  // no streaming matrix
+            if (!g.vectors_with_resident) {
+                e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
+                if (e != hipSuccess) return failed(e);
+            }
             continue;
         }
         bool vectors_pending = g.vec_end > g.vec_begin;  // they ride along with the first sweep-1 launch
@@ -450,12 +507,21 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
                      void* hip_stream)
 {
     if (!ctx) return CAME_EINVAL;
+    if (*static_cast<volatile int32_t*>(ctx->fail_host) != 0) return CAME_ETIMEOUT;
     int rc = check_step_arguments(ctx->plan, theta_dev, grad_dev, theta16_dev, hyper, lr, step);
     if (rc != CAME_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (ctx->plan.n_resident > 0) {
+        // cooperative launches are not recorded into graphs here
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        const hipError_t ce = hipStreamIsCapturing(s, &capturing);
+        if (ce != hipSuccess) return hip_fail(ctx, ce);
+        if (capturing != hipStreamCaptureStatusNone) return CAME_EINVAL;
+    }
     rc = upload_pointers(ctx, theta_dev, grad_dev, theta16_dev, s);
     if (rc != CAME_OK) return rc;
-    rc = enqueue_step(ctx, ctx->plan, tables_for(ctx, ctx->slot), hyper, lr, s, nullptr);
+    const ResidentCtl rctl = resident_ctl(ctx->plan, ctx->scratch, ctx->fail_host);
+    rc = enqueue_step(ctx, ctx->plan, tables_for(ctx, ctx->slot), hyper, lr, s, nullptr, &rctl);
     if (rc != CAME_OK) return rc;
     ctx->last_step = step;
     return CAME_OK;
@@ -486,8 +552,13 @@ int came_step_noalloc(const came_tensor_desc* descs, int32_t count, const came_o
 {
     return guarded([&]() -> int {
         if (!state_dev || count > kNoallocMaxTensors) return !state_dev ? CAME_EINVAL : CAME_ESIZE;
+        // no context, hence nowhere for the on-chip kernel to report a wait that ran out: streaming only
+        came_options o{};
+        if (opts) o = *opts;
+        if (o.resident == CAME_RESIDENT_ON) return CAME_EINVAL;
+        o.resident = CAME_RESIDENT_OFF;
         Plan p;  // host memory only
-        int rc = build_plan(descs, count, opts, &p);
+        int rc = build_plan(descs, count, &o, &p);
         if (rc != CAME_OK) return rc;
         const size_t table_bytes = sizeof(TensorMeta) * p.metas.size() + sizeof(WorkItem) * p.items.size() +
                                    sizeof(FinalizeItem) * p.fins.size() + sizeof(void*) * kPtrArrays * p.descs.size();
@@ -525,6 +596,45 @@ int came_step_noalloc(const came_tensor_desc* descs, int32_t count, const came_o
         if (e != hipSuccess) return failed(e);
         return enqueue_step(nullptr, p, tables_in(p, sp, static_cast<float*>(state_dev), 0), hyper, lr, s, &noalloc_last_hip);
     });
+}
+
+int came_plan_traffic(const came_tensor_desc* descs, int32_t count, const came_options* opts, double out[4])
+{
+    return guarded([&]() -> int {
+        if (!out) return CAME_EINVAL;
+        Plan plan;
+        const int rc = build_plan(descs, count, opts, &plan);
+        if (rc != CAME_OK) return rc;
+        const int32_t mb = plan.momentum_dtype == CAME_MOMENTUM_BF16 ? 2 : 4;
+        double planned = 0.0, streaming = 0.0;
+        for (const TensorMeta& tm : plan.metas) {
+            const int32_t gb = (tm.flags & kFlagBf16Grad) ? 2 : 4;
+            const double nm = static_cast<double>(tm.n) * static_cast<double>(tm.m);
+            if (tm.flags & kFlagVector) {
+                // g read; v, s, theta and M read and written; vectors too long for one workgroup read g and v twice
+                const double per = 24.0 + gb + 2.0 * mb + (tm.n > kFusedVectorMax ? gb + 4.0 : 0.0);
+                planned += per * nm;
+                streaming += per * nm;
+                continue;
+            }
+            const double stream_per = came_algorithmic_bytes(gb, mb, plan.algo, 0);
+            streaming += stream_per * nm;
+            planned += ((tm.flags & kFlagResident) ? came_algorithmic_bytes(gb, mb, plan.algo, 4) : stream_per) * nm;
+        }
+        out[0] = static_cast<double>(plan.n_resident);
+        out[1] = static_cast<double>(plan.resident_elements);
+        out[2] = planned;
+        out[3] = streaming;
+        return CAME_OK;
+    });
+}
+
+int came_device_status(came_ctx* ctx, void* hip_stream)
+{
+    if (!ctx) return CAME_EINVAL;
+    const hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return *static_cast<volatile int32_t*>(ctx->fail_host) != 0 ? CAME_ETIMEOUT : CAME_OK;
 }
 
 int came_state_view_get(const came_ctx* ctx, int32_t i, came_state_view* view)
@@ -620,11 +730,11 @@ int came_profile_enable(came_ctx* ctx, int32_t on)
     return CAME_OK;
 }
 
-int came_profile_read(came_ctx* ctx, double phase_ms[6], int64_t phase_launches[6])
+int came_profile_read(came_ctx* ctx, double phase_ms[7], int64_t phase_launches[7])
 {
     return guarded([&]() -> int {
         if (!ctx || !phase_ms || !phase_launches) return CAME_EINVAL;
-        for (int k = 0; k < 6; ++k) { phase_ms[k] = 0.0; phase_launches[k] = 0; }
+        for (int k = 0; k < 7; ++k) { phase_ms[k] = 0.0; phase_launches[k] = 0; }
         int rc = CAME_OK;
         for (const came_ctx::Timed& t : ctx->timed) {
             hipError_t e = hipEventSynchronize(t.stop);
@@ -668,6 +778,7 @@ const char* came_strerror(int status)
         case CAME_EALIGN: return "device pointer not aligned as required";
         case CAME_EHIP: return "HIP runtime call failed";
         case CAME_ENOMEM: return "host allocation failed";
+        case CAME_ETIMEOUT: return "a wait inside the on-chip kernel ran into its time limit";
         default: return "unknown status";
     }
 }

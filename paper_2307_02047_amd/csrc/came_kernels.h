@@ -41,6 +41,14 @@ struct DeviceTables {
     char* scratch;
 };
 
+// How the on-chip kernel reports a wait that ran into its limit.
+struct ResidentCtl {
+    int32_t* fail_dev;     // device memory (scratch blob): non-zero once any workgroup gave up a wait
+    int32_t* fail_host;    // pinned host memory, device-accessible: the same, for the host to see
+    uint64_t limit_ticks;  // longest single wait, in ticks of the constant 100 MHz clock
+    char* regions;         // device memory (scratch blob): the workgroups' partial-sum regions
+};
+
 hipError_t launch_fill_zero(float* p, size_t count, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void* p, size_t bytes, hipStream_t s);
 
@@ -79,5 +87,15 @@ hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fi
 // Sweep 3: momentum and parameter update.
 hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
                          int32_t item_end, const SweepHyper& h, hipStream_t s);
+
+// On-chip path (came_resident.hip): the complete Algorithm-2 step of the matrices whose tiles are
+// the work items [item_begin, item_end) (kind 3, all of `variant`), one cooperative launch of at most
+// kResidentGrid workgroups.  The whole-vector items [vec_begin, vec_end) ride along; pass an empty
+// range for none.
+hipError_t launch_resident(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,
+                           int32_t vec_begin, int32_t vec_end, const SweepHyper& h, const FinalizeHyper& fh,
+                           const ResidentCtl& ctl, hipStream_t s);
+// Workgroups of the on-chip kernel `variant` that the runtime will keep on one compute unit at once.
+hipError_t resident_occupancy(int variant, int* workgroups_per_cu);
 
 }  // namespace came

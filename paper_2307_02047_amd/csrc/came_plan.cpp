@@ -26,14 +26,14 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // and BERT-large-shaped lists: six to twelve tiles per compute unit (256 CUs) is the flat
 // optimum; smaller tiles pay more per-tile prologue/epilogue and more column partials,
 // larger ones leave compute units idle in the last round of a launch.
-int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count)
+int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count, const std::vector<char>& resident)
 {
     const int64_t want = kNumCus * 12;
     int32_t best = 16;
     for (int32_t tr = 512; tr >= 16; tr -= 16) {
         int64_t tiles = 0;
         for (int32_t t = 0; t < count; ++t)
-            if (d[t].ndim == 2) tiles += ceil_div(d[t].rows, tr) * ceil_div(d[t].cols, kTileCols);
+            if (d[t].ndim == 2 && !resident[t]) tiles += ceil_div(d[t].rows, tr) * ceil_div(d[t].cols, kTileCols);
         if (tiles >= want) { best = tr; break; }
     }
     return best;
@@ -61,8 +61,9 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     if (!descs || !plan || count <= 0) return CAME_EINVAL;
     came_options o{};
     if (opts) o = *opts;
-    for (int32_t v : o.reserved)
-        if (v != 0) return CAME_EINVAL;
+    if (o.resident != CAME_RESIDENT_AUTO && o.resident != CAME_RESIDENT_OFF && o.resident != CAME_RESIDENT_ON)
+        return CAME_EINVAL;
+    if (o.resident_wait_us < 0) return CAME_EINVAL;
     if (o.algo != CAME_ALGO_CAME && o.algo != CAME_ALGO_ADAFACTOR) return CAME_EINVAL;
     if (o.tile_rows != 0 && (o.tile_rows < 4 || o.tile_rows > 1024 || o.tile_rows % 4 != 0))
         return CAME_EINVAL;
@@ -86,14 +87,30 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     p.descs.assign(descs, descs + count);
     p.algo = o.algo;
     p.momentum_dtype = o.momentum_dtype;
-    p.tile_rows = o.tile_rows ? o.tile_rows : auto_tile_rows(descs, count);
+    p.resident_wait_us = o.resident_wait_us;
+    // Which matrices take the on-chip path: Algorithm 2 only, rows 16-byte aligned, and all tiles of
+    // the matrix on the chip at once (one per workgroup of the co-resident grid).
+    std::vector<char> resident(count, 0);
+    // (a caller who shapes the streaming launches -- tile height, launch groups -- gets them unless
+    // the on-chip path is asked for explicitly)
+    const bool on_chip = o.resident == CAME_RESIDENT_ON ||
+                         (o.resident == CAME_RESIDENT_AUTO && o.tile_rows == 0 && o.group_elements == 0);
+    if (on_chip && o.algo == CAME_ALGO_CAME) {
+        for (int32_t t = 0; t < count; ++t) {
+            const came_tensor_desc& d = descs[t];
+            if (d.ndim != 2 || d.cols % kLaneCols != 0) continue;
+            const int64_t RB = ceil_div(d.rows, kResidentRows), CB = ceil_div(d.cols, kTileCols);
+            if (RB <= kResidentGrid && CB <= kResidentGrid && RB * CB <= kResidentGrid) resident[t] = 1;
+        }
+    }
+    p.tile_rows = o.tile_rows ? o.tile_rows : auto_tile_rows(descs, count, resident);
     {
         // counted in 64 bits before anything 32-bit is derived from them
         int64_t items = 0, fins = 0;
         for (int32_t t = 0; t < count; ++t) {
             const came_tensor_desc& d = descs[t];
             if (d.ndim == 2) {
-                const int64_t RB = ceil_div(d.rows, p.tile_rows), CB = ceil_div(d.cols, kTileCols);
+                const int64_t RB = ceil_div(d.rows, resident[t] ? kResidentRows : p.tile_rows), CB = ceil_div(d.cols, kTileCols);
                 if (RB > kMaxItems || CB > kMaxItems || RB * CB > kMaxItems) return CAME_EINVAL;
                 items += RB * CB;
                 fins += ceil_div(d.rows, kWorkgroup) + ceil_div(d.cols, kFinalizeCols);
@@ -131,6 +148,11 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             tm.off_C = off; off = round_up(off + tm.m, kAlignFloats);
             ++p.n_matrices;
             if (tm.m % kLaneCols == 0) tm.flags |= kFlagAligned;
+            if (resident[t]) {
+                tm.flags |= kFlagResident;
+                ++p.n_resident;
+                p.resident_elements += nm;
+            }
         } else {
             tm.off_C = -1;
             tm.flags |= kFlagVector;
@@ -167,10 +189,17 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
             TensorMeta& tm = p.metas[t];
             if (tm.flags & kFlagVector) continue;
-            tm.tile_rows = p.tile_rows;
+            tm.tile_rows = (tm.flags & kFlagResident) ? kResidentRows : p.tile_rows;
             tm.RB = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows));
             tm.CB = static_cast<int32_t>(ceil_div(tm.m, kTileCols));
             tm.ntiles = tm.RB * tm.CB;
+            if (tm.flags & kFlagResident) {
+                // no finalize launch: the workgroups of the matrix reduce their own partial sums; the
+                // sums of r and of R are kept per row block
+                tm.f_row_wgs = tm.RB;
+                tm.f_col_wgs = 0;
+                continue;
+            }
             tm.f_row_wgs = static_cast<int32_t>(ceil_div(tm.n, kWorkgroup));
             tm.f_col_wgs = static_cast<int32_t>(ceil_div(tm.m, kFinalizeCols));
             for (int32_t k = 0; k < tm.f_row_wgs; ++k) p.fins.push_back(FinalizeItem{t, k, 0, 0});
@@ -181,7 +210,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             g.var_begin[v] = static_cast<int32_t>(p.items.size());
             for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
                 const TensorMeta& tm = p.metas[t];
-                if ((tm.flags & kFlagVector) || variant_of(tm.flags) != v) continue;
+                if ((tm.flags & (kFlagVector | kFlagResident)) || variant_of(tm.flags) != v) continue;
                 for (int32_t rb = 0; rb < tm.RB; ++rb)
                     for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 0});
             }
@@ -203,6 +232,25 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             for (int32_t k = 0; k < tm.ntiles; ++k) p.items.push_back(WorkItem{t, k, 0, 2});
         }
         g.lvec_end = static_cast<int32_t>(p.items.size());
+        // on-chip path: per variant, matrix after matrix in list order, tiles of a matrix
+        // consecutive.  Workgroup b of the launch takes tiles b, b + grid, ...: every workgroup
+        // meets the matrices in the same order, which is what keeps the waits free of cycles.
+        for (int v = 0; v < kVariants; ++v) {
+            g.res_begin[v] = static_cast<int32_t>(p.items.size());
+            for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
+                const TensorMeta& tm = p.metas[t];
+                if (!(tm.flags & kFlagResident) || variant_of(tm.flags) != v) continue;
+                for (int32_t rb = 0; rb < tm.RB; ++rb)
+                    for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 3});
+            }
+            g.res_end[v] = static_cast<int32_t>(p.items.size());
+        }
+        g.vectors_with_resident = g.fin_end == g.fin_begin && g.vec_end > g.vec_begin;
+        if (g.vectors_with_resident) {
+            bool any = false;
+            for (int v = 0; v < kVariants; ++v) any = any || g.res_end[v] > g.res_begin[v];
+            g.vectors_with_resident = any;
+        }
     }
 
     // ---- scratch blob
@@ -211,8 +259,11 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     p.off_items = s;   s = round_up_sz(s + sizeof(WorkItem) * std::max<size_t>(p.items.size(), 1), kAlignBytes);
     p.off_fins = s;    s = round_up_sz(s + sizeof(FinalizeItem) * std::max<size_t>(p.fins.size(), 1), kAlignBytes);
     p.off_scalars = s; s = round_up_sz(s + sizeof(TensorScalars) * count, kAlignBytes);
+    p.off_sync = s;    s = round_up_sz(s + sizeof(ResidentSync) * (static_cast<size_t>(count) + 1), kAlignBytes);
     p.ptr_slot_bytes = round_up_sz(sizeof(void*) * kPtrArrays * count, kAlignBytes);
     p.off_ptrs = s;    s += p.ptr_slot_bytes * kPtrSlots;
+    p.off_regions = s;
+    if (p.n_resident > 0) s += kResidentRegionBytes * kResidentGrid;
     p.off_partials = s;
     for (int32_t t = 0; t < count; ++t) {
         TensorMeta& tm = p.metas[t];
@@ -221,6 +272,15 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
                 tm.off_tileP = static_cast<int64_t>(s);
                 s = round_up_sz(s + sizeof(double) * tm.ntiles, kAlignBytes);
             }
+            continue;
+        }
+        tm.off_sync = static_cast<int64_t>(p.off_sync + sizeof(ResidentSync) * static_cast<size_t>(t));
+        if (tm.flags & kFlagResident) {
+            // the tiles' partial sums live in the per-workgroup regions; per matrix only the row
+            // blocks' sums of r and of R
+            tm.off_rowpart = tm.off_colpart = tm.off_tileP = -1;
+            tm.off_fpart = static_cast<int64_t>(s);
+            s = round_up_sz(s + sizeof(double) * 2 * tm.f_row_wgs, kAlignBytes);
             continue;
         }
         // sized for sweep 2 (three doubles per entry); sweep 1 reuses the front of each region

@@ -26,12 +26,31 @@ constexpr int kWaves = 4;
 constexpr int kLaneCols = 8;
 constexpr int kTileCols = 64 * kLaneCols;  // 512
 
+// The on-chip path (came_options.resident): one launch of kResidentGrid workgroups that are all
+// on the chip at once (kResidentWgsPerCu per compute unit: what the 160 KB of LDS of a compute unit
+// hold; came_init_state checks it against the occupancy the runtime reports).  A matrix is cut into
+// tiles of kResidentRows x kTileCols, one per workgroup, whose gradient and momentum stay in LDS
+// from the first phase to the last; a matrix qualifies when all its tiles are on the chip together.
+constexpr int kResidentWgsPerCu = 2;
+constexpr int kResidentGrid = kNumCus * kResidentWgsPerCu;  // 512
+constexpr int kResidentRowsPerWave = 4;
+constexpr int kResidentRows = kWaves * kResidentRowsPerWave;  // 16
+// Partial sums of the tile a workgroup of the on-chip launch currently holds: one region per
+// workgroup of the grid, reused tile after tile.  Three binary64 statistics per column and per row
+// of the tile (the first phase keeps one binary32 sum each in the same place) and the tile's sum of u^2.
+constexpr size_t kResidentColpartOffset = 0;
+constexpr size_t kResidentRowpartOffset = sizeof(double) * 3 * kTileCols;                          // 12288
+constexpr size_t kResidentTilePOffset = kResidentRowpartOffset + sizeof(double) * 3 * kResidentRows;  // 12672
+constexpr size_t kResidentRegionBytes = 12800;
+static_assert(kResidentTilePOffset + sizeof(double) <= kResidentRegionBytes && kResidentRegionBytes % 256 == 0, "region layout");
+
 enum TensorFlags : int32_t {
     kFlagBf16Grad = 1,  // gradient stored as bfloat16
     kFlagVector = 2,    // 1-D parameter: unfactored update, one workgroup
     kFlagAligned = 4,   // cols % 8 == 0: every row starts 16-byte aligned -> vector loads
     kFlagBf16Momentum = 8,  // M stored as bfloat16 (off_M still counts floats from the blob's start)
     kFlagMomentumOnly = 16, // vector updated by -eta M (no instability / confidence statistics)
+    kFlagResident = 32,     // matrix on the on-chip path (tile_rows = kResidentRows, no finalize items)
 };
 
 // Per-tensor descriptor in device memory (scratch blob).
@@ -49,14 +68,25 @@ struct TensorMeta {
     int32_t f_row_wgs, f_col_wgs;             // finalize workgroups covering the rows / the columns
     int32_t flags;                            // TensorFlags
     int32_t pad_;
+    int64_t off_sync;                         // byte offset in scratch: this matrix's ResidentSync (on-chip path)
 };
-static_assert(sizeof(TensorMeta) == 120, "TensorMeta layout");
+static_assert(sizeof(TensorMeta) == 128, "TensorMeta layout");
+
+// Counters through which the workgroups of one matrix on the on-chip path wait for each other.
+// Zero between launches: the last workgroup to leave a matrix clears them.
+struct ResidentSync {
+    int32_t arrived;   // workgroups that have reached a meeting point, summed over the meeting points so far
+    int32_t departed;  // workgroups that are through with the matrix
+    int32_t pad_[14];
+};
+static_assert(sizeof(ResidentSync) == 64, "ResidentSync layout");
 
 // One workgroup of a sweep launch.
 struct WorkItem {
     int32_t tensor;
     int32_t rb, cb;  // row block, column block (matrix tiles)
-    int32_t kind;    // 0 = matrix tile, 1 = whole vector, 2 = chunk `rb` of a long vector
+    int32_t kind;    // 0 = matrix tile, 1 = whole vector, 2 = chunk `rb` of a long vector,
+                     // 3 = tile of a matrix on the on-chip path
 };
 
 // Vectors up to this length are updated by one workgroup in one kernel.  Longer ones are cut
@@ -105,6 +135,11 @@ struct Group {
     int32_t vec_begin, vec_end;                        // whole-vector items (one workgroup each)
     int32_t lvec_begin, lvec_end;                      // chunks of long vectors (two passes)
     int32_t fin_begin, fin_end;
+    // tiles of the matrices on the on-chip path, per variant (aligned variants only), matrix
+    // after matrix in list order: one launch per variant present
+    int32_t res_begin[kVariants], res_end[kVariants];
+    bool vectors_with_resident;  // no streaming matrix in the group: the whole-vector items ride in the
+                                 // first on-chip launch instead of the first sweep-1 launch
 };
 
 struct Plan {
@@ -122,10 +157,15 @@ struct Plan {
     // 109M-parameter list, nothing on lists beyond 300M parameters, +0.3 % at 6.7B).
     bool reverse_sweep2 = false;
     int64_t n_matrices = 0, n_vectors = 0, total_elements = 0;
+    int64_t n_resident = 0, resident_elements = 0;  // matrices on the on-chip path
+    int32_t resident_wait_us = 0;
     // state blob
     size_t state_bytes = 0;
     // scratch blob sections (byte offsets)
     size_t off_metas = 0, off_items = 0, off_fins = 0, off_scalars = 0, off_ptrs = 0;
+    size_t off_sync = 0;        // ResidentSync[count + 1], directly behind the scalars (cleared with them);
+                                // the last entry's first word is the device-side failure flag
+    size_t off_regions = 0;     // kResidentGrid regions of kResidentRegionBytes (only with matrices on the on-chip path)
     size_t ptr_slot_bytes = 0;  // one slot: theta[count], grad[count], bf16 parameter copy[count] (entries may be null)
     size_t off_partials = 0;
     size_t scratch_bytes = 0;

@@ -4,7 +4,7 @@
 // kernels assume about it: every work item and finalize item names a tensor and a block that
 // exist, every state array and every scratch region lies inside its blob, none overlap.
 //
-//   plan_driver <descs.txt> <tile_rows> <algo> <group_elements> <momentum_dtype> <vector_rule>
+//   plan_driver <descs.txt> <tile_rows> <algo> <group_elements> <momentum_dtype> <vector_rule> <resident>
 //
 // Prints "rc state_bytes scratch_bytes items fins groups" and exits 0, or exits 3 with a message
 // when an invariant is broken.
@@ -43,7 +43,7 @@ int check_disjoint(std::vector<Range>& r, long long limit, const char* blob)
 
 int main(int argc, char** argv)
 {
-    if (argc != 7) return 2;
+    if (argc != 8) return 2;
     std::vector<came_tensor_desc> descs;
     if (FILE* f = std::fopen(argv[1], "r")) {
         long long rows, cols;
@@ -60,6 +60,7 @@ int main(int argc, char** argv)
     o.group_elements = std::atoll(argv[4]);
     o.momentum_dtype = std::atoi(argv[5]);
     o.vector_rule = std::atoi(argv[6]);
+    o.resident = std::atoi(argv[7]);
     Plan p;
     const int rc = build_plan(descs.empty() ? nullptr : descs.data(), static_cast<int32_t>(descs.size()), &o, &p);
     if (rc != CAME_OK) {
@@ -95,6 +96,9 @@ int main(int argc, char** argv)
     add(p.off_items, sizeof(WorkItem) * p.items.size(), "items", -1);
     add(p.off_fins, sizeof(FinalizeItem) * p.fins.size(), "fins", -1);
     add(p.off_scalars, sizeof(TensorScalars) * count, "scalars", -1);
+    add(p.off_sync, sizeof(ResidentSync) * (count + 1), "on-chip counters", -1);
+    if (p.off_sync < p.off_scalars + sizeof(TensorScalars) * count) return fail("counters not behind the scalars", p.off_sync, p.off_scalars);
+    if (p.n_resident > 0) add(p.off_regions, kResidentRegionBytes * kResidentGrid, "on-chip partial-sum regions", -1);
     add(p.off_ptrs, p.ptr_slot_bytes * kPtrSlots, "pointer slots", -1);
     if (p.ptr_slot_bytes < sizeof(void*) * kPtrArrays * count) return fail("pointer slot too small", p.ptr_slot_bytes, count);
     for (int t = 0; t < count; ++t) {
@@ -114,6 +118,15 @@ int main(int argc, char** argv)
         if (static_cast<long long>(tm.CB) * kTileCols < tm.m || static_cast<long long>(tm.CB - 1) * kTileCols >= tm.m)
             return fail("column blocks", tm.CB, tm.m);
         if (tm.ntiles != tm.RB * tm.CB) return fail("tile count", tm.ntiles, t);
+        if (tm.off_sync != static_cast<long long>(p.off_sync + sizeof(ResidentSync) * t)) return fail("counter slot", t, tm.off_sync);
+        if (tm.flags & kFlagResident) {
+            // all tiles of the matrix on the chip at once, aligned rows, Algorithm 2, no finalize items
+            if (tm.tile_rows != kResidentRows || tm.ntiles > kResidentGrid || !(tm.flags & kFlagAligned) || p.algo != CAME_ALGO_CAME)
+                return fail("on-chip matrix does not qualify", t, tm.ntiles);
+            if (tm.f_row_wgs != tm.RB || tm.f_col_wgs != 0) return fail("on-chip row-block sums", tm.f_row_wgs, tm.f_col_wgs);
+            add(tm.off_fpart, sizeof(double) * 2 * tm.RB, "row-block sums", t);
+            continue;
+        }
         if (static_cast<long long>(tm.f_row_wgs) * kWorkgroup < tm.n || static_cast<long long>(tm.f_col_wgs) * kFinalizeCols < tm.m)
             return fail("finalize coverage", tm.f_row_wgs, tm.f_col_wgs);
         add(tm.off_rowpart, sizeof(double) * 3 * tm.n * tm.CB, "row partials", t);
@@ -135,6 +148,31 @@ int main(int argc, char** argv)
                     return fail("tile item block", it.rb, it.cb);
                 ++seen[it.tensor];
             }
+        for (int v = 0; v < kVariants; ++v) {
+            int32_t last_tensor = -1, expect = 0;
+            for (int32_t k = g.res_begin[v]; k < g.res_end[v]; ++k) {
+                const WorkItem& it = p.items[k];
+                if (it.tensor < g.tensor_begin || it.tensor >= g.tensor_end || it.kind != 3) return fail("on-chip item", k, it.tensor);
+                const TensorMeta& tm = p.metas[it.tensor];
+                if (!(tm.flags & kFlagResident) || variant_of(tm.flags) != v || (v & 2)) return fail("on-chip item variant", k, v);
+                // the tiles of a matrix are consecutive, in (row block, column block) order, matrices in list order
+                if (it.tensor != last_tensor) {
+                    if (it.tensor < last_tensor || expect != 0) return fail("on-chip matrices out of order", k, it.tensor);
+                    last_tensor = it.tensor;
+                    expect = tm.ntiles;
+                }
+                if (it.rb * tm.CB + it.cb != tm.ntiles - expect) return fail("on-chip tile order", it.rb, it.cb);
+                --expect;
+                ++seen[it.tensor];
+            }
+            if (expect != 0) return fail("on-chip matrix cut short", v, expect);
+        }
+        {
+            bool any = false;
+            for (int v = 0; v < kVariants; ++v) any = any || g.res_end[v] > g.res_begin[v];
+            const bool want = any && g.fin_end == g.fin_begin && g.vec_end > g.vec_begin;
+            if (g.vectors_with_resident != want) return fail("vectors riding with the on-chip launch", g.vectors_with_resident, want);
+        }
         for (int32_t k = g.vec_begin; k < g.vec_end; ++k) {
             const WorkItem& it = p.items[k];
             if (it.kind != 1 || !(p.metas[it.tensor].flags & kFlagVector) || p.metas[it.tensor].n > kFusedVectorMax)

@@ -99,14 +99,21 @@ SHAPES = [(300, 1024), (64, 520), (37, 77), (1, 9), (130, 1), (1000,), (5,), (20
 @pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["f32", "bf16"])
 def test_each_step_from_the_oracles_state(dtype, algo):
     w = W.Workload("mb16", SHAPES, dtype, seed=61, steps=12, grad_kind="normal", scale_range=(1e-4, 1e-1))
+    one_step_from_oracle_state(w, 12, algo=algo, tile_rows=32)
+
+
+def one_step_from_oracle_state(w, steps, algo=P.ALGO_CAME, **opts):
+    """Every step starts from the oracle's state; theta and the factored statistics at the
+    one-step bar, every stored M entry a correct rounding of the oracle's unrounded M_t."""
+    SHAPES, dtype = w.shapes, w.grad_dtype
     gen = W.Generator(w, device="cuda:0")
     n = len(SHAPES)
-    opt = P.CameStep(SHAPES, [dtype] * n, tile_rows=32, algo=algo, momentum_dtype=P.MOMENTUM_BF16)
+    opt = P.CameStep(SHAPES, [dtype] * n, algo=algo, momentum_dtype=P.MOMENTUM_BF16, **opts)
     theta = [gen.theta0(i) for i in range(n)]
     otl = O.TensorList(SHAPES, [to_f64(t) for t in theta])
     h, oh = P.CameHyper(), O.Hyper(lr=w.lr)
     try:
-        for t in range(1, 13):
+        for t in range(1, steps + 1):
             grads = [gen.grad(i, t) for i in range(n)]
             load_oracle_state(opt, theta, otl, algo)
             M_prev = [st.M.copy() for st in otl.state]

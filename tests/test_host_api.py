@@ -41,15 +41,41 @@ def test_state_size_is_nm_plus_2n_plus_2m():
     (W.llama_7b, 6_738_415_616, 226, 65)])
 def test_plan_of_the_named_workloads(make, params, mats, vecs):
     w = make()
-    q = P.plan_query(w.shapes, [w.grad_dtype] * len(w.shapes))
+    q = P.plan_query(w.shapes, [w.grad_dtype] * len(w.shapes), resident=P.RESIDENT_OFF)  # the streaming plan
     assert (q["elements"], q["matrices"], q["vectors"]) == (params, mats, vecs)
     tr, tc = q["tile_rows"], q["tile_cols"]
     want = sum(-(-s[0] // tr) * -(-s[1] // tc) for s in w.shapes if len(s) == 2) + vecs  # all vectors are short
     assert q["sweep_items"] == want
     assert q["finalize_items"] == sum(-(-s[0] // 256) + -(-s[1] // 64) for s in w.shapes if len(s) == 2)
-    sb, wb = P.state_size(w.shapes, [w.grad_dtype] * len(w.shapes))
+    sb, wb = P.state_size(w.shapes, [w.grad_dtype] * len(w.shapes), resident=P.RESIDENT_OFF)
     assert sb >= 4 * sum((s[0] * s[1] + 2 * (s[0] + s[1])) if len(s) == 2 else 3 * s[0] for s in w.shapes)
     assert wb < 0.25 * sb or wb < (1 << 20)  # scratch stays a fraction of the state
+
+
+def test_which_matrices_take_the_on_chip_path():
+    """A matrix qualifies when its ceil(rows/16) * ceil(cols/512) tiles fit the 512 co-resident
+    workgroups, its rows are 16-byte aligned and Algorithm 2 is selected; the traffic the plan
+    reports prices those at 8 + grad_bytes + 2*momentum_bytes per element."""
+    fits = lambda s: len(s) == 2 and s[1] % 8 == 0 and -(-s[0] // 16) * -(-s[1] // 512) <= 512
+    for make in (W.single_matrix, W.bert_base, W.gpt2_medium, W.bert_large, W.llama_7b):
+        w = make()
+        dt = [w.grad_dtype] * len(w.shapes)
+        t = P.plan_traffic(w.shapes, dt)
+        want = [s for s in w.shapes if fits(s)]
+        assert t["resident_matrices"] == len(want)
+        assert t["resident_elements"] == sum(s[0] * s[1] for s in want)
+        gb = w.grad_bytes
+        saved = (P.algorithmic_bytes(gb, 4, P.ALGO_CAME, 0) - P.algorithmic_bytes(gb, 4, P.ALGO_CAME, 4)) * t["resident_elements"]
+        assert t["bytes_per_step_streaming"] - t["bytes_per_step"] == saved
+        off = P.plan_traffic(w.shapes, dt, resident=P.RESIDENT_OFF)
+        assert off["resident_matrices"] == 0 and off["bytes_per_step"] == off["bytes_per_step_streaming"] == t["bytes_per_step_streaming"]
+        ada = P.plan_traffic(w.shapes, dt, algo=P.ALGO_ADAFACTOR)
+        assert ada["resident_matrices"] == 0  # Algorithm 1 streams
+    assert P.algorithmic_bytes(4, 4, P.ALGO_CAME, 4) == 20.0 and P.algorithmic_bytes(2, 4, P.ALGO_CAME, 4) == 18.0
+    # the largest that fits, and the first that does not
+    assert P.plan_traffic([(16 * 512, 512)], [0])["resident_matrices"] == 1
+    assert P.plan_traffic([(16 * 512 + 1, 512)], [0])["resident_matrices"] == 0
+    assert P.plan_traffic([(64, 520)], [0])["resident_matrices"] == 1 and P.plan_traffic([(64, 516)], [0])["resident_matrices"] == 0
 
 
 def test_long_vectors_are_chunked():
@@ -124,12 +150,10 @@ def test_bad_counts_options_and_null_pointers():
     assert lib.came_state_size(None, 1, None, ctypes.byref(sb), ctypes.byref(wb)) == -1
     assert lib.came_state_size(good, 1, None, None, ctypes.byref(wb)) == -1
     for kw in (dict(tile_rows=3), dict(tile_rows=2), dict(tile_rows=2048), dict(algo=7), dict(group_elements=-5),
-               dict(momentum_dtype=3), dict(vector_rule=2), dict(vector_rule=-1)):
+               dict(momentum_dtype=3), dict(vector_rule=2), dict(vector_rule=-1), dict(resident=3), dict(resident=-1),
+               dict(resident_wait_us=-1)):
         o = B._options(**kw)
         assert lib.came_state_size(good, 1, ctypes.byref(o), ctypes.byref(sb), ctypes.byref(wb)) == -1, kw
-    o = B._options()
-    o.reserved[1] = 1
-    assert lib.came_state_size(good, 1, ctypes.byref(o), ctypes.byref(sb), ctypes.byref(wb)) == -1
     assert lib.came_state_size(good, 1, None, ctypes.byref(sb), ctypes.byref(wb)) == 0
 
 

@@ -24,10 +24,11 @@ def _both_ways(shapes, dtype, seed, steps, tile_rows):
                    zero_row_fraction=0.05)
     gen = W.Generator(w, device="cuda:0")
     h = P.CameHyper()
-    ref = P.CameStep(shapes, [dtype] * n, tile_rows=tile_rows)
+    # (the entry point without allocations has only the streaming kernels)
+    ref = P.CameStep(shapes, [dtype] * n, tile_rows=tile_rows, resident=P.RESIDENT_OFF)
     th_ref = [gen.theta0(i) for i in range(n)]
     th_new = [gen.theta0(i) for i in range(n)]
-    state_bytes, scratch_bytes = P.state_size(shapes, [dtype] * n, tile_rows=tile_rows)
+    state_bytes, scratch_bytes = P.state_size(shapes, [dtype] * n, tile_rows=tile_rows, resident=P.RESIDENT_OFF)
     assert scratch_bytes <= 16 << 20
     # the state starts as garbage: the first call is asked to clear it
     state = torch.full((state_bytes,), 0x5A, dtype=torch.uint8, device="cuda:0")
