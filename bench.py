@@ -133,6 +133,9 @@ def main() -> int:
     ap.add_argument("--grad-dtype", choices=("workload", "f32", "bf16"), default="workload",
                     help="gradient storage type: the workload's own (default), or overridden to see the other "
                          "kernel variants at the same shapes")
+    ap.add_argument("--resident", choices=("auto", "off", "on"), default="auto",
+                    help="the on-chip path for matrices whose tiles all fit on the chip (came_options.resident); "
+                         "auto = the library's default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=12.0)
     ap.add_argument("--no-placement", action="store_true",
@@ -181,6 +184,7 @@ def main() -> int:
     hyper = P.CameHyper()
     mdt = P.MOMENTUM_BF16 if args.momentum_dtype == "bf16" else P.MOMENTUM_F32
     mbytes = 2 if mdt == P.MOMENTUM_BF16 else 4
+    resident = {"auto": P.RESIDENT_AUTO, "off": P.RESIDENT_OFF, "on": P.RESIDENT_ON}[args.resident]
 
     def run(w, steps, warmup, placement):
         """Times `steps` came_step calls on workload w (after `warmup` untimed ones), everything
@@ -191,7 +195,7 @@ def main() -> int:
         # two gradient sets, alternated step by step: no random numbers are drawn inside the timed region
         grad_sets = [[gen.grad(i, t) for i in range(n)] for t in (1, 2)]
         opt = P.CameStep(w.shapes, [w.grad_dtype] * n, device=dev, tile_rows=args.tile_rows,
-                         group_elements=args.group_elements, momentum_dtype=mdt,
+                         group_elements=args.group_elements, momentum_dtype=mdt, resident=resident,
                          place_against=theta if placement else None,
                          place_against_grads=grad_sets[0] if placement else None)
         opt.check_tensors(theta, grad_sets[0])
@@ -221,11 +225,17 @@ def main() -> int:
         mid = len(per_step) // 2
         gb = w.grad_bytes
         n_matrix = sum(s[0] * s[1] for s in w.shapes if len(s) == 2)
-        bpp = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 0)
+        # what the plan moves: streamed matrices 8 + 3 g + 3 M bytes per element, matrices on the
+        # on-chip path 8 + g + 2 M, 1-D parameters 24 + g + 2 M
+        traffic = P.plan_traffic(w.shapes, [w.grad_dtype] * n, tile_rows=args.tile_rows, group_elements=args.group_elements,
+                                 momentum_dtype=mdt, resident=resident)
+        bpp = traffic["bytes_per_step"] / w.n_params
+        bpp_stream = traffic["bytes_per_step_streaming"] / w.n_params
         bmin = 8.0 + gb + 2.0 * mbytes  # every array crosses once: g, M read, M written, theta read and written
         s3_ms, s3_launches = phases["sweep3"]
         s3_avg = s3_ms / max(s3_launches, 1)
-        s3_bytes = P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 3) * n_matrix * (steps / max(s3_launches, 1))
+        s3_bytes = (P.algorithmic_bytes(gb, mbytes, P.ALGO_CAME, 3) * (n_matrix - traffic["resident_elements"]) *
+                    (steps / max(s3_launches, 1)))
         fig = {
             "ms_per_step": ms,
             "step_ms": {"median": per_step[mid] if len(per_step) % 2 else 0.5 * (per_step[mid - 1] + per_step[mid]),
@@ -234,6 +244,12 @@ def main() -> int:
             "bytes_per_param": bpp,
             "whole_step_GBs": bpp * w.n_params / (ms * 1e-3) / 1e9,
             "whole_step_frac": bpp * w.n_params / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            # the same time priced as if every matrix had taken the three streaming sweeps
+            # (20 + 3 sizeof(g) bytes per parameter): comparable across plans, not a bandwidth
+            "streaming_bytes_per_param": bpp_stream,
+            "streaming_equivalent_frac": bpp_stream * w.n_params / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "on_chip_matrices": traffic["resident_matrices"],
+            "on_chip_elements": traffic["resident_elements"],
             "bmin_bytes_per_param": bmin,
             "bmin_frac": bmin * w.n_params / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "sweep3_avg_launch_ms": s3_avg,
@@ -246,7 +262,8 @@ def main() -> int:
         return fig, opt, gen
 
     n = len(w.shapes)
-    plan = P.plan_query(w.shapes, [w.grad_dtype] * n, tile_rows=args.tile_rows, group_elements=args.group_elements)
+    plan = P.plan_query(w.shapes, [w.grad_dtype] * n, tile_rows=args.tile_rows, group_elements=args.group_elements,
+                        resident=resident)
     gb = w.grad_bytes
 
     # The state blob where the allocator puts it by itself (what a caller gets who does not use
@@ -275,6 +292,10 @@ def main() -> int:
         "bytes_per_launch": fig["sweep3_bytes_per_launch"],
         "avg_launch_ms": fig["sweep3_avg_launch_ms"],
         "whole_step": {
+            "streaming_bytes_per_param": fig["streaming_bytes_per_param"],
+            "streaming_equivalent_frac": fig["streaming_equivalent_frac"],
+            "on_chip_matrices": fig["on_chip_matrices"],
+            "on_chip_elements": fig["on_chip_elements"],
             "algorithmic_bytes_per_param": fig["bytes_per_param"],
             "achieved_GBs": fig["whole_step_GBs"],
             "frac": fig["whole_step_frac"],
@@ -313,6 +334,7 @@ def main() -> int:
         "roofline": roofline,
         # the same list, same steps, with the state blob where the allocator put it (no search)
         "no_placement": {k: plain[k] for k in ("ms_per_step", "value", "whole_step_frac", "bmin_frac", "sweep3_GBs",
+                                               "streaming_equivalent_frac",
                                                "phase_ms_per_step")},
     }
     if not args.no_cpu_baseline:
@@ -334,6 +356,8 @@ def main() -> int:
                 del o
                 torch.cuda.empty_cache()
                 res[label] = {k: f[k] for k in ("ms_per_step", "value", "bytes_per_param", "whole_step_frac", "bmin_frac",
+                                                "streaming_bytes_per_param", "streaming_equivalent_frac",
+                                                "on_chip_matrices", "on_chip_elements",
                                                 "sweep3_GBs", "phase_ms_per_step", "placement_probe_GBs")}
             res["params"] = ow.n_params
             res["grad_dtype"] = "bf16" if ow.grad_bytes == 2 else "f32"

@@ -470,7 +470,7 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
             }
         }
         if (g.fin_end == g.fin_begin) {  // no streaming matrix
-            if (!g.vectors_with_resident) {
+            if (!g.vectors_with_resident && g.vec_end > g.vec_begin) {
                 e = timed_launch(ctx, 5, s, [&] { return launch_vectors(tb, g.vec_begin, g.vec_end, sh, fh, s); });
                 if (e != hipSuccess) return failed(e);
             }

@@ -91,10 +91,10 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     // Which matrices take the on-chip path: Algorithm 2 only, rows 16-byte aligned, and all tiles of
     // the matrix on the chip at once (one per workgroup of the co-resident grid).
     std::vector<char> resident(count, 0);
-    // (a caller who shapes the streaming launches -- tile height, launch groups -- gets them unless
-    // the on-chip path is asked for explicitly)
-    const bool on_chip = o.resident == CAME_RESIDENT_ON ||
-                         (o.resident == CAME_RESIDENT_AUTO && o.tile_rows == 0 && o.group_elements == 0);
+    // Off unless asked for: measured on MI355X the on-chip path moves a third fewer bytes but is
+    // bound by the latency of the meetings between workgroups on different dies, and ends up slower
+    // than the three streaming sweeps on every list tried.
+    const bool on_chip = o.resident == CAME_RESIDENT_ON;
     if (on_chip && o.algo == CAME_ALGO_CAME) {
         for (int32_t t = 0; t < count; ++t) {
             const came_tensor_desc& d = descs[t];

@@ -72,14 +72,20 @@ struct TensorMeta {
 };
 static_assert(sizeof(TensorMeta) == 128, "TensorMeta layout");
 
-// Counters through which the workgroups of one matrix on the on-chip path wait for each other.
-// Zero between launches: the last workgroup to leave a matrix clears them.
+// Through these the workgroups of one matrix on the on-chip path wait for each other.  Arrivals are
+// counted in one memory line; the last to arrive at a meeting publishes its number in another
+// line, which is the only one the waiting workgroups poll (hundreds of pollers on the line that
+// also takes the atomic additions would hold those up).  All zero between launches: the last
+// workgroup to leave a matrix clears them.
 struct ResidentSync {
-    int32_t arrived;   // workgroups that have reached a meeting point, summed over the meeting points so far
-    int32_t departed;  // workgroups that are through with the matrix
-    int32_t pad_[14];
+    int32_t arrived;    // workgroups that have reached a meeting point, summed over the meeting points so far
+    int32_t pad0_[31];
+    int32_t released;   // number of the last meeting point that everybody has reached
+    int32_t pad1_[15];
+    int32_t departed;   // workgroups that are through with the matrix
+    int32_t pad2_[15];
 };
-static_assert(sizeof(ResidentSync) == 64, "ResidentSync layout");
+static_assert(sizeof(ResidentSync) == 256, "ResidentSync layout");
 
 // One workgroup of a sweep launch.
 struct WorkItem {

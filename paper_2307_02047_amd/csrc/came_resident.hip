@@ -82,12 +82,52 @@ __device__ __forceinline__ T uniform(const T& x)
     return out.v;
 }
 
+// A coherent load is an ordered access: the compiler neither moves it across another one nor out
+// of a conditional, and waits for it where its value is first used.  A loop "s += ld_agent(..)"
+// therefore pays one full memory round trip per term.  The sums below take four terms per trip:
+// four requests in straight-line code (terms beyond the end re-request the first of the four and
+// are dropped), then the additions, in index order -- a fixed order, so every caller that adds
+// the same list gets the same bits.
+//   at(k) -> const T* is the address of term k; terms begin, begin + step, ... below end.
+template <class At>
+__device__ __forceinline__ double sum_agent(int begin, int end, int step, At at)
+{
+    double s = 0.0;
+    for (int k = begin; k < end; k += 4 * step) {
+        const int k1 = k + step, k2 = k + 2 * step, k3 = k + 3 * step;
+        const auto v0 = ld_agent(at(k));
+        const auto v1 = ld_agent(at(k1 < end ? k1 : k));
+        const auto v2 = ld_agent(at(k2 < end ? k2 : k));
+        const auto v3 = ld_agent(at(k3 < end ? k3 : k));
+        s += static_cast<double>(v0);
+        s += k1 < end ? static_cast<double>(v1) : 0.0;
+        s += k2 < end ? static_cast<double>(v2) : 0.0;
+        s += k3 < end ? static_cast<double>(v3) : 0.0;
+    }
+    return s;
+}
+
+// The same for three statistics kept `gap` elements apart (u^2, u M, M^2 of one row or column).
+template <class At>
+__device__ __forceinline__ void sum3_agent(int begin, int end, int step, int gap, At at, double& sP, double& sQ, double& sW)
+{
+    sP = sQ = sW = 0.0;
+    for (int k = begin; k < end; k += 2 * step) {
+        const int k1 = k + step;
+        const double* p0 = at(k);
+        const double* p1 = at(k1 < end ? k1 : k);
+        const double a0 = ld_agent(p0), a1 = ld_agent(p0 + gap), a2 = ld_agent(p0 + 2 * gap);
+        const double b0 = ld_agent(p1), b1 = ld_agent(p1 + gap), b2 = ld_agent(p1 + 2 * gap);
+        sP += a0; sQ += a1; sW += a2;
+        if (k1 < end) { sP += b0; sQ += b1; sW += b2; }
+    }
+}
+
 // Sum of list[0..count) by one wave in a fixed order, read coherently; same bits in every wave
 // that evaluates it.  Every lane of the wave must be active.
 __device__ __forceinline__ double wave_sum_list_agent(const double* list, int count)
 {
-    double s = 0.0;
-    for (int k = threadIdx.x & 63; k < count; k += 64) s += ld_agent(list + k);
+    const double s = sum_agent(threadIdx.x & 63, count, 64, [&](int k) { return list + k; });
     return wave_sum(s);
 }
 
@@ -103,13 +143,14 @@ __device__ __forceinline__ void meet(ResidentSync* sync, int32_t k, int32_t& met
     met += 1;
     if (threadIdx.x == 0) {
         bool f = failed;
-        add_agent(&sync->arrived, 1);
-        if (!f) {
-            const int32_t target = met * k;
+        const int32_t before = add_agent(&sync->arrived, 1);
+        if (before + 1 == met * k) {
+            st_agent(&sync->released, met);  // the last one in: everybody may go on
+        } else if (!f) {
             const uint64_t t0 = wall_clock64();
             uint32_t spins = 0;
-            while (ld_agent(&sync->arrived) < target) {
-                __builtin_amdgcn_s_sleep(1);
+            while (ld_agent(&sync->released) < met) {
+                __builtin_amdgcn_s_sleep(4);
                 if ((++spins & 15u) == 0u) {
                     if (ld_agent(ctl.fail_dev) != 0) { f = true; break; }
                     if (wall_clock64() - t0 > ctl.limit_ticks) {
@@ -250,6 +291,7 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
                                               char* ldsG /* [16][512] gradient entries */,
                                               char* ldsM /* [16][512] momentum entries */, double* lds /* [4][256] */,
                                               double* lds4, double* rowbuf /* [3][16] */, float* rowfac /* [2][16] */,
+                                              float* colfac /* [512] */,
                                               int32_t* lds_flag, bool& failed, int32_t k /* tile's place in the launch's list */)
 {
     const TileGeom t = tile_geom(tm, it);
@@ -342,11 +384,12 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
             double mine = 0.0;
             if (static_cast<int>(threadIdx.x) < t.nrows) {
                 const int64_t row = t.row0 + threadIdx.x;
-                double s = 0.0;
-                for (int cb = 0; cb < CB; ++cb)
-                    s += static_cast<double>(ld_agent(reinterpret_cast<const float*>(region_of(it.rb, cb) + kResidentRowpartOffset) + threadIdx.x));
+                const float r_old = glob(r)[row];  // last step's: an ordinary load, requested ahead of the partials
+                double s = sum_agent(0, CB, 1, [&](int cb) {
+                    return reinterpret_cast<const float*>(region_of(it.rb, cb) + kResidentRowpartOffset) + threadIdx.x;
+                });
                 s += static_cast<double>(m) * fh.eps1;
-                const float rn = static_cast<float>(fh.beta2 * static_cast<double>(ld_agent(&r[row])) + fh.one_minus_beta2 * s);
+                const float rn = static_cast<float>(fh.beta2 * static_cast<double>(r_old) + fh.one_minus_beta2 * s);
                 st_agent(&r[row], rn);
                 mine = static_cast<double>(rn);
             }
@@ -356,13 +399,14 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
         for (int j = share.j0 + t.wave; j < share.j1; j += kWaves) {
             const int64_t cj = col0 + j;
             if (cj >= m) break;
-            double s = 0.0;
-            for (int rb = t.lane; rb < RB; rb += 64)
-                s += static_cast<double>(ld_agent(reinterpret_cast<const float*>(region_of(rb, it.cb) + kResidentColpartOffset) + j));
+            const float c_old = glob(c)[cj];
+            double s = sum_agent(t.lane, RB, 64, [&](int rb) {
+                return reinterpret_cast<const float*>(region_of(rb, it.cb) + kResidentColpartOffset) + j;
+            });
             s = wave_sum_lane63(s);
             if (t.lane == 63) {
                 s += static_cast<double>(n) * fh.eps1;
-                st_agent(&c[cj], static_cast<float>(fh.beta2 * static_cast<double>(ld_agent(&c[cj])) + fh.one_minus_beta2 * s));
+                st_agent(&c[cj], static_cast<float>(fh.beta2 * static_cast<double>(c_old) + fh.one_minus_beta2 * s));
             }
         }
     }
@@ -371,14 +415,23 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
     // ---------------------------------------------------------------- phase 2: statistics of u
     float* rs_r = rowfac;                      // rsqrt(r_i) of the tile's rows (0 beyond the last)
     float* row_S = rowfac + kResidentRows;     // eta rsqrt(R_i / 1^T R) (phase 3)
-    const float sqrt_sum_r = static_cast<float>(sqrt(wave_sum_list_agent(fpart, RB)));
-    if (first_tile && threadIdx.x == 0) sc->sqrt_sum_r = sqrt_sum_r;
-    if (threadIdx.x < kResidentRows)
-        rs_r[threadIdx.x] = static_cast<int>(threadIdx.x) < t.nrows ? rsqrtf(ld_agent(&r[t.row0 + threadIdx.x])) : 0.f;
     float b[8];  // rsqrt(c_j) of this lane's columns
+    float sqrt_sum_r;
+    {
+        // the tile's column factors, two columns per thread, and row factors, all requested in one
+        // go (columns and rows beyond the matrix re-request its last ones and are zeroed)
+        const int64_t ca = min(col0 + threadIdx.x, m - 1), cb2 = min(col0 + kHalfCols + threadIdx.x, m - 1);
+        const float c_a = ld_agent(&c[ca]), c_b = ld_agent(&c[cb2]);
+        const float r_i = ld_agent(&r[min(t.row0 + (threadIdx.x & (kResidentRows - 1)), n - 1)]);
+        sqrt_sum_r = static_cast<float>(sqrt(wave_sum_list_agent(fpart, RB)));
+        colfac[threadIdx.x] = col0 + threadIdx.x < m ? rsqrtf(c_a) : 0.f;
+        colfac[kHalfCols + threadIdx.x] = col0 + kHalfCols + threadIdx.x < m ? rsqrtf(c_b) : 0.f;
+        if (threadIdx.x < kResidentRows) rs_r[threadIdx.x] = static_cast<int>(threadIdx.x) < t.nrows ? rsqrtf(r_i) : 0.f;
+        if (first_tile && threadIdx.x == 0) sc->sqrt_sum_r = sqrt_sum_r;
+        __syncthreads();
 #pragma unroll
-    for (int e = 0; e < 8; ++e) b[e] = lane_valid ? rsqrtf(ld_agent(&c[t.col + e])) : 0.f;
-    __syncthreads();
+        for (int e = 0; e < 8; ++e) b[e] = colfac[t.lane * kLaneCols + e];
+    }
     {
         double cP[8], cQ[8], cW[8];
 #pragma unroll
@@ -434,10 +487,10 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
     // ---------------------------------------------------------------- reduce 2: kappa, R_t, C_t
     float kappa_f;
     {
-        double pp = 0.0;
-        for (int q = threadIdx.x; q < tm.ntiles; q += kWorkgroup)
-            pp += ld_agent(reinterpret_cast<const double*>(
-                ctl.regions + static_cast<size_t>((first_k + q) % static_cast<int32_t>(gridDim.x)) * kResidentRegionBytes + kResidentTilePOffset));
+        const double pp = sum_agent(threadIdx.x, tm.ntiles, kWorkgroup, [&](int q) {
+            return reinterpret_cast<const double*>(
+                ctl.regions + static_cast<size_t>((first_k + q) % static_cast<int32_t>(gridDim.x)) * kResidentRegionBytes + kResidentTilePOffset);
+        });
         const double P = block_sum(pp, lds4);
         const double rms = sqrt(P / (static_cast<double>(n) * static_cast<double>(m)));
         const double kappa = 1.0 / fmax(1.0, rms / fh.clip_d);
@@ -451,15 +504,15 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
             double mine = 0.0;
             if (static_cast<int>(threadIdx.x) < t.nrows) {
                 const int64_t row = t.row0 + threadIdx.x;
-                double sP = 0.0, sQ = 0.0, sW = 0.0;
-                for (int cb = 0; cb < CB; ++cb) {
-                    const double* rp = reinterpret_cast<const double*>(region_of(it.rb, cb) + kResidentRowpartOffset) + threadIdx.x;
-                    sP += ld_agent(rp); sQ += ld_agent(rp + kResidentRows); sW += ld_agent(rp + 2 * kResidentRows);
-                }
+                const float R_old = glob(R)[row];
+                double sP, sQ, sW;
+                sum3_agent(0, CB, 1, kResidentRows, [&](int cb) {
+                    return reinterpret_cast<const double*>(region_of(it.rb, cb) + kResidentRowpartOffset) + threadIdx.x;
+                }, sP, sQ, sW);
                 double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
                 U = U < 0.0 ? 0.0 : U;  // rounding of the three-term sum; a NaN stays a NaN
                 U += static_cast<double>(m) * fh.eps2;
-                const float Rn = static_cast<float>(fh.beta3 * static_cast<double>(ld_agent(&R[row])) + fh.one_minus_beta3 * U);
+                const float Rn = static_cast<float>(fh.beta3 * static_cast<double>(R_old) + fh.one_minus_beta3 * U);
                 st_agent(&R[row], Rn);
                 mine = static_cast<double>(Rn);
             }
@@ -469,17 +522,17 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
         for (int j = share.j0 + t.wave; j < share.j1; j += kWaves) {
             const int64_t cj = col0 + j;
             if (cj >= m) break;
-            double sP = 0.0, sQ = 0.0, sW = 0.0;
-            for (int rb = t.lane; rb < RB; rb += 64) {
-                const double* cp = reinterpret_cast<const double*>(region_of(rb, it.cb) + kResidentColpartOffset) + j;
-                sP += ld_agent(cp); sQ += ld_agent(cp + kTileCols); sW += ld_agent(cp + 2 * kTileCols);
-            }
+            const float C_old = glob(C)[cj];
+            double sP, sQ, sW;
+            sum3_agent(t.lane, RB, 64, kTileCols, [&](int rb) {
+                return reinterpret_cast<const double*>(region_of(rb, it.cb) + kResidentColpartOffset) + j;
+            }, sP, sQ, sW);
             sP = wave_sum_lane63(sP); sQ = wave_sum_lane63(sQ); sW = wave_sum_lane63(sW);
             if (t.lane == 63) {
                 double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
                 U = U < 0.0 ? 0.0 : U;
                 U += static_cast<double>(n) * fh.eps2;
-                st_agent(&C[cj], static_cast<float>(fh.beta3 * static_cast<double>(ld_agent(&C[cj])) + fh.one_minus_beta3 * U));
+                st_agent(&C[cj], static_cast<float>(fh.beta3 * static_cast<double>(C_old) + fh.one_minus_beta3 * U));
             }
         }
     }
@@ -487,16 +540,20 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
 
     // ---------------------------------------------------------------- phase 3: M_t, theta_t
     {
+        const int64_t ca = min(col0 + threadIdx.x, m - 1), cb2 = min(col0 + kHalfCols + threadIdx.x, m - 1);
+        const float C_a = ld_agent(&C[ca]), C_b = ld_agent(&C[cb2]);
+        const float R_i = ld_agent(&R[min(t.row0 + (threadIdx.x & (kResidentRows - 1)), n - 1)]);
         const float sqrt_sum_R = static_cast<float>(sqrt(wave_sum_list_agent(fpart + RB, RB)));
         if (first_tile && threadIdx.x == 0) sc->sqrt_sum_R = sqrt_sum_R;
         const float row_scale_u = sqrt_sum_r * kappa_f;
         const float row_scale_s = sqrt_sum_R * h.lr;
-        if (threadIdx.x < kResidentRows)
-            row_S[threadIdx.x] = static_cast<int>(threadIdx.x) < t.nrows ? rsqrtf(ld_agent(&R[t.row0 + threadIdx.x])) * row_scale_s : 0.f;
+        colfac[threadIdx.x] = col0 + threadIdx.x < m ? rsqrtf(C_a) : 0.f;
+        colfac[kHalfCols + threadIdx.x] = col0 + kHalfCols + threadIdx.x < m ? rsqrtf(C_b) : 0.f;
+        if (threadIdx.x < kResidentRows) row_S[threadIdx.x] = static_cast<int>(threadIdx.x) < t.nrows ? rsqrtf(R_i) * row_scale_s : 0.f;
+        __syncthreads();
         float Bc[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) Bc[e] = lane_valid ? rsqrtf(ld_agent(&C[t.col + e])) : 0.f;
-        __syncthreads();
+        for (int e = 0; e < 8; ++e) Bc[e] = colfac[t.lane * kLaneCols + e];
 #pragma unroll
         for (int u = 0; u < RPW; ++u) {
             const int i = row_of(u);
@@ -525,6 +582,7 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
         const int32_t before = add_agent(&sync->departed, 1);
         if (before == tm.ntiles - 1) {
             st_agent(&sync->arrived, 0);
+            st_agent(&sync->released, 0);
             st_agent(&sync->departed, 0);
         }
     }
@@ -556,6 +614,7 @@ __device__ __attribute__((noinline)) void resident_vector_item(DeviceTables tb, 
         __shared__ double lds4[4];                                                                          \
         __shared__ double rowbuf[3 * kResidentRows];                                                        \
         __shared__ float rowfac[2 * kResidentRows];                                                         \
+        __shared__ __attribute__((aligned(16))) float colfac[kTileCols];                                    \
         __shared__ int32_t lds_flag;                                                                        \
         bool failed = false;                                                                                \
         for (int32_t k = blockIdx.x; k < item_count; k += gridDim.x) {                                      \
@@ -568,7 +627,7 @@ __device__ __attribute__((noinline)) void resident_vector_item(DeviceTables tb, 
             a.sc = scalars + it.tensor;                                                                     \
             a.state = state;                                                                                \
             a.scratch = scratch;                                                                            \
-            resident_tile<BF16, MB16>(uniform(a), tm, it, h, fh, ctl, ldsG, ldsM, lds, lds4, rowbuf, rowfac, \
+            resident_tile<BF16, MB16>(uniform(a), tm, it, h, fh, ctl, ldsG, ldsM, lds, lds4, rowbuf, rowfac, colfac, \
                                       &lds_flag, failed, k);                                                \
             __syncthreads();                                                                                \
         }                                                                                                   \

@@ -53,14 +53,17 @@ def _typed(arena, shape, dtype):
 
 @pytest.mark.parametrize("momentum", [P.MOMENTUM_F32, P.MOMENTUM_BF16], ids=["m-f32", "m-bf16"])
 @pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["g-f32", "g-bf16"])
-@pytest.mark.parametrize("tile_rows", [8, 0], ids=["tr8", "tr-auto"])
+@pytest.mark.parametrize("tile_rows", [8, 0, -1], ids=["tr8", "tr-auto", "on-chip"])
 def test_margins_stay_untouched(dtype, momentum, tile_rows):
+    # "on-chip": the matrices that qualify (rows 16-byte aligned) take the on-chip path
+    resident = P.RESIDENT_ON if tile_rows < 0 else P.RESIDENT_OFF
+    tile_rows = max(tile_rows, 0)
     shapes = ODD_SHAPES + [(300, 1032), (64, 2048), (1,), (7,), (255,), (257,), (5000,), (16385,), (50257,)]
     n = len(shapes)
     w = W.Workload("canary", shapes, dtype, seed=123, steps=3, grad_kind="normal", scale_range=(1e-3, 1e-1),
                    zero_row_fraction=0.1)
     gen = W.Generator(w, device="cuda:0")
-    state_bytes, scratch_bytes = P.state_size(shapes, [dtype] * n, tile_rows=tile_rows, momentum_dtype=momentum)
+    state_bytes, scratch_bytes = P.state_size(shapes, [dtype] * n, tile_rows=tile_rows, momentum_dtype=momentum, resident=resident)
     total = sum(int(np.prod(s)) for s in shapes)
     arena = Arena(total * (4 + 4 + 2) + state_bytes + scratch_bytes + (3 * n + 4) * (MARGIN + 512) + (1 << 16))
     gdt = torch.bfloat16 if dtype == W.GRAD_BF16 else torch.float32
@@ -70,7 +73,7 @@ def test_margins_stay_untouched(dtype, momentum, tile_rows):
     state, scratch = arena.carve(state_bytes), arena.carve(scratch_bytes)
     for i in range(n):
         theta[i].copy_(gen.theta0(i))
-    opt = P.CameStep(shapes, [dtype] * n, tile_rows=tile_rows, momentum_dtype=momentum, blobs=(state, scratch))
+    opt = P.CameStep(shapes, [dtype] * n, tile_rows=tile_rows, momentum_dtype=momentum, resident=resident, blobs=(state, scratch))
     try:
         assert opt.state.data_ptr() == state.data_ptr()
         for t in range(1, 4):

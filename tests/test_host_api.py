@@ -60,7 +60,8 @@ def test_which_matrices_take_the_on_chip_path():
     for make in (W.single_matrix, W.bert_base, W.gpt2_medium, W.bert_large, W.llama_7b):
         w = make()
         dt = [w.grad_dtype] * len(w.shapes)
-        t = P.plan_traffic(w.shapes, dt)
+        assert P.plan_traffic(w.shapes, dt)["resident_matrices"] == 0  # off unless asked for
+        t = P.plan_traffic(w.shapes, dt, resident=P.RESIDENT_ON)
         want = [s for s in w.shapes if fits(s)]
         assert t["resident_matrices"] == len(want)
         assert t["resident_elements"] == sum(s[0] * s[1] for s in want)
@@ -69,13 +70,14 @@ def test_which_matrices_take_the_on_chip_path():
         assert t["bytes_per_step_streaming"] - t["bytes_per_step"] == saved
         off = P.plan_traffic(w.shapes, dt, resident=P.RESIDENT_OFF)
         assert off["resident_matrices"] == 0 and off["bytes_per_step"] == off["bytes_per_step_streaming"] == t["bytes_per_step_streaming"]
-        ada = P.plan_traffic(w.shapes, dt, algo=P.ALGO_ADAFACTOR)
+        ada = P.plan_traffic(w.shapes, dt, algo=P.ALGO_ADAFACTOR, resident=P.RESIDENT_ON)
         assert ada["resident_matrices"] == 0  # Algorithm 1 streams
     assert P.algorithmic_bytes(4, 4, P.ALGO_CAME, 4) == 20.0 and P.algorithmic_bytes(2, 4, P.ALGO_CAME, 4) == 18.0
     # the largest that fits, and the first that does not
-    assert P.plan_traffic([(16 * 512, 512)], [0])["resident_matrices"] == 1
-    assert P.plan_traffic([(16 * 512 + 1, 512)], [0])["resident_matrices"] == 0
-    assert P.plan_traffic([(64, 520)], [0])["resident_matrices"] == 1 and P.plan_traffic([(64, 516)], [0])["resident_matrices"] == 0
+    on = dict(resident=P.RESIDENT_ON)
+    assert P.plan_traffic([(16 * 512, 512)], [0], **on)["resident_matrices"] == 1
+    assert P.plan_traffic([(16 * 512 + 1, 512)], [0], **on)["resident_matrices"] == 0
+    assert P.plan_traffic([(64, 520)], [0], **on)["resident_matrices"] == 1 and P.plan_traffic([(64, 516)], [0], **on)["resident_matrices"] == 0
 
 
 def test_long_vectors_are_chunked():

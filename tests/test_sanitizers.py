@@ -42,7 +42,7 @@ def _descs(w):
 def test_planner_on_the_named_workloads(plan_driver, tmp_path, make):
     w = make()
     for kw in ({}, {"momentum": 1}, {"tile_rows": 4 if w.n_params < 10 ** 9 else 64, "group_elements": 10 ** 7},
-               {"resident": 1}, {"resident": 1, "tile_rows": 4 if w.n_params < 10 ** 9 else 64, "group_elements": 10 ** 7},
+               {"resident": 2}, {"resident": 2, "tile_rows": 4 if w.n_params < 10 ** 9 else 64, "group_elements": 10 ** 7},
                {"resident": 2, "momentum": 1, "group_elements": 3 * 10 ** 7}):
         rc, state, scratch, items, fins, groups = _plan(plan_driver, tmp_path, _descs(w), **kw)
         assert rc == 0 and state >= (2 if kw.get("momentum") else 4) * w.n_params and items > 0 and groups >= 1
@@ -52,7 +52,7 @@ def test_planner_on_degenerate_descriptors(plan_driver, tmp_path):
     ok = [(1, 1, 2, 0), (1, 8, 2, 1), (8, 1, 2, 0), (2, 768, 2, 0), (4, 4104, 2, 1), (1, 1, 1, 0), (16385, 1, 1, 1),
           (10 ** 9, 1, 1, 0)]
     for tr in (0, 4, 1024):
-        for res in (0, 1):
+        for res in (0, 2):
             assert _plan(plan_driver, tmp_path, ok, tile_rows=tr, resident=res)[0] == 0
     huge = [(1 << 20, 1 << 20, 2, 1)]  # 2^40 elements: fine in tall tiles, too many 4-row tiles for 32-bit tables
     assert _plan(plan_driver, tmp_path, huge, tile_rows=1024)[0] == 0
@@ -61,7 +61,7 @@ def test_planner_on_degenerate_descriptors(plan_driver, tmp_path):
     edge = [(16 * 512, 512, 2, 0), (16 * 512 + 1, 512, 2, 1), (16, 512 * 512, 2, 0), (17, 512 * 512, 2, 1), (8192, 520, 2, 0),
             (40, 1032, 2, 1), (512,  1, 1, 0)]
     for kw in ({}, {"momentum": 1}, {"group_elements": 1}, {"algo": 1}):
-        assert _plan(plan_driver, tmp_path, edge, **kw)[0] == 0, kw
+        assert _plan(plan_driver, tmp_path, edge, resident=2, **kw)[0] == 0, kw
     bad = [[], [(0, 5, 2, 0)], [(5, 0, 2, 0)], [(-1, 5, 2, 0)], [(5, 5, 3, 0)], [(5, 5, 0, 0)], [(5, 2, 1, 0)],
            [(5, 5, 2, 7)], [((1 << 40) + 1, 1, 2, 0)], [(1 << 40, 1 << 40, 2, 0)], [(1 << 30, 1 << 30, 2, 0)],
            [((1 << 38) + 1, 1, 1, 0)], [(1 << 40, 64, 2, 0)] * 2]
