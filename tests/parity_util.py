@@ -85,6 +85,10 @@ class SideBySide:
         self.theta0 = [to_f64(self.theta[k]) for k in self.check]  # for the undiluted check of the first move
         self.strict = {}
         self.t = 0
+        # a context manager factory under which the progress line of a check is printed; a long test
+        # passes pytest's capsys.disabled so that the line appears when the check is made, not
+        # when the test ends
+        self.progress = None
 
     def step(self, nthreads: int = 0):
         self.t += 1
@@ -152,7 +156,12 @@ class SideBySide:
         bad = {k: v for k, v in errs.items() if not (v[0] <= tol)}
         summary = ", ".join(f"{k}={v[0]:.2e}" for k, v in errs.items())
         strict = ", ".join(f"{k}={v:.2e}" for k, v in self.strict.items())
-        print(f"[parity] {self.w.name} {label} step {self.t}: {summary}; strict elementwise: {strict}", flush=True)
+        line = f"[parity] {self.w.name} {label} step {self.t}: {summary}; strict elementwise: {strict}"
+        if self.progress is None:
+            print(line, flush=True)
+        else:
+            with self.progress():
+                print(line, flush=True)
         assert not bad, f"{self.w.name} step {self.t}: over tolerance {tol:g}: {bad}"
         return errs
 

@@ -14,8 +14,9 @@ pytestmark = pytest.mark.gpu
 TOL_1, TOL_100 = 1e-5, 1e-4
 
 
-def _run(w, steps, tol_end, check_every=None, **kw):
+def _run(w, steps, tol_end, check_every=None, progress=None, **kw):
     sbs = SideBySide(w, **kw)
+    sbs.progress = progress
     try:
         for t in range(1, steps + 1):
             sbs.step()
@@ -52,7 +53,7 @@ def _vocabulary_and_one_per_shape(w):
 
 @pytest.mark.parametrize("make,follow", [(W.bert_base, "all"), (W.gpt2_medium, "shapes"), (W.bert_large, "shapes")],
                          ids=["bert_base", "gpt2_medium", "bert_large"])
-def test_full_list_100_steps(make, follow):
+def test_full_list_100_steps(make, follow, capsys):
     """The stated bar on the stated configurations: every tensor of the list in one grouped
     launch, 100 steps, 1e-5 after the first (incl. the first move theta_1 - theta_0 by itself)
     and 1e-4 at steps 25, 50, 75, 100.  The oracle follows every tensor of the BERT-base-shaped
@@ -60,7 +61,8 @@ def test_full_list_100_steps(make, follow):
     follows the vocabulary matrix and one tensor of every other distinct shape, while the
     library still updates all of them together."""
     w = make()
-    _run(w, 100, TOL_100, check_every=25, check=None if follow == "all" else _vocabulary_and_one_per_shape(w))
+    _run(w, 100, TOL_100, check_every=25, check=None if follow == "all" else _vocabulary_and_one_per_shape(w),
+         progress=capsys.disabled)  # these take minutes: each check reports when it is made
 
 
 def test_llama_full_size_sampled():
