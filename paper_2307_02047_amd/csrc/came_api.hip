@@ -345,15 +345,12 @@ int came_init_state(came_ctx** out, const came_tensor_desc* descs, int32_t count
 
         hipError_t e = hipSuccess;
         if (p.n_resident > 0) {
-            // the on-chip path relies on all kResidentGrid workgroups being on the chip at once: the
-            // launches are cooperative (the runtime refuses what does not fit), and the plan, made
-            // without a device, is checked here against what this device and this build give
-            int dev = -1, cus = 0, coop = 0;
+            // the on-chip path counts on all kResidentGrid workgroups being on the chip at once: the
+            // plan, made without a device, is checked here against what this device and this build give
+            int dev = -1, cus = 0;
             e = hipGetDevice(&dev);
             if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-            if (e == hipSuccess) e = hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev);
             if (e != hipSuccess) return CAME_EHIP;
-            if (!coop) return CAME_EHIP;
             for (int v = 0; v < kVariants; ++v) {
                 bool present = false;
                 for (const Group& g : p.groups) present = present || g.res_end[v] > g.res_begin[v];
@@ -511,13 +508,6 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
     int rc = check_step_arguments(ctx->plan, theta_dev, grad_dev, theta16_dev, hyper, lr, step);
     if (rc != CAME_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (ctx->plan.n_resident > 0) {
-        // cooperative launches are not recorded into graphs here
-        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-        const hipError_t ce = hipStreamIsCapturing(s, &capturing);
-        if (ce != hipSuccess) return hip_fail(ctx, ce);
-        if (capturing != hipStreamCaptureStatusNone) return CAME_EINVAL;
-    }
     rc = upload_pointers(ctx, theta_dev, grad_dev, theta16_dev, s);
     if (rc != CAME_OK) return rc;
     const ResidentCtl rctl = resident_ctl(ctx->plan, ctx->scratch, ctx->fail_host);

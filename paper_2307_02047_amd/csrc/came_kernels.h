@@ -89,7 +89,7 @@ hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, 
                          int32_t item_end, const SweepHyper& h, hipStream_t s);
 
 // On-chip path (came_resident.hip): the complete Algorithm-2 step of the matrices whose tiles are
-// the work items [item_begin, item_end) (kind 3, all of `variant`), one cooperative launch of at most
+// the work items [item_begin, item_end) (kind 3, all of `variant`), one launch of at most
 // kResidentGrid workgroups.  The whole-vector items [vec_begin, vec_end) ride along; pass an empty
 // range for none.
 hipError_t launch_resident(const DeviceTables& t, int variant, int32_t item_begin, int32_t item_end,

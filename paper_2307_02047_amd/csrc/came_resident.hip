@@ -26,13 +26,16 @@
 //
 // Workgroup b of the launch takes the tiles b, b + grid, b + 2 grid, ... of a list in which the
 // tiles of a matrix are consecutive and no matrix has more tiles than the grid has workgroups.
-// Every workgroup thus meets the matrices in list order and each at most once, and all workgroups
-// are resident (cooperative launch), so among the matrices somebody still works on, the first in
-// the list has all its workgroups either working on it or on their way to it without anything to
-// wait for in between: no cycle of waits can form.  Each wait is bounded in time all the same: when
-// the bound runs out the workgroup raises a flag, every workgroup stops waiting from then on and
-// runs through its remaining tiles (all addresses are independent of loaded data), the launch ends
-// normally and the host reports CAME_ETIMEOUT.
+// Every workgroup thus meets the matrices in list order and each at most once.  The grid is no
+// larger than what the chip holds at once (the host checks it against the occupancy the runtime
+// reports), so on a GPU that this launch has to itself all workgroups are resident, and among the
+// matrices somebody still works on, the first in the list has all its workgroups either working on
+// it or on their way to it without anything to wait for in between: no cycle of waits can form.
+// Should other work hold compute units back, the missing workgroups start when that work ends, and
+// the waiting ones go on then.  Each wait is bounded in time all the same: when the bound runs out
+// the workgroup raises a flag, every workgroup stops waiting from then on and runs through its
+// remaining tiles (all addresses are independent of loaded data), the launch ends normally and the
+// host reports CAME_ETIMEOUT.
 //
 // What one workgroup writes and another reads inside the launch (partial sums, r, c, R, C, the
 // row-block sums, the counters) goes through agent-scope atomic loads and stores: write-through
@@ -690,8 +693,7 @@ hipError_t launch_resident(const DeviceTables& t, int variant, int32_t item_begi
     void* args[] = {&metas, &items, &theta_tab, &grad_tab, &theta16_tab, &scalars, &state, &scratch,
                     &ib, &ic, &vb, &vc, &sh, &fhh, &c};
     const int32_t grid = ic < kResidentGrid ? ic : kResidentGrid;
-    // cooperative: the runtime refuses the launch unless all workgroups can be on the chip at once
-    return hipLaunchCooperativeKernel(f, dim3(static_cast<unsigned>(grid)), dim3(kWorkgroup), args, 0, s);
+    return hipLaunchKernel(f, dim3(static_cast<unsigned>(grid)), dim3(kWorkgroup), args, 0, s);
 }
 
 }  // namespace came

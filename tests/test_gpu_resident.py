@@ -1,5 +1,5 @@
 """GPU parity of the on-chip path (came_options.resident): the matrices whose tiles all fit on
-the chip take one cooperative launch in which g and M stay in LDS across the two whole-tensor
+the chip take one launch in which g and M stay in LDS across the two whole-tensor
 dependencies of Algorithm 2 (r_t, c_t before any u_t; RMS(u_t) of Eq. 1 before any u^_t).
 Same bar as the streaming path: 1e-5 after one step, 1e-4 after 100, against the CPU oracle."""
 import numpy as np
@@ -223,30 +223,53 @@ def test_a_wait_that_runs_out_is_reported_and_nothing_hangs():
         opt.close()
 
 
-def test_capture_is_refused_with_matrices_on_chip():
-    """Cooperative launches are not recorded into graphs: a context that plans the on-chip path
-    refuses a step on a capturing stream, and nothing is recorded."""
-    shapes = [(256, 512), (512,)]
-    w = W.Workload("on-chip-capture", shapes, W.GRAD_F32, seed=91, steps=2, grad_kind="normal", scale_range=(1e-3, 1e-1))
+def test_hip_graph_replay_on_chip():
+    """The on-chip launch clears its own counters, so a captured step can be replayed: every
+    replay must give exactly what the eager call gives."""
+    shapes = [(256, 512), (512,), (300, 1032), (77,)]
+    n = len(shapes)
+    w = W.Workload("on-chip-graph", shapes, W.GRAD_F32, seed=91, steps=6, grad_kind="normal", scale_range=(1e-3, 1e-1))
     gen = W.Generator(w, device="cuda:0")
-    th = [gen.theta0(i) for i in range(2)]
-    g = [gen.grad(i, 1) for i in range(2)]
-    opt = P.CameStep(shapes, [0, 0], resident=ON)
+    h, lr = P.CameHyper(), 1e-3
+
+    def fresh():
+        th = [gen.theta0(i) for i in range(n)]
+        gbuf = [torch.empty_like(gen.grad(i, 1)) for i in range(n)]  # fixed addresses, refilled per step
+        return th, gbuf, P.CameStep(shapes, [0] * n, resident=ON)
+
+    th_e, g_e, opt_e = fresh()
+    for t in range(1, 7):
+        for i in range(n):
+            g_e[i].copy_(gen.grad(i, t))
+        opt_e.step(th_e, g_e, h, lr, t)
+    torch.cuda.synchronize()
+    th_g, g_g, opt_g = fresh()
     try:
-        opt.step(th, g, P.CameHyper(), 1e-3, 1)
+        for i in range(n):
+            g_g[i].copy_(gen.grad(i, 1))
+        opt_g.step(th_g, g_g, h, lr, 1)  # uploads the pointer table
         torch.cuda.synchronize()
-        before = [t.clone() for t in th]
         graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
-                with pytest.raises(P.CameError) as e:
-                    opt.step(th, g, P.CameHyper(), 1e-3, 2)
-                (th[1] * 1.0).sum()  # something harmless, so that the graph is not empty
-        assert e.value.status == -1
+                opt_g.step(th_g, g_g, h, lr, 2)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        assert all(torch.equal(a, b) for a, b in zip(before, th))
+        for t in range(2, 7):
+            for i in range(n):
+                g_g[i].copy_(gen.grad(i, t))
+            graph.replay()
+            torch.cuda.synchronize()
+            _ = (th_g[0] * 2).sum().item()  # unrelated eager work between replays
+        assert opt_g.device_status() == 0
+        for a, b in zip(th_e, th_g):
+            assert torch.equal(a, b)
+        for i in range(n):
+            for k in "MrcRC":
+                if opt_e.state_view(i)[k] is not None:
+                    assert torch.equal(opt_e.state_view(i)[k], opt_g.state_view(i)[k])
     finally:
-        opt.close()
+        opt_e.close()
+        opt_g.close()
