@@ -10,7 +10,9 @@ timed region.  Prints ONE JSON line:
                state blob placed by came_probe_placement
   no_placement the same steps with the state blob where the allocator put it by itself
   other_workloads  the BERT-Base-, GPT-2-medium- and BERT-Large-shaped lists, timed in the same
-               process after the headline (placed and unplaced)
+               process after the headline: placed, unplaced, and ("on_chip") with the matrices
+               that fit on the on-chip path of came_options.resident, which moves a third fewer
+               bytes and is off by default because it measures slower
   roofline     the dominant kernel (sweep 3: reads g, M, theta, writes M, theta) --
                algorithmic bytes per launch / mean launch time, the latter taken
                with HIP events on the step's stream inside the timed region
@@ -186,7 +188,7 @@ def main() -> int:
     mbytes = 2 if mdt == P.MOMENTUM_BF16 else 4
     resident = {"auto": P.RESIDENT_AUTO, "off": P.RESIDENT_OFF, "on": P.RESIDENT_ON}[args.resident]
 
-    def run(w, steps, warmup, placement):
+    def run(w, steps, warmup, placement, resident=resident):
         """Times `steps` came_step calls on workload w (after `warmup` untimed ones), everything
         resident in HBM beforehand.  Returns (figures, context, generator); the caller closes the context."""
         gen = W.Generator(w, device=dev)
@@ -350,8 +352,11 @@ def main() -> int:
         for name in ("bert_base", "gpt2_medium", "bert_large"):
             ow = W.by_name(name)
             res = {}
-            for label, placed in (("no_placement", False), ("placed", True)):
-                f, o, _ = run(ow, args.other_steps, 20, placement=placed)
+            # "on_chip": the same list with the matrices that fit on the on-chip path
+            # (came_options.resident; off by default because it measures slower)
+            for label, placed, res_mode in (("no_placement", False, resident), ("placed", True, resident),
+                                            ("on_chip", False, P.RESIDENT_ON)):
+                f, o, _ = run(ow, args.other_steps, 20, placement=placed, resident=res_mode)
                 o.close()
                 del o
                 torch.cuda.empty_cache()

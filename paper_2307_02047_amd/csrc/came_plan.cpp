@@ -25,18 +25,23 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // to 512 that still yields at least `want` tiles.  Measured on BERT-base-, GPT-2-medium-
 // and BERT-large-shaped lists: six to twelve tiles per compute unit (256 CUs) is the flat
 // optimum; smaller tiles pay more per-tile prologue/epilogue and more column partials,
-// larger ones leave compute units idle in the last round of a launch.
+// larger ones leave compute units idle in the last round of a launch.  Below 64 rows the
+// column partials of a tall matrix (one per row block and column) outgrow what the finalize
+// kernels add up cheaply, so a list too small for twelve 64-row tiles per compute unit keeps
+// 64 rows as long as that still gives two tiles per compute unit, and goes lower only then.
 int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count, const std::vector<char>& resident)
 {
-    const int64_t want = kNumCus * 12;
-    int32_t best = 16;
-    for (int32_t tr = 512; tr >= 16; tr -= 16) {
+    auto tiles_at = [&](int32_t tr) {
         int64_t tiles = 0;
         for (int32_t t = 0; t < count; ++t)
             if (d[t].ndim == 2 && !resident[t]) tiles += ceil_div(d[t].rows, tr) * ceil_div(d[t].cols, kTileCols);
-        if (tiles >= want) { best = tr; break; }
-    }
-    return best;
+        return tiles;
+    };
+    for (int32_t tr = 512; tr >= 64; tr -= 16)
+        if (tiles_at(tr) >= kNumCus * 12) return tr;
+    for (int32_t tr = 64; tr >= 16; tr -= 16)
+        if (tiles_at(tr) >= kNumCus * 2) return tr;
+    return 16;
 }
 
 }  // namespace
