@@ -15,9 +15,12 @@
  * (length m).  All reductions are SUMS, as printed -- not means.
  *
  * Every intermediate of Algorithm 2 (g^2+eps1, v, u, u_hat, U, S) is
- * materialised as a dense n x m array and every statement of the algorithm is
- * one plain loop, in the printed order, so the code can be checked against
- * the paper by eye.  No blocking, fusion or algebraic rewriting.
+ * materialised as a dense n x m array, in the paper's notation, and each step
+ * of the algorithm is one plain loop over it, in the algorithm's order
+ * (second-moment statistics, rank-one second moment, raw and clipped update,
+ * momentum, instability, confidence statistics, rank-one instability, step),
+ * so the code can be checked against the paper by eye.  No blocking, fusion or
+ * algebraic rewriting.
  *
  * Readings where the paper is silent (all listed in the design document):
  *   - R_0 = C_0 = 0, like r_0, c_0, m_0 (Algorithm 2's input list names only
@@ -82,66 +85,66 @@ int came_oracle_matrix_step(int64_t n, int64_t m, double *theta, const double *g
         return -1;
     }
 
-    /* g_t^2 + eps1 1_n 1_m^T */
+    /* the regularised squared gradient, entry by entry */
     for (int64_t i = 0; i < n; ++i)
         for (int64_t j = 0; j < m; ++j)
             G[i * m + j] = g[i * m + j] * g[i * m + j] + h->eps1;
 
-    /* r_t = beta2 r_{t-1} + (1-beta2) (g^2 + eps1) 1_m        (row sums) */
+    /* second-moment row statistic: moving average (beta2) of the ROW SUMS of G */
     for (int64_t i = 0; i < n; ++i) {
         double rowsum = 0.0;
         for (int64_t j = 0; j < m; ++j) rowsum += G[i * m + j];
         r[i] = h->beta2 * r[i] + (1.0 - h->beta2) * rowsum;
     }
-    /* c_t = beta2 c_{t-1} + (1-beta2) 1_n^T (g^2 + eps1)      (column sums) */
+    /* second-moment column statistic: moving average (beta2) of the COLUMN SUMS of G */
     for (int64_t j = 0; j < m; ++j) {
         double colsum = 0.0;
         for (int64_t i = 0; i < n; ++i) colsum += G[i * m + j];
         c[j] = h->beta2 * c[j] + (1.0 - h->beta2) * colsum;
     }
 
-    /* v_t = r_t c_t / (1_n^T r_t) */
+    /* rank-one second moment: outer product of the two statistics over the total of r */
     double sum_r = 0.0;
     for (int64_t i = 0; i < n; ++i) sum_r += r[i];
     for (int64_t i = 0; i < n; ++i)
         for (int64_t j = 0; j < m; ++j)
             v[i * m + j] = r[i] * c[j] / sum_r;
 
-    /* u_t = g_t / sqrt(v_t) */
+    /* the raw update: gradient over the root of the second moment */
     for (int64_t k = 0; k < nm; ++k) u[k] = g[k] / sqrt(v[k]);
 
-    /* u_hat_t = u_t / max(1, RMS(u_t)/d)                         (Eq. 1) */
+    /* clipping (Eq. 1): scaled down, never up, so that its RMS does not exceed d */
     const double rms_u = rms_of(u, nm);
     const double denom = fmax(1.0, rms_u / h->clip_d);
     for (int64_t k = 0; k < nm; ++k) uh[k] = u[k] / denom;
 
-    /* m_t = beta1 m_{t-1} + (1-beta1) u_hat_t */
+    /* momentum: moving average (beta1) of the clipped update */
     for (int64_t k = 0; k < nm; ++k) M[k] = h->beta1 * M[k] + (1.0 - h->beta1) * uh[k];
 
-    /* U_t = (u_hat_t - m_t)^2 */
+    /* instability: squared distance between the clipped update and the NEW momentum */
     for (int64_t k = 0; k < nm; ++k) U[k] = (uh[k] - M[k]) * (uh[k] - M[k]);
 
-    /* R_t = beta3 R_{t-1} + (1-beta3) (U_t + eps2 1_n 1_m^T) 1_m */
+    /* confidence row statistic: moving average (beta3) of the row sums of U + eps2 */
     for (int64_t i = 0; i < n; ++i) {
         double rowsum = 0.0;
         for (int64_t j = 0; j < m; ++j) rowsum += U[i * m + j] + h->eps2;
         R[i] = h->beta3 * R[i] + (1.0 - h->beta3) * rowsum;
     }
-    /* C_t = beta3 C_{t-1} + (1-beta3) 1_n^T (U_t + eps2 1_n 1_m^T) */
+    /* confidence column statistic: the same over the columns */
     for (int64_t j = 0; j < m; ++j) {
         double colsum = 0.0;
         for (int64_t i = 0; i < n; ++i) colsum += U[i * m + j] + h->eps2;
         C[j] = h->beta3 * C[j] + (1.0 - h->beta3) * colsum;
     }
 
-    /* S_t = R_t C_t / (1_n^T R_t) */
+    /* rank-one instability estimate, formed from R and C the way v is formed from r and c */
     double sum_R = 0.0;
     for (int64_t i = 0; i < n; ++i) sum_R += R[i];
     for (int64_t i = 0; i < n; ++i)
         for (int64_t j = 0; j < m; ++j)
             S[i * m + j] = R[i] * C[j] / sum_R;
 
-    /* theta_t = theta_{t-1} - eta / sqrt(S_t) * m_t */
+    /* the step: the momentum over the root of the instability estimate, times the learning rate */
     for (int64_t k = 0; k < nm; ++k) theta[k] = theta[k] - h->lr / sqrt(S[k]) * M[k];
 
     if (diag) { diag[0] = rms_u; diag[1] = rms_of(uh, nm); }
@@ -162,7 +165,7 @@ int came_oracle_vector_step(int64_t n, double *theta, const double *g, double *M
     double *uh = malloc(sizeof(double) * n);
     if (!u || !uh) { free(u); free(uh); return -1; }
 
-    /* v_t = beta2 v_{t-1} + (1-beta2)(g^2 + eps1);  u_t = g_t / sqrt(v_t) */
+    /* unfactored second moment and raw update */
     for (int64_t i = 0; i < n; ++i) {
         v[i] = h->beta2 * v[i] + (1.0 - h->beta2) * (g[i] * g[i] + h->eps1);
         u[i] = g[i] / sqrt(v[i]);
