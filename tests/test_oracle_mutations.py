@@ -33,8 +33,8 @@ MUTATIONS = [
     ("rms_not_a_mean",
      "return sqrt(ss / (double)count);", "return sqrt(ss);", 1),
     ("momentum_coefficients_swapped",
-     "M[k] = h->beta1 * M[k] + (1.0 - h->beta1) * uh[k];\n\n    /* U_t",
-     "M[k] = (1.0 - h->beta1) * M[k] + h->beta1 * uh[k];\n\n    /* U_t", 1),
+     "M[k] = h->beta1 * M[k] + (1.0 - h->beta1) * uh[k];\n\n    /* instability",
+     "M[k] = (1.0 - h->beta1) * M[k] + h->beta1 * uh[k];\n\n    /* instability", 1),
     ("instability_from_unclipped_u",
      "U[k] = (uh[k] - M[k]) * (uh[k] - M[k]);", "U[k] = (u[k] - M[k]) * (u[k] - M[k]);", 1),
     ("instability_not_squared",
@@ -47,8 +47,8 @@ MUTATIONS = [
      "R[i] = h->beta3 * R[i] + (1.0 - h->beta3) * rowsum;",
      "R[i] = h->beta2 * R[i] + (1.0 - h->beta2) * rowsum;", 1),
     ("second_moment_forgets_history",
-     "c[j] = h->beta2 * c[j] + (1.0 - h->beta2) * colsum;\n    }\n\n    /* v_t",
-     "c[j] = (1.0 - h->beta2) * colsum;\n    }\n\n    /* v_t", 1),
+     "c[j] = h->beta2 * c[j] + (1.0 - h->beta2) * colsum;\n    }\n\n    /* rank-one second moment",
+     "c[j] = (1.0 - h->beta2) * colsum;\n    }\n\n    /* rank-one second moment", 1),
     ("S_without_normaliser",
      "S[i * m + j] = R[i] * C[j] / sum_R;", "S[i * m + j] = R[i] * C[j];", 1),
     ("S_not_under_sqrt",
