@@ -183,6 +183,30 @@ __device__ __forceinline__ ColumnShare column_share(int rb, int RB)
     return s;
 }
 
+// How a workgroup adds up its share of columns: groups of `gsz` consecutive lanes (a power of two,
+// at most a wave) take one column each, lane l of a group the row blocks l, l + gsz, ...; the
+// group's lanes then add their sums in a butterfly (fixed order).  All columns of a pass -- and with
+// shares of up to 16 columns that is all of them -- are thus requested at once instead of one
+// column and one round trip after the other.
+struct ColumnGroups { int gsz, cols_per_pass; };
+__device__ __forceinline__ ColumnGroups column_groups(int share_cols)
+{
+    const int per = min(share_cols, static_cast<int>(kWorkgroup));
+    int gsz = 64;
+    while (gsz > 1 && gsz * per > kWorkgroup) gsz >>= 1;
+    ColumnGroups g;
+    g.gsz = gsz;
+    g.cols_per_pass = kWorkgroup / gsz;
+    return g;
+}
+
+// Sum over the `gsz` lanes of a group (gsz a power of two <= 64), the same value in all of them.
+__device__ __forceinline__ double group_sum(double v, int gsz)
+{
+    for (int mask = gsz >> 1; mask >= 1; mask >>= 1) v += __shfl_xor(v, mask);
+    return v;
+}
+
 constexpr int RPW = kResidentRowsPerWave;
 constexpr int kHalfCols = kTileCols / 2;  // the column sums of a tile cross the waves 256 columns at a time
 
@@ -382,35 +406,52 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
     meet(sync, tm.ntiles, met, failed, ctl, lds_flag);
 
     // ---------------------------------------------------------------- reduce 1: r_t, c_t
+    const ColumnGroups cg = column_groups(share.j1 - share.j0);
+    const bool has_columns = share.j0 < share.j1 && col0 + share.j0 < m;
+    const bool row_thread = it.cb == 0 && static_cast<int>(threadIdx.x) < t.nrows;
     {
-        if (it.cb == 0) {
+        // the first four row partials are requested before the columns' and used after them, so
+        // that the workgroups that do both pay one round trip for both
+        float rv[4] = {0.f, 0.f, 0.f, 0.f};
+        float r_old = 0.f;
+        if (row_thread) {
+            r_old = glob(r)[t.row0 + threadIdx.x];  // last step's: an ordinary load
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                rv[q] = ld_agent(reinterpret_cast<const float*>(region_of(it.rb, min(q, CB - 1)) + kResidentRowpartOffset) + threadIdx.x);
+        }
+        if (has_columns) {
+            for (int base = share.j0; base < share.j1; base += cg.cols_per_pass) {
+                const int j = base + static_cast<int>(threadIdx.x) / cg.gsz, li = static_cast<int>(threadIdx.x) % cg.gsz;
+                const bool ok = j < share.j1 && col0 + j < m;
+                const int jc = ok ? j : share.j0;
+                const float c_old = glob(c)[col0 + jc];
+                double s = sum_agent(li, RB, cg.gsz, [&](int rb) {
+                    return reinterpret_cast<const float*>(region_of(rb, it.cb) + kResidentColpartOffset) + jc;
+                });
+                s = group_sum(s, cg.gsz);
+                if (ok && li == 0) {
+                    s += static_cast<double>(n) * fh.eps1;
+                    st_agent(&c[col0 + j], static_cast<float>(fh.beta2 * static_cast<double>(c_old) + fh.one_minus_beta2 * s));
+                }
+            }
+        }
+        if (it.cb == 0 && t.wave == 0) {  // (a tile has 16 rows: they all sit in the first wave)
             double mine = 0.0;
-            if (static_cast<int>(threadIdx.x) < t.nrows) {
-                const int64_t row = t.row0 + threadIdx.x;
-                const float r_old = glob(r)[row];  // last step's: an ordinary load, requested ahead of the partials
-                double s = sum_agent(0, CB, 1, [&](int cb) {
+            if (row_thread) {
+                double s = 0.0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) s += q < CB ? static_cast<double>(rv[q]) : 0.0;
+                s += sum_agent(4, CB, 1, [&](int cb) {
                     return reinterpret_cast<const float*>(region_of(it.rb, cb) + kResidentRowpartOffset) + threadIdx.x;
                 });
                 s += static_cast<double>(m) * fh.eps1;
                 const float rn = static_cast<float>(fh.beta2 * static_cast<double>(r_old) + fh.one_minus_beta2 * s);
-                st_agent(&r[row], rn);
+                st_agent(&r[t.row0 + threadIdx.x], rn);
                 mine = static_cast<double>(rn);
             }
-            const double total = block_sum(mine, lds4);
-            if (threadIdx.x == 0) st_agent(&fpart[it.rb], total);
-        }
-        for (int j = share.j0 + t.wave; j < share.j1; j += kWaves) {
-            const int64_t cj = col0 + j;
-            if (cj >= m) break;
-            const float c_old = glob(c)[cj];
-            double s = sum_agent(t.lane, RB, 64, [&](int rb) {
-                return reinterpret_cast<const float*>(region_of(rb, it.cb) + kResidentColpartOffset) + j;
-            });
-            s = wave_sum_lane63(s);
-            if (t.lane == 63) {
-                s += static_cast<double>(n) * fh.eps1;
-                st_agent(&c[cj], static_cast<float>(fh.beta2 * static_cast<double>(c_old) + fh.one_minus_beta2 * s));
-            }
+            const double total = wave_sum(mine);
+            if (t.lane == 0) st_agent(&fpart[it.rb], total);
         }
     }
     meet(sync, tm.ntiles, met, failed, ctl, lds_flag);
@@ -490,10 +531,22 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
     // ---------------------------------------------------------------- reduce 2: kappa, R_t, C_t
     float kappa_f;
     {
+        // requested in one go: the tiles' sums of u^2, the first two column blocks' row partials,
+        // (inside the column pass) the column partials; kappa is needed only where they are combined
         const double pp = sum_agent(threadIdx.x, tm.ntiles, kWorkgroup, [&](int q) {
             return reinterpret_cast<const double*>(
                 ctl.regions + static_cast<size_t>((first_k + q) % static_cast<int32_t>(gridDim.x)) * kResidentRegionBytes + kResidentTilePOffset);
         });
+        double rP[2] = {0.0, 0.0}, rQ[2] = {0.0, 0.0}, rW[2] = {0.0, 0.0};
+        float R_old = 0.f;
+        if (row_thread) {
+            R_old = glob(R)[t.row0 + threadIdx.x];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const double* rp = reinterpret_cast<const double*>(region_of(it.rb, min(q, CB - 1)) + kResidentRowpartOffset) + threadIdx.x;
+                rP[q] = ld_agent(rp); rQ[q] = ld_agent(rp + kResidentRows); rW[q] = ld_agent(rp + 2 * kResidentRows);
+            }
+        }
         const double P = block_sum(pp, lds4);
         const double rms = sqrt(P / (static_cast<double>(n) * static_cast<double>(m)));
         const double kappa = 1.0 / fmax(1.0, rms / fh.clip_d);
@@ -503,40 +556,44 @@ __device__ __forceinline__ void resident_tile(const ResidentArgs& ra, const Tens
             sc->rms_u = static_cast<float>(rms);
         }
         const double b1sq = fh.beta1 * fh.beta1, k2 = kappa * kappa, km2 = -2.0 * kappa;
-        if (it.cb == 0) {
-            double mine = 0.0;
-            if (static_cast<int>(threadIdx.x) < t.nrows) {
-                const int64_t row = t.row0 + threadIdx.x;
-                const float R_old = glob(R)[row];
+        if (has_columns) {
+            for (int base = share.j0; base < share.j1; base += cg.cols_per_pass) {
+                const int j = base + static_cast<int>(threadIdx.x) / cg.gsz, li = static_cast<int>(threadIdx.x) % cg.gsz;
+                const bool ok = j < share.j1 && col0 + j < m;
+                const int jc = ok ? j : share.j0;
+                const float C_old = glob(C)[col0 + jc];
                 double sP, sQ, sW;
-                sum3_agent(0, CB, 1, kResidentRows, [&](int cb) {
+                sum3_agent(li, RB, cg.gsz, kTileCols, [&](int rb) {
+                    return reinterpret_cast<const double*>(region_of(rb, it.cb) + kResidentColpartOffset) + jc;
+                }, sP, sQ, sW);
+                sP = group_sum(sP, cg.gsz); sQ = group_sum(sQ, cg.gsz); sW = group_sum(sW, cg.gsz);
+                if (ok && li == 0) {
+                    double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
+                    U = U < 0.0 ? 0.0 : U;  // rounding of the three-term sum; a NaN stays a NaN
+                    U += static_cast<double>(n) * fh.eps2;
+                    st_agent(&C[col0 + j], static_cast<float>(fh.beta3 * static_cast<double>(C_old) + fh.one_minus_beta3 * U));
+                }
+            }
+        }
+        if (it.cb == 0 && t.wave == 0) {
+            double mine = 0.0;
+            if (row_thread) {
+                double sP, sQ, sW;
+                sum3_agent(2, CB, 1, kResidentRows, [&](int cb) {
                     return reinterpret_cast<const double*>(region_of(it.rb, cb) + kResidentRowpartOffset) + threadIdx.x;
                 }, sP, sQ, sW);
-                double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
-                U = U < 0.0 ? 0.0 : U;  // rounding of the three-term sum; a NaN stays a NaN
-                U += static_cast<double>(m) * fh.eps2;
-                const float Rn = static_cast<float>(fh.beta3 * static_cast<double>(R_old) + fh.one_minus_beta3 * U);
-                st_agent(&R[row], Rn);
-                mine = static_cast<double>(Rn);
-            }
-            const double total = block_sum(mine, lds4);
-            if (threadIdx.x == 0) st_agent(&fpart[RB + it.rb], total);
-        }
-        for (int j = share.j0 + t.wave; j < share.j1; j += kWaves) {
-            const int64_t cj = col0 + j;
-            if (cj >= m) break;
-            const float C_old = glob(C)[cj];
-            double sP, sQ, sW;
-            sum3_agent(t.lane, RB, 64, kTileCols, [&](int rb) {
-                return reinterpret_cast<const double*>(region_of(rb, it.cb) + kResidentColpartOffset) + j;
-            }, sP, sQ, sW);
-            sP = wave_sum_lane63(sP); sQ = wave_sum_lane63(sQ); sW = wave_sum_lane63(sW);
-            if (t.lane == 63) {
+                sP = (rP[0] + (CB > 1 ? rP[1] : 0.0)) + sP;
+                sQ = (rQ[0] + (CB > 1 ? rQ[1] : 0.0)) + sQ;
+                sW = (rW[0] + (CB > 1 ? rW[1] : 0.0)) + sW;
                 double U = b1sq * ((k2 * sP + km2 * sQ) + sW);
                 U = U < 0.0 ? 0.0 : U;
-                U += static_cast<double>(n) * fh.eps2;
-                st_agent(&C[cj], static_cast<float>(fh.beta3 * static_cast<double>(C_old) + fh.one_minus_beta3 * U));
+                U += static_cast<double>(m) * fh.eps2;
+                const float Rn = static_cast<float>(fh.beta3 * static_cast<double>(R_old) + fh.one_minus_beta3 * U);
+                st_agent(&R[t.row0 + threadIdx.x], Rn);
+                mine = static_cast<double>(Rn);
             }
+            const double total = wave_sum(mine);
+            if (t.lane == 0) st_agent(&fpart[RB + it.rb], total);
         }
     }
     meet(sync, tm.ntiles, met, failed, ctl, lds_flag);
