@@ -127,7 +127,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama_7b")
-    ap.add_argument("--tile-rows", type=int, default=0)
+    ap.add_argument("--tile-rows", type=int, default=0, help="rows per tile of sweeps 1 and 2 (0: chosen from the list)")
+    ap.add_argument("--tile-rows3", type=int, default=0, help="rows per tile of the update sweep (0: the library's default, 32)")
     ap.add_argument("--group-elements", type=int, default=0)
     ap.add_argument("--momentum-dtype", choices=("f32", "bf16"), default="f32",
                     help="storage type of the momentum M between steps (f32: the configuration the metric is "
@@ -196,7 +197,7 @@ def main() -> int:
         theta = [gen.theta0(i) for i in range(n)]
         # two gradient sets, alternated step by step: no random numbers are drawn inside the timed region
         grad_sets = [[gen.grad(i, t) for i in range(n)] for t in (1, 2)]
-        opt = P.CameStep(w.shapes, [w.grad_dtype] * n, device=dev, tile_rows=args.tile_rows,
+        opt = P.CameStep(w.shapes, [w.grad_dtype] * n, device=dev, tile_rows=args.tile_rows, tile_rows3=args.tile_rows3,
                          group_elements=args.group_elements, momentum_dtype=mdt, resident=resident,
                          place_against=theta if placement else None,
                          place_against_grads=grad_sets[0] if placement else None)
@@ -330,6 +331,7 @@ def main() -> int:
             "param_state_dtype": "f32",
             "momentum_dtype": args.momentum_dtype,
             "tile_rows": plan["tile_rows"],
+            "tile_rows_update_sweep": args.tile_rows3 or 32,
             "launch_groups": plan["groups"],
             "state_placement_probe_GBs": fig["placement_probe_GBs"],
         },

@@ -141,7 +141,8 @@ typedef struct {
 
 /* Planner knobs; pass NULL for defaults.  Zero in a field means "default". */
 typedef struct {
-    int32_t tile_rows;       /* rows of a matrix one workgroup sweeps per tile: multiple of 4,
+    int32_t tile_rows;       /* rows of a matrix one workgroup sweeps per tile in the two sweeps
+                                that form sums (r_t, c_t; the statistics of u_t): multiple of 4,
                                 4..1024; 0 = chosen from the list so the launch fills the GPU */
     int32_t algo;            /* came_algo */
     int64_t group_elements;  /* 0 = all tensors in one launch group; otherwise consecutive
@@ -160,6 +161,14 @@ typedef struct {
                                 it runs out the kernel flags the failure, every workgroup stops
                                 waiting and the launch ends normally; the next came_step or
                                 came_device_status on the context returns CAME_ETIMEOUT */
+    int32_t tile_rows3;      /* rows per tile of the update sweep (M_t, theta_t), which forms no
+                                sums and so has no per-tile results to pay for: multiple of 4,
+                                4..1024; 0 = 32.  Short tiles keep the addresses that are read and
+                                written at any one time close together, which is what the memory
+                                system wants of a stream pair that reads and writes the same
+                                arrays (tall tiles: up to 20 % slower, depending on where the
+                                arrays lie) */
+    int32_t reserved;        /* must be 0 */
 } came_options;
 
 /* Device addresses of one tensor's state inside the caller's state blob.

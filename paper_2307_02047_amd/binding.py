@@ -45,7 +45,8 @@ class _Hyper(ctypes.Structure):
 class _Options(ctypes.Structure):
     _fields_ = [("tile_rows", ctypes.c_int32), ("algo", ctypes.c_int32),
                 ("group_elements", ctypes.c_int64), ("momentum_dtype", ctypes.c_int32),
-                ("vector_rule", ctypes.c_int32), ("resident", ctypes.c_int32), ("resident_wait_us", ctypes.c_int32)]
+                ("vector_rule", ctypes.c_int32), ("resident", ctypes.c_int32), ("resident_wait_us", ctypes.c_int32),
+                ("tile_rows3", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class _View(ctypes.Structure):
@@ -149,11 +150,12 @@ def _descs(shapes: Sequence[Sequence[int]], grad_dtypes: Sequence[int]):
 
 def _options(tile_rows: int = 0, algo: int = ALGO_CAME, group_elements: int = 0,
              momentum_dtype: int = MOMENTUM_F32, vector_rule: int = VECTOR_ALGORITHM2,
-             resident: int = RESIDENT_AUTO, resident_wait_us: int = 0):
+             resident: int = RESIDENT_AUTO, resident_wait_us: int = 0, tile_rows3: int = 0):
     o = _Options()
     o.tile_rows, o.algo, o.group_elements = int(tile_rows), int(algo), int(group_elements)
     o.momentum_dtype, o.vector_rule = int(momentum_dtype), int(vector_rule)
     o.resident, o.resident_wait_us = int(resident), int(resident_wait_us)
+    o.tile_rows3 = int(tile_rows3)
     return o
 
 
@@ -228,7 +230,7 @@ class CameStep:
     def __init__(self, shapes, grad_dtypes, device="cuda:0", tile_rows: int = 0, algo: int = ALGO_CAME,
                  group_elements: int = 0, momentum_dtype: int = MOMENTUM_F32,
                  vector_rule: int = VECTOR_ALGORITHM2, resident: int = RESIDENT_AUTO, resident_wait_us: int = 0,
-                 place_against=None, place_against_grads=None,
+                 tile_rows3: int = 0, place_against=None, place_against_grads=None,
                  placement_candidates: int = 8, placement_spacer_bytes: int = 16 << 30,
                  placement_accept_ratio: float = 1.12, placement_reserve_bytes: int = 2 << 30, blobs=None):
         """blobs: (state, scratch), two uint8 tensors on `device` of at least state_size()'s bytes
@@ -252,7 +254,8 @@ class CameStep:
         self.grad_dtypes = [int(d) for d in grad_dtypes]
         self.device = torch.device(device)
         self._d = _descs(self.shapes, self.grad_dtypes)
-        self._o = _options(tile_rows, algo, group_elements, momentum_dtype, vector_rule, resident, resident_wait_us)
+        self._o = _options(tile_rows, algo, group_elements, momentum_dtype, vector_rule, resident, resident_wait_us,
+                           tile_rows3)
         self.momentum_dtype = int(momentum_dtype)
         n = len(self.shapes)
         sb, wb = ctypes.c_size_t(), ctypes.c_size_t()

@@ -290,7 +290,8 @@ int came_plan_query(const came_tensor_desc* descs, int32_t count, const came_opt
         Plan plan;
         const int rc = build_plan(descs, count, opts, &plan);
         if (rc != CAME_OK) return rc;
-        const int64_t tiles = static_cast<int64_t>(plan.items.size());
+        int64_t tiles = 0;  // the update sweep's own cut of the same matrices is not counted again
+        for (const WorkItem& it : plan.items) tiles += it.kind != 4;
         out[0] = plan.tile_rows;
         out[1] = kTileCols;
         out[2] = tiles;
@@ -492,7 +493,7 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
         if (e != hipSuccess) return failed(e);
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], sh, s); });
+            e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, p.tile_rows3, g.var3_begin[v], g.var3_end[v], sh, s); });
             if (e != hipSuccess) return failed(e);
         }
     }
@@ -693,7 +694,9 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, const void* cons
                 for (const Group& g : p.groups)
                     for (int v = 0; v < kVariants; ++v) {
                         if (v & 2) continue;
-                        const hipError_t le = launch_placement_probe(tb, g.var_begin[v], g.var_end[v], mode, with_g, s);
+                        // the update sweep's streams in its own tiles, sweep 2's in the shared ones
+                        const hipError_t le = mode == 0 ? launch_placement_probe(tb, g.var3_begin[v], g.var3_end[v], mode, with_g, s)
+                                                        : launch_placement_probe(tb, g.var_begin[v], g.var_end[v], mode, with_g, s);
                         if (le != hipSuccess) return le;
                     }
             return hipSuccess;

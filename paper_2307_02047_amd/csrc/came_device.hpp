@@ -316,18 +316,25 @@ struct TileGeom {
     int ncol;     // valid columns of this lane: 0..8
 };
 
-__device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkItem& it)
+// `tile_rows`: the height of the row blocks that it.rb counts (TensorMeta.tile_rows for the items
+// of sweeps 1 and 2, TensorMeta.tile_rows3 for the update sweep's).
+__device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkItem& it, int32_t tile_rows)
 {
     TileGeom t;
     t.lane = threadIdx.x & 63;
     t.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    t.row0 = static_cast<int64_t>(it.rb) * tm.tile_rows;
+    t.row0 = static_cast<int64_t>(it.rb) * tile_rows;
     const int64_t left = tm.n - t.row0;
-    t.nrows = static_cast<int>(left < tm.tile_rows ? left : tm.tile_rows);
+    t.nrows = static_cast<int>(left < tile_rows ? left : tile_rows);
     t.col = static_cast<int64_t>(it.cb) * kTileCols + t.lane * kLaneCols;
     const int64_t cleft = tm.m - t.col;
     t.ncol = cleft >= kLaneCols ? kLaneCols : (cleft > 0 ? static_cast<int>(cleft) : 0);
     return t;
+}
+
+__device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkItem& it)
+{
+    return tile_geom(tm, it, tm.tile_rows);
 }
 
 // ---------------------------------------------------------------- vectors

@@ -654,10 +654,10 @@ constexpr int kRows3 = CAME_ROWS3;
 template <bool BF16, bool ALIGNED, bool FULL, bool COPY16, bool MB16>
 __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
                             float* theta, void* theta16, float* state, const char* scratch,
-                            const TensorScalars* sc, const SweepHyper& h, float* rowfac /* [2][tile_rows] */)
+                            const TensorScalars* sc, const SweepHyper& h, float* rowfac /* [2][tile_rows3] */)
 {
     const int64_t m = tm.m;
-    const int TR = tm.tile_rows;
+    const int TR = tm.tile_rows3;
     const float* r = state + tm.off_r;
     const float* c = state + tm.off_c;
     const float* R = state + tm.off_R;
@@ -775,7 +775,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         extern __shared__ float rowfac_f32[];                                                       \
         const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];                 \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
-        const TileGeom t = tile_geom(tm, it);                                                       \
+        const TileGeom t = tile_geom(tm, it, tm.tile_rows3);                                        \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
         float* theta = static_cast<float*>(tb.theta[it.tensor]);                         \
         void* theta16 = tb.theta16[it.tensor];                       \
@@ -818,7 +818,7 @@ __global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTable
     const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];
     const TensorMeta& tm = tb.metas[it.tensor];
     if (!(tm.flags & kFlagAligned)) return;
-    const TileGeom t = tile_geom(tm, it);
+    const TileGeom t = tile_geom(tm, it, it.kind == 4 ? tm.tile_rows3 : tm.tile_rows);
     if (t.ncol == 0) return;
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
     float* M = tb.state + tm.off_M;

@@ -15,20 +15,28 @@ constexpr int64_t kAlignFloats = 64;  // 256-byte alignment of every state array
 // the device and a launch takes one workgroup per item.  2^26 is twenty times what a
 // 6.7-billion-parameter list needs at the smallest tile height.
 constexpr int64_t kMaxItems = int64_t(1) << 26;
+
+// Rows per tile of the update sweep when the caller does not choose.  Measured on lists from 1e8
+// to 6.7e9 parameters: 32 rows are fastest or within 1 % of it everywhere (16: the per-tile
+// prologue begins to show; 64 and more: the read-and-write stream pair slows down by up to 20 %
+// when theta and M lie in the same region of the address space).
+constexpr int32_t kDefaultTileRows3 = 32;
 constexpr size_t kAlignBytes = 256;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Rows per tile when the caller does not choose: the largest multiple of 16 up
-// to 512 that still yields at least `want` tiles.  Measured on BERT-base-, GPT-2-medium-
-// and BERT-large-shaped lists: six to twelve tiles per compute unit (256 CUs) is the flat
-// optimum; smaller tiles pay more per-tile prologue/epilogue and more column partials,
-// larger ones leave compute units idle in the last round of a launch.  Below 64 rows the
-// column partials of a tall matrix (one per row block and column) outgrow what the finalize
-// kernels add up cheaply, so a list too small for twelve 64-row tiles per compute unit keeps
-// 64 rows as long as that still gives two tiles per compute unit, and goes lower only then.
+// Rows per tile of sweeps 1 and 2 when the caller does not choose: the largest multiple of 16 up
+// to 1024 that still yields six tiles per compute unit (256 CUs).  A tile of these sweeps costs
+// 20 to 25 us beyond its streaming (a chain of dependent loads under load before its first row --
+// work item, descriptor, r, c -- and the combination and storing of its partial sums after its
+// last), so tiles should be as tall as the list allows: measured on BERT-base-, GPT-2-medium-,
+// BERT-large- and Llama-7B-shaped lists, 128 / 256..512 / 512 / 1024 rows are the optima, and
+// below five tiles per compute unit the launch's last round leaves too many of them idle.  Below
+// 64 rows the column partials of a tall matrix (one per row block and column) outgrow what the
+// finalize kernels add up cheaply, so a list too small for that keeps 64 rows as long as that
+// still gives two tiles per compute unit, and goes lower only then.
 int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count, const std::vector<char>& resident)
 {
     auto tiles_at = [&](int32_t tr) {
@@ -37,8 +45,8 @@ int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count, const std::vect
             if (d[t].ndim == 2 && !resident[t]) tiles += ceil_div(d[t].rows, tr) * ceil_div(d[t].cols, kTileCols);
         return tiles;
     };
-    for (int32_t tr = 512; tr >= 64; tr -= 16)
-        if (tiles_at(tr) >= kNumCus * 12) return tr;
+    for (int32_t tr = 1024; tr >= 64; tr -= 16)
+        if (tiles_at(tr) >= kNumCus * 6) return tr;
     for (int32_t tr = 64; tr >= 16; tr -= 16)
         if (tiles_at(tr) >= kNumCus * 2) return tr;
     return 16;
@@ -72,6 +80,9 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     if (o.algo != CAME_ALGO_CAME && o.algo != CAME_ALGO_ADAFACTOR) return CAME_EINVAL;
     if (o.tile_rows != 0 && (o.tile_rows < 4 || o.tile_rows > 1024 || o.tile_rows % 4 != 0))
         return CAME_EINVAL;
+    if (o.tile_rows3 != 0 && (o.tile_rows3 < 4 || o.tile_rows3 > 1024 || o.tile_rows3 % 4 != 0))
+        return CAME_EINVAL;
+    if (o.reserved != 0) return CAME_EINVAL;
     if (o.group_elements < 0) return CAME_EINVAL;
     if (o.momentum_dtype != CAME_MOMENTUM_F32 && o.momentum_dtype != CAME_MOMENTUM_BF16) return CAME_EINVAL;
     if (o.vector_rule != CAME_VECTOR_ALGORITHM2 && o.vector_rule != CAME_VECTOR_MOMENTUM_ONLY) return CAME_EINVAL;
@@ -109,6 +120,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         }
     }
     p.tile_rows = o.tile_rows ? o.tile_rows : auto_tile_rows(descs, count, resident);
+    p.tile_rows3 = o.tile_rows3 ? o.tile_rows3 : kDefaultTileRows3;
     {
         // counted in 64 bits before anything 32-bit is derived from them
         int64_t items = 0, fins = 0;
@@ -118,6 +130,11 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
                 const int64_t RB = ceil_div(d.rows, resident[t] ? kResidentRows : p.tile_rows), CB = ceil_div(d.cols, kTileCols);
                 if (RB > kMaxItems || CB > kMaxItems || RB * CB > kMaxItems) return CAME_EINVAL;
                 items += RB * CB;
+                if (!resident[t]) {
+                    const int64_t RB3 = ceil_div(d.rows, p.tile_rows3);
+                    if (RB3 > kMaxItems || RB3 * CB > kMaxItems) return CAME_EINVAL;
+                    items += RB3 * CB;
+                }
                 fins += ceil_div(d.rows, kWorkgroup) + ceil_div(d.cols, kFinalizeCols);
             } else {
                 items += d.rows <= kFusedVectorMax ? 1 : kMaxVectorChunks;
@@ -166,7 +183,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
         }
     }
     p.state_bytes = static_cast<size_t>(off) * sizeof(float);
-    p.reverse_sweep2 = p.total_elements <= (int64_t(1) << 28);
+    p.reverse_sweep2 = true;
 
     // ---- groups of consecutive tensors
     {
@@ -195,6 +212,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             TensorMeta& tm = p.metas[t];
             if (tm.flags & kFlagVector) continue;
             tm.tile_rows = (tm.flags & kFlagResident) ? kResidentRows : p.tile_rows;
+            tm.tile_rows3 = p.tile_rows3;
             tm.RB = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows));
             tm.CB = static_cast<int32_t>(ceil_div(tm.m, kTileCols));
             tm.ntiles = tm.RB * tm.CB;
@@ -220,6 +238,17 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
                     for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 0});
             }
             g.var_end[v] = static_cast<int32_t>(p.items.size());
+        }
+        for (int v = 0; v < kVariants; ++v) {
+            g.var3_begin[v] = static_cast<int32_t>(p.items.size());
+            for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
+                const TensorMeta& tm = p.metas[t];
+                if ((tm.flags & (kFlagVector | kFlagResident)) || variant_of(tm.flags) != v) continue;
+                const int32_t RB3 = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows3));
+                for (int32_t rb = 0; rb < RB3; ++rb)
+                    for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 4});
+            }
+            g.var3_end[v] = static_cast<int32_t>(p.items.size());
         }
         g.vec_begin = static_cast<int32_t>(p.items.size());
         for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t)

@@ -67,7 +67,7 @@ struct TensorMeta {
     int32_t ntiles;                           // RB * CB
     int32_t f_row_wgs, f_col_wgs;             // finalize workgroups covering the rows / the columns
     int32_t flags;                            // TensorFlags
-    int32_t pad_;
+    int32_t tile_rows3;                       // rows per tile of the update sweep (its own work items)
     int64_t off_sync;                         // byte offset in scratch: this matrix's ResidentSync (on-chip path)
 };
 static_assert(sizeof(TensorMeta) == 128, "TensorMeta layout");
@@ -92,7 +92,8 @@ struct WorkItem {
     int32_t tensor;
     int32_t rb, cb;  // row block, column block (matrix tiles)
     int32_t kind;    // 0 = matrix tile, 1 = whole vector, 2 = chunk `rb` of a long vector,
-                     // 3 = tile of a matrix on the on-chip path
+                     // 3 = tile of a matrix on the on-chip path,
+                     // 4 = matrix tile of the update sweep (row blocks of TensorMeta.tile_rows3 rows)
 };
 
 // Vectors up to this length are updated by one workgroup in one kernel.  Longer ones are cut
@@ -137,7 +138,8 @@ inline int variant_of(int32_t flags)
 // variant present.  Work items of a group: matrix tiles sorted by variant, then vectors.
 struct Group {
     int32_t tensor_begin, tensor_end;
-    int32_t var_begin[kVariants], var_end[kVariants];  // matrix tiles of each variant
+    int32_t var_begin[kVariants], var_end[kVariants];  // matrix tiles of each variant (sweeps 1 and 2)
+    int32_t var3_begin[kVariants], var3_end[kVariants];  // the same matrices cut into the update sweep's tiles
     int32_t vec_begin, vec_end;                        // whole-vector items (one workgroup each)
     int32_t lvec_begin, lvec_end;                      // chunks of long vectors (two passes)
     int32_t fin_begin, fin_end;
@@ -155,12 +157,14 @@ struct Plan {
     std::vector<FinalizeItem> fins;
     std::vector<Group> groups;
     int32_t tile_rows = 0;
+    int32_t tile_rows3 = 0;  // update sweep
     int32_t algo = 0;
     int32_t momentum_dtype = 0;
-    // Sweep 2 walks the tiles backwards when the whole list is only a few times the 256 MB
-    // on-package cache: it then starts on the gradients sweep 1 read last and ends on the
-    // momenta sweep 3 reads first, both still cached (measured: -4 % per step on a
-    // 109M-parameter list, nothing on lists beyond 300M parameters, +0.3 % at 6.7B).
+    // Sweep 2 walks the tiles backwards: it then starts on the momenta sweep 3 wrote last (still in
+    // the 256 MB on-package cache, and dirty: read there instead of being written back first and
+    // fetched again later) and ends on the momenta and gradients sweep 3 reads first (measured:
+    // sweep 2 10 % faster on a 109M-parameter list, 3 % on 350M-parameter lists, no difference
+    // at 6.7B).
     bool reverse_sweep2 = false;
     int64_t n_matrices = 0, n_vectors = 0, total_elements = 0;
     int64_t n_resident = 0, resident_elements = 0;  // matrices on the on-chip path

@@ -61,6 +61,7 @@ int main(int argc, char** argv)
     o.momentum_dtype = std::atoi(argv[5]);
     o.vector_rule = std::atoi(argv[6]);
     o.resident = std::atoi(argv[7]);
+    if (argc > 8) o.tile_rows3 = std::atoi(argv[8]);
     Plan p;
     const int rc = build_plan(descs.empty() ? nullptr : descs.data(), static_cast<int32_t>(descs.size()), &o, &p);
     if (rc != CAME_OK) {
@@ -138,6 +139,7 @@ int main(int argc, char** argv)
 
     // work items: each matrix tile exactly once, inside its group's variant range; vectors once
     std::vector<long long> seen(count, 0);
+    std::vector<long long> seen3(count, 0);  // elements covered by the update sweep's items
     for (const Group& g : p.groups) {
         for (int v = 0; v < kVariants; ++v)
             for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
@@ -147,6 +149,21 @@ int main(int argc, char** argv)
                 if (variant_of(tm.flags) != v || it.rb < 0 || it.rb >= tm.RB || it.cb < 0 || it.cb >= tm.CB)
                     return fail("tile item block", it.rb, it.cb);
                 ++seen[it.tensor];
+            }
+        // the update sweep's own cut: every streaming matrix's rows and columns covered exactly once
+        for (int v = 0; v < kVariants; ++v)
+            for (int32_t k = g.var3_begin[v]; k < g.var3_end[v]; ++k) {
+                const WorkItem& it = p.items[k];
+                if (it.tensor < g.tensor_begin || it.tensor >= g.tensor_end || it.kind != 4) return fail("update-sweep item", k, it.tensor);
+                const TensorMeta& tm = p.metas[it.tensor];
+                if (tm.tile_rows3 < 4 || tm.tile_rows3 % 4 != 0) return fail("update-sweep tile height", it.tensor, tm.tile_rows3);
+                const long long RB3 = (tm.n + tm.tile_rows3 - 1) / tm.tile_rows3;
+                if ((tm.flags & (kFlagVector | kFlagResident)) || variant_of(tm.flags) != v || it.rb < 0 || it.rb >= RB3 ||
+                    it.cb < 0 || it.cb >= tm.CB)
+                    return fail("update-sweep item block", it.rb, it.cb);
+                const long long rows = std::min<long long>(tm.tile_rows3, tm.n - static_cast<long long>(it.rb) * tm.tile_rows3);
+                const long long cols = std::min<long long>(kTileCols, tm.m - static_cast<long long>(it.cb) * kTileCols);
+                seen3[it.tensor] += rows * cols;
             }
         for (int v = 0; v < kVariants; ++v) {
             int32_t last_tensor = -1, expect = 0;
@@ -195,6 +212,8 @@ int main(int argc, char** argv)
         const TensorMeta& tm = p.metas[t];
         const long long want = (tm.flags & kFlagVector) ? (tm.ntiles > 0 ? tm.ntiles : 1) : tm.ntiles;
         if (seen[t] != want) return fail("tensor covered a wrong number of times", seen[t], want);
+        const long long want3 = (tm.flags & (kFlagVector | kFlagResident)) ? 0 : tm.n * tm.m;
+        if (seen3[t] != want3) return fail("update sweep covers a wrong number of elements", seen3[t], want3);
     }
     std::printf("%d %zu %zu %zu %zu %zu\n", rc, p.state_bytes, p.scratch_bytes, p.items.size(), p.fins.size(), p.groups.size());
     return 0;

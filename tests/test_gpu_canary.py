@@ -63,7 +63,9 @@ def test_margins_stay_untouched(dtype, momentum, tile_rows):
     w = W.Workload("canary", shapes, dtype, seed=123, steps=3, grad_kind="normal", scale_range=(1e-3, 1e-1),
                    zero_row_fraction=0.1)
     gen = W.Generator(w, device="cuda:0")
-    state_bytes, scratch_bytes = P.state_size(shapes, [dtype] * n, tile_rows=tile_rows, momentum_dtype=momentum, resident=resident)
+    tile_rows3 = 12 if tile_rows == 8 else 0  # the update sweep's own tiling: a ragged height once, the default otherwise
+    state_bytes, scratch_bytes = P.state_size(shapes, [dtype] * n, tile_rows=tile_rows, tile_rows3=tile_rows3,
+                                              momentum_dtype=momentum, resident=resident)
     total = sum(int(np.prod(s)) for s in shapes)
     arena = Arena(total * (4 + 4 + 2) + state_bytes + scratch_bytes + (3 * n + 4) * (MARGIN + 512) + (1 << 16))
     gdt = torch.bfloat16 if dtype == W.GRAD_BF16 else torch.float32
@@ -73,7 +75,8 @@ def test_margins_stay_untouched(dtype, momentum, tile_rows):
     state, scratch = arena.carve(state_bytes), arena.carve(scratch_bytes)
     for i in range(n):
         theta[i].copy_(gen.theta0(i))
-    opt = P.CameStep(shapes, [dtype] * n, tile_rows=tile_rows, momentum_dtype=momentum, resident=resident, blobs=(state, scratch))
+    opt = P.CameStep(shapes, [dtype] * n, tile_rows=tile_rows, tile_rows3=tile_rows3, momentum_dtype=momentum,
+                     resident=resident, blobs=(state, scratch))
     try:
         assert opt.state.data_ptr() == state.data_ptr()
         for t in range(1, 4):

@@ -39,6 +39,32 @@ def test_single_matrix_tile_rows(tile_rows):
     _run(W.single_matrix(), 3, TOL_100, check_every=1, tile_rows=tile_rows)
 
 
+@pytest.mark.parametrize("tile_rows3", [4, 12, 100, 1024])
+def test_update_sweep_tile_rows(tile_rows3):
+    """The update sweep cuts the matrices into row blocks of its own (came_options.tile_rows3),
+    independent of the other two sweeps' (here 20): same result whatever their height, ragged
+    last block included, on aligned and unaligned widths."""
+    shapes = [(256, 512), (333, 1032), (70, 515), (512,)]
+    w = W.Workload("update-sweep-tiles", shapes, W.GRAD_BF16, seed=5, steps=3, grad_kind="normal",
+                   scale_range=(1e-3, 1e-1), zero_row_fraction=0.1)
+    _run(w, 3, TOL_100, check_every=1, tile_rows=20, tile_rows3=tile_rows3)
+    # bit-identical to the default height: the per-element arithmetic does not depend on the tiling
+    gen = W.Generator(w, device="cuda:0")
+    out = []
+    for tr3 in (0, tile_rows3):
+        th = [gen.theta0(i) for i in range(len(shapes))]
+        opt = P.CameStep(shapes, [w.grad_dtype] * len(shapes), tile_rows=20, tile_rows3=tr3)
+        try:
+            for t in (1, 2):
+                opt.step(th, [gen.grad(i, t) for i in range(len(shapes))], P.CameHyper(), w.lr, t)
+            torch.cuda.synchronize()
+            out.append([x.clone() for x in th] + [opt.state_view(0)["M"].clone()])
+        finally:
+            opt.close()
+    for a, b in zip(*out):
+        assert torch.equal(a, b)
+
+
 def _vocabulary_and_one_per_shape(w):
     """Tensor 0 (the vocabulary matrix: the tallest column reduction of the list) plus the first
     tensor of every other distinct shape, matrices and vectors."""

@@ -151,7 +151,8 @@ def test_bad_counts_options_and_null_pointers():
     assert lib.came_state_size(good, 0, None, ctypes.byref(sb), ctypes.byref(wb)) == -1
     assert lib.came_state_size(None, 1, None, ctypes.byref(sb), ctypes.byref(wb)) == -1
     assert lib.came_state_size(good, 1, None, None, ctypes.byref(wb)) == -1
-    for kw in (dict(tile_rows=3), dict(tile_rows=2), dict(tile_rows=2048), dict(algo=7), dict(group_elements=-5),
+    for kw in (dict(tile_rows=3), dict(tile_rows=2), dict(tile_rows=2048), dict(tile_rows3=3), dict(tile_rows3=2048),
+               dict(tile_rows3=-4), dict(algo=7), dict(group_elements=-5),
                dict(momentum_dtype=3), dict(vector_rule=2), dict(vector_rule=-1), dict(resident=3), dict(resident=-1),
                dict(resident_wait_us=-1)):
         o = B._options(**kw)

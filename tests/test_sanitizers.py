@@ -24,11 +24,11 @@ def plan_driver(tmp_path_factory):
     return exe
 
 
-def _plan(exe, tmp_path, descs, tile_rows=0, algo=0, group_elements=0, momentum=0, vector_rule=0, resident=0):
+def _plan(exe, tmp_path, descs, tile_rows=0, algo=0, group_elements=0, momentum=0, vector_rule=0, resident=0, tile_rows3=0):
     f = tmp_path / "descs.txt"
     f.write_text("".join(f"{r} {c} {nd} {dt}\n" for r, c, nd, dt in descs))
     res = subprocess.run([exe, str(f), str(tile_rows), str(algo), str(group_elements), str(momentum), str(vector_rule),
-                          str(resident)],
+                          str(resident), str(tile_rows3)],
                          capture_output=True, text=True, env=ENV)
     assert res.returncode == 0, res.stderr[-2000:]
     return [int(x) for x in res.stdout.split()]
@@ -42,6 +42,7 @@ def _descs(w):
 def test_planner_on_the_named_workloads(plan_driver, tmp_path, make):
     w = make()
     for kw in ({}, {"momentum": 1}, {"tile_rows": 4 if w.n_params < 10 ** 9 else 64, "group_elements": 10 ** 7},
+               {"tile_rows3": 4 if w.n_params < 10 ** 9 else 64}, {"tile_rows3": 1024, "tile_rows": 16 if w.n_params < 10 ** 9 else 64},
                {"resident": 2}, {"resident": 2, "tile_rows": 4 if w.n_params < 10 ** 9 else 64, "group_elements": 10 ** 7},
                {"resident": 2, "momentum": 1, "group_elements": 3 * 10 ** 7}):
         rc, state, scratch, items, fins, groups = _plan(plan_driver, tmp_path, _descs(w), **kw)
@@ -54,7 +55,7 @@ def test_planner_on_degenerate_descriptors(plan_driver, tmp_path):
     for tr in (0, 4, 1024):
         for res in (0, 2):
             assert _plan(plan_driver, tmp_path, ok, tile_rows=tr, resident=res)[0] == 0
-    huge = [(1 << 20, 1 << 20, 2, 1)]  # 2^40 elements: fine in tall tiles, too many 4-row tiles for 32-bit tables
+    huge = [(1 << 18, 1 << 20, 2, 1)]  # 2^38 elements: fine in tall tiles, too many 4-row tiles for 32-bit tables
     assert _plan(plan_driver, tmp_path, huge, tile_rows=1024)[0] == 0
     assert _plan(plan_driver, tmp_path, huge, tile_rows=4)[0] == -1
     # matrices at and around the on-chip limit of 512 tiles of 16 x 512
@@ -70,7 +71,7 @@ def test_planner_on_degenerate_descriptors(plan_driver, tmp_path):
     # a plan whose tile table would not fit 32-bit indices: 2^40 rows of 4-row tiles
     assert _plan(plan_driver, tmp_path, [(1 << 40, 8, 2, 0)], tile_rows=4)[0] == -1
     for kw in ({"tile_rows": 3}, {"tile_rows": 2048}, {"algo": 2}, {"group_elements": -1}, {"momentum": 2}, {"vector_rule": 2},
-               {"resident": 3}, {"resident": -1}):
+               {"resident": 3}, {"resident": -1}, {"tile_rows3": 6}, {"tile_rows3": 1028}):
         assert _plan(plan_driver, tmp_path, [(8, 8, 2, 0)], **kw)[0] == -1, kw
 
 
