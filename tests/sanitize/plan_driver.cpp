@@ -43,7 +43,7 @@ int check_disjoint(std::vector<Range>& r, long long limit, const char* blob)
 
 int main(int argc, char** argv)
 {
-    if (argc != 8) return 2;
+    if (argc != 9) return 2;
     std::vector<came_tensor_desc> descs;
     if (FILE* f = std::fopen(argv[1], "r")) {
         long long rows, cols;
@@ -61,7 +61,7 @@ int main(int argc, char** argv)
     o.momentum_dtype = std::atoi(argv[5]);
     o.vector_rule = std::atoi(argv[6]);
     o.resident = std::atoi(argv[7]);
-    if (argc > 8) o.tile_rows3 = std::atoi(argv[8]);
+    o.tile_rows3 = std::atoi(argv[8]);
     Plan p;
     const int rc = build_plan(descs.empty() ? nullptr : descs.data(), static_cast<int32_t>(descs.size()), &o, &p);
     if (rc != CAME_OK) {
