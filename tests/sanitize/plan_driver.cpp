@@ -4,7 +4,7 @@
 // kernels assume about it: every work item and finalize item names a tensor and a block that
 // exist, every state array and every scratch region lies inside its blob, none overlap.
 //
-//   plan_driver <descs.txt> <tile_rows> <algo> <group_elements> <momentum_dtype> <vector_rule> <resident>
+//   plan_driver <descs.txt> <tile_rows> <algo> <group_elements> <momentum_dtype> <vector_rule> <resident> <tile_rows3>
 //
 // Prints "rc state_bytes scratch_bytes items fins groups" and exits 0, or exits 3 with a message
 // when an invariant is broken.
