@@ -108,6 +108,26 @@ ODD_SHAPES = [(1, 1), (1, 8), (8, 1), (3, 5), (2, 768), (5, 520), (7, 1000), (13
               (1030, 8), (4, 4104)]
 
 
+NARROW_SHAPES = [(37, 768), (129, 256), (77, 8), (50, 1160), (1, 264), (2, 128), (3, 640), (261, 768)]
+
+
+@pytest.mark.parametrize("momentum", [P.MOMENTUM_F32, P.MOMENTUM_BF16], ids=["m-f32", "m-bf16"])
+@pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["g-f32", "g-bf16"])
+@pytest.mark.parametrize("algo", [P.ALGO_CAME, P.ALGO_ADAFACTOR], ids=["came", "adafactor"])
+def test_last_column_block_of_at_most_256_columns(dtype, momentum, algo):
+    """Matrices whose last column block is at most half a tile wide (768 = 512 + 256, 8, 264 = 256 + 8,
+    1160 = 2 * 512 + 136 ...: the widths of BERT-base / GPT-2-small shaped layers among them), with odd
+    and even row counts and one to several row blocks, through all kernel variants."""
+    w = W.Workload("narrow-tiles", NARROW_SHAPES, dtype, seed=321, steps=5, grad_kind="normal",
+                   scale_range=(1e-4, 1e-1), zero_row_fraction=0.2)
+    if momentum == P.MOMENTUM_BF16:
+        # the stored momentum is rounded: compared one step at a time from the oracle's state
+        from test_gpu_bf16_momentum import one_step_from_oracle_state
+        one_step_from_oracle_state(w, 4, algo=algo, tile_rows=12, tile_rows3=20)
+    else:
+        _run(w, 5, TOL_100, check_every=1, algo=algo, tile_rows=12, tile_rows3=20)
+
+
 @pytest.mark.parametrize("dtype", [W.GRAD_F32, W.GRAD_BF16], ids=["f32", "bf16"])
 def test_odd_shapes(dtype):
     """Ragged rows and columns, widths that are not a multiple of 8 (scalar-load
