@@ -27,7 +27,7 @@ inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Rows per tile of sweeps 1 and 2 when the caller does not choose: the largest multiple of 16 up
+// Rows per tile of sweeps 1 and 2 when the caller does not choose: the largest power of two up
 // to 1024 that still yields six tiles per compute unit (256 CUs).  A tile of these sweeps costs
 // 20 to 25 us beyond its streaming (a chain of dependent loads under load before its first row --
 // work item, descriptor, r, c -- and the combination and storing of its partial sums after its
@@ -45,7 +45,9 @@ int32_t auto_tile_rows(const came_tensor_desc* d, int32_t count, const std::vect
             if (d[t].ndim == 2 && !resident[t]) tiles += ceil_div(d[t].rows, tr) * ceil_div(d[t].cols, kTileCols);
         return tiles;
     };
-    for (int32_t tr = 1024; tr >= 64; tr -= 16)
+    // (powers of two only: they divide the usual matrix heights, whereas e.g. 496 rows would cut a
+    // 1024-row matrix into 496 + 496 + 32 and add a third more tiles, most of them nearly empty)
+    for (int32_t tr = 1024; tr >= 64; tr /= 2)
         if (tiles_at(tr) >= kNumCus * 6) return tr;
     for (int32_t tr = 64; tr >= 16; tr -= 16)
         if (tiles_at(tr) >= kNumCus * 2) return tr;
