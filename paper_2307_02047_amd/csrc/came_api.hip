@@ -474,13 +474,10 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
             }
             continue;
         }
-        bool vectors_pending = g.vec_end > g.vec_begin;  // they ride along with the first sweep-1 launch
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            const int32_t vb = vectors_pending ? g.vec_begin : 0, ve = vectors_pending ? g.vec_end : 0;
-            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], vb, ve, sh, fh, s); });
+            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], 0, 0, sh, fh, s); });
             if (e != hipSuccess) return failed(e);
-            vectors_pending = false;
         }
         e = timed_launch(ctx, 1, s, [&] { return launch_finalize1(tb, g.fin_begin, g.fin_end, fh, s); });
         if (e != hipSuccess) return failed(e);
@@ -491,10 +488,15 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
         }
         e = timed_launch(ctx, 3, s, [&] { return launch_finalize2(tb, g.fin_begin, g.fin_end, fh, s); });
         if (e != hipSuccess) return failed(e);
+        // the whole-vector items are the first workgroups of the first sweep-3 launch: independent,
+        // latency-bound work that is over long before the launch's tiles are
+        bool vectors_pending = g.vec_end > g.vec_begin;
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, p.tile_rows3, g.var3_begin[v], g.var3_end[v], sh, s); });
+            const int32_t vb = vectors_pending ? g.vec_begin : 0, ve = vectors_pending ? g.vec_end : 0;
+            e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, p.tile_rows3, g.var3_begin[v], g.var3_end[v], vb, ve, sh, fh, s); });
             if (e != hipSuccess) return failed(e);
+            vectors_pending = false;
         }
     }
     return CAME_OK;

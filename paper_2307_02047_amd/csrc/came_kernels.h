@@ -84,9 +84,11 @@ hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32
 // Finalize 2: kappa (Eq. 1), R, C and the per-workgroup sums of R.
 hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);
-// Sweep 3: momentum and parameter update.
+// Sweep 3: momentum and parameter update.  The launch's first vec_end - vec_begin workgroups
+// update the whole-vector items [vec_begin, vec_end) (pass 0, 0 for none).
 hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
-                         int32_t item_end, const SweepHyper& h, hipStream_t s);
+                         int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
+                         const FinalizeHyper& fh, hipStream_t s);
 
 // On-chip path (came_resident.hip): the complete Algorithm-2 step of the matrices whose tiles are
 // the work items [item_begin, item_end) (kind 3, all of `variant`), one launch of at most

@@ -34,6 +34,8 @@
 // No atomics on data: results are bit-reproducible run to run.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "came_device.hpp"
 #include "came_kernels.h"
 
@@ -770,10 +772,16 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #endif
 #define CAME_SWEEP3_KERNEL(NAME, BF16, ALIGNED, MB16, WAVES)                                              \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
-    void NAME(DeviceTables tb, int32_t item_begin, SweepHyper h)                                    \
+    void NAME(DeviceTables tb, int32_t item_begin, int32_t vec_begin, int32_t vec_count,            \
+              SweepHyper h, FinalizeHyper fh)                                                       \
     {                                                                                               \
-        extern __shared__ float rowfac_f32[];                                                       \
-        const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];                 \
+        extern __shared__ __attribute__((aligned(16))) float rowfac_f32[];                          \
+        if (static_cast<int32_t>(blockIdx.x) < vec_count) {                                         \
+            vector_item(tb, vec_begin + blockIdx.x, h, fh, reinterpret_cast<double*>(rowfac_f32));  \
+            return;                                                                                 \
+        }                                                                                           \
+        const int32_t ntile = static_cast<int32_t>(gridDim.x) - vec_count;                          \
+        const WorkItem it = tb.items[item_begin + xcd_item(static_cast<int32_t>(blockIdx.x) - vec_count, ntile)]; \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const TileGeom t = tile_geom(tm, it, tm.tile_rows3);                                        \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
@@ -977,20 +985,23 @@ hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fi
 }
 
 hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
-                         int32_t item_end, const SweepHyper& h, hipStream_t s)
+                         int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
+                         const FinalizeHyper& fh, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
-    const dim3 grid(item_end - item_begin), block(kWorkgroup);
-    const size_t dyn = sizeof(float) * 2 * static_cast<size_t>(tile_rows);  // two row factors per row of a tile
+    const int32_t vec_count = vec_end - vec_begin;
+    const dim3 grid(item_end - item_begin + vec_count), block(kWorkgroup);
+    // two row factors per row of a tile; a whole-vector item needs 4 doubles
+    const size_t dyn = std::max(sizeof(float) * 2 * static_cast<size_t>(tile_rows), sizeof(double) * 4);
     switch (variant) {
-        case 0: sweep3_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        case 1: sweep3_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        case 2: sweep3_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        case 3: sweep3_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        case 4: sweep3_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        case 5: sweep3_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        case 6: sweep3_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
-        default: sweep3_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, h); break;
+        case 0: sweep3_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        case 1: sweep3_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        case 2: sweep3_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        case 3: sweep3_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        case 4: sweep3_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        case 5: sweep3_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        case 6: sweep3_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        default: sweep3_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
     }
     return hipGetLastError();
 }
