@@ -291,7 +291,7 @@ int came_plan_query(const came_tensor_desc* descs, int32_t count, const came_opt
         const int rc = build_plan(descs, count, opts, &plan);
         if (rc != CAME_OK) return rc;
         int64_t tiles = 0;  // the update sweep's own cut of the same matrices is not counted again
-        for (const WorkItem& it : plan.items) tiles += it.kind != 4;
+        for (const WorkItem& it : plan.items) tiles += it.kind != 4 && it.kind != 5;
         out[0] = plan.tile_rows;
         out[1] = kTileCols;
         out[2] = tiles;

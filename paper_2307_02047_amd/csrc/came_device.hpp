@@ -314,6 +314,7 @@ struct TileGeom {
     int nrows;
     int64_t col;  // first column of this lane
     int ncol;     // valid columns of this lane: 0..8
+    int rsel;     // folded tiles: which row of the pair this lane's columns lie in (0 otherwise)
 };
 
 // `tile_rows`: the height of the row blocks that it.rb counts (TensorMeta.tile_rows for the items
@@ -329,12 +330,31 @@ __device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkIt
     t.col = static_cast<int64_t>(it.cb) * kTileCols + t.lane * kLaneCols;
     const int64_t cleft = tm.m - t.col;
     t.ncol = cleft >= kLaneCols ? kLaneCols : (cleft > 0 ? static_cast<int>(cleft) : 0);
+    t.rsel = 0;
     return t;
 }
 
 __device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkItem& it)
 {
     return tile_geom(tm, it, tm.tile_rows);
+}
+
+// Tile of a folded matrix (work items of kind 5): rows and columns of the view with ceil(n/2)
+// rows of 2m columns.  `col` is the lane's first column in that view; rsel says which of the two
+// rows of the matrix it lies in (0: row 2v, 1: row 2v+1) -- a lane's 8 columns never straddle,
+// since m is a multiple of 256.  All 512 columns of the tile exist.
+__device__ __forceinline__ TileGeom folded_geom(const TensorMeta& tm, const WorkItem& it, int32_t tile_rows)
+{
+    TileGeom t;
+    t.lane = threadIdx.x & 63;
+    t.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    t.row0 = static_cast<int64_t>(it.rb) * tile_rows;
+    const int64_t left = (tm.n + 1) / 2 - t.row0;
+    t.nrows = static_cast<int>(left < tile_rows ? left : tile_rows);
+    t.col = static_cast<int64_t>(it.cb) * kTileCols + t.lane * kLaneCols;
+    t.ncol = kLaneCols;
+    t.rsel = t.col >= tm.m ? 1 : 0;
+    return t;
 }
 
 // ---------------------------------------------------------------- vectors

@@ -653,13 +653,21 @@ constexpr int kRows3 = CAME_ROWS3;
 // with a decoupled weight decay theta_{t-1} is first scaled by h.decay = 1 - eta lambda.
 // COPY16: also write theta_t as bfloat16 to theta16 (came_step_bf16_copy).
 // MB16: M is stored as bfloat16; theta_t is formed from the unrounded M_t.
-template <bool BF16, bool ALIGNED, bool FULL, bool COPY16, bool MB16>
+// SHAPE: kSweep3Full (the tile's 512 columns exist), kSweep3Ragged (the matrix ends inside the
+// tile), kSweep3Folded (tile of the ceil(n/2) x 2m view of a folded matrix, t from folded_geom: a
+// step of the wave covers 512 consecutive entries of rows 2v, 2v+1 as they lie in memory, each
+// lane with the row and column factors of the entry it really holds).
+enum : int { kSweep3Full = 0, kSweep3Ragged = 1, kSweep3Folded = 2 };
+template <bool BF16, bool ALIGNED, int SHAPE, bool COPY16, bool MB16>
 __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
                             float* theta, void* theta16, float* state, const char* scratch,
-                            const TensorScalars* sc, const SweepHyper& h, float* rowfac /* [2][tile_rows3] */)
+                            const TensorScalars* sc, const SweepHyper& h, float* rowfac /* [2][2 tile_rows3] */)
 {
+    constexpr bool FULL = SHAPE != kSweep3Ragged;
+    constexpr bool FOLDED = SHAPE == kSweep3Folded;
     const int64_t m = tm.m;
-    const int TR = tm.tile_rows3;
+    const int64_t pitch = FOLDED ? 2 * m : m;  // elements from one row of the tile to the next
+    const int TR = 2 * tm.tile_rows3;           // room per factor array: a folded tile has two rows of the matrix per row
     const float* r = state + tm.off_r;
     const float* c = state + tm.off_c;
     const float* R = state + tm.off_R;
@@ -668,13 +676,19 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const bool came = h.algo == CAME_ALGO_CAME;
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
+    // folded tiles: rows of the matrix in the tile, first of them, this lane's column in the matrix
+    const int64_t mrow0 = FOLDED ? 2 * t.row0 : t.row0;
+    const int mrows = FOLDED ? static_cast<int>(min(static_cast<int64_t>(2 * t.nrows), tm.n - mrow0)) : t.nrows;
+    const int64_t mcol = FOLDED ? lcol - t.rsel * m : lcol;
 
     struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; F32Raw th; };
     // real = false: the pipelined loop's last, unused request; the streaming gradient load of it
     // goes to the tensor's descriptor (hot in L2) instead of fetching the last batch again
     auto load_row = [&](int j, bool real = true) {
         Row x;
-        const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
+        // (folded, odd number of rows: the lanes of the missing last row read the row before it)
+        const int64_t off = FOLDED ? (2 * (t.wave + kWaves * j) + 1 < mrows ? lcol : mcol) : lcol;
+        const int64_t idx = (t.row0 + t.wave + kWaves * j) * pitch + off;
         x.g = load_grad_raw<BF16, ALIGNED>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
         x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         x.th = load_f32_raw<ALIGNED>(theta, idx, lncol);
@@ -700,19 +714,19 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 
     // per-row factors kappa rsqrt(r_i / 1^T r) and eta rsqrt(R_i / 1^T R) of the tile's rows,
     // once, into LDS (inside the row loop: LDS broadcast reads, no global load to wait for)
-    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup) {
-        rowfac[i] = rsqrtf(r[t.row0 + i]) * row_scale_u;
-        rowfac[TR + i] = came ? rsqrtf(R[t.row0 + i]) * row_scale_s : row_scale_s;
+    for (int i = threadIdx.x; i < mrows; i += kWorkgroup) {
+        rowfac[i] = rsqrtf(r[mrow0 + i]) * row_scale_u;
+        rowfac[TR + i] = came ? rsqrtf(R[mrow0 + i]) * row_scale_s : row_scale_s;
     }
 
     float b[8], Bc[8];
     {
         float cv[8];
-        unpack(load_f32_raw<ALIGNED>(c, lcol, lncol), cv);
+        unpack(load_f32_raw<ALIGNED>(c, mcol, lncol), cv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) b[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
         if (came) {
-            unpack(load_f32_raw<ALIGNED>(C, lcol, lncol), cv);
+            unpack(load_f32_raw<ALIGNED>(C, mcol, lncol), cv);
 #pragma unroll
             for (int e = 0; e < 8; ++e) Bc[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
         } else {
@@ -723,9 +737,12 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     __syncthreads();
 
     auto consume_row = [&](const Row& row, int j) {
-        const int i = t.wave + kWaves * j;
-        const float a = rowfac[i];
-        const float Ar = rowfac[TR + i];
+        // i: the lane's row of the matrix, counted from the tile's first
+        const int i = FOLDED ? 2 * (t.wave + kWaves * j) + t.rsel : t.wave + kWaves * j;
+        const bool row_ok = !FOLDED || i < mrows;
+        const int ic = FOLDED ? (row_ok ? i : i - 1) : i;
+        const float a = rowfac[ic];
+        const float Ar = rowfac[TR + ic];
         float x[8], mo[8], th[8], mn[8], tn[8];
         unpack<BF16>(row.g, x);
         unpack<MB16>(row.mo, mo);
@@ -736,8 +753,13 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             mn[e] = fmaf(h.beta1, mo[e], h.one_minus_beta1 * uh);
             tn[e] = fmaf(th[e], h.decay, -((mn[e] * Ar) * Bc[e]));
         }
-        const int64_t idx = (t.row0 + i) * m + t.col;
-        if constexpr (ALIGNED && FULL) {
+        const int64_t idx = (t.row0 + t.wave + kWaves * j) * pitch + t.col;
+        if constexpr (FOLDED) {
+            const int nc = row_ok ? kLaneCols : 0;
+            store_mom<MB16, true>(M, idx, nc, mn);
+            store_f32x8<true>(theta, idx, nc, tn);
+            if constexpr (COPY16) store_bf16x8<true>(theta16, idx, nc, tn);
+        } else if constexpr (ALIGNED && FULL) {
             store_mom<MB16, true>(M, idx, kLaneCols, mn);
             store_f32x8<true>(theta, idx, kLaneCols, tn);
             if constexpr (COPY16) store_bf16x8<true>(theta16, idx, kLaneCols, tn);
@@ -783,18 +805,22 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const int32_t ntile = static_cast<int32_t>(gridDim.x) - vec_count;                          \
         const WorkItem it = tb.items[item_begin + xcd_item(static_cast<int32_t>(blockIdx.x) - vec_count, ntile)]; \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
-        const TileGeom t = tile_geom(tm, it, tm.tile_rows3);                                        \
+        const bool folded = ALIGNED && it.kind == 5;                                                \
+        const TileGeom t = folded ? folded_geom(tm, it, tm.tile_rows3) : tile_geom(tm, it, tm.tile_rows3); \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
         float* theta = static_cast<float*>(tb.theta[it.tensor]);                         \
         void* theta16 = tb.theta16[it.tensor];                       \
         const void* g = tb.grad[it.tensor];                    \
         const TensorScalars* sc = tb.scalars + it.tensor;                                           \
-        if (!ALIGNED || full) {                                                                     \
-            if (theta16) sweep3_tile<BF16, ALIGNED, true, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
-            else sweep3_tile<BF16, ALIGNED, true, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+        if (folded) {                                                                               \
+            if (theta16) sweep3_tile<BF16, ALIGNED, ALIGNED ? kSweep3Folded : kSweep3Full, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, ALIGNED ? kSweep3Folded : kSweep3Full, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+        } else if (!ALIGNED || full) {                                                              \
+            if (theta16) sweep3_tile<BF16, ALIGNED, kSweep3Full, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, kSweep3Full, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
         } else {                                                                                    \
-            if (theta16) sweep3_tile<BF16, ALIGNED, false, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
-            else sweep3_tile<BF16, ALIGNED, false, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            if (theta16) sweep3_tile<BF16, ALIGNED, kSweep3Ragged, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, kSweep3Ragged, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
         }                                                                                           \
     }
 CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, false, CAME_WAVES3)
@@ -826,15 +852,19 @@ __global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTable
     const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];
     const TensorMeta& tm = tb.metas[it.tensor];
     if (!(tm.flags & kFlagAligned)) return;
-    const TileGeom t = tile_geom(tm, it, it.kind == 4 ? tm.tile_rows3 : tm.tile_rows);
+    const bool folded = it.kind == 5;
+    const TileGeom t = folded ? folded_geom(tm, it, tm.tile_rows3)
+                              : tile_geom(tm, it, it.kind == 4 ? tm.tile_rows3 : tm.tile_rows);
     if (t.ncol == 0) return;
+    const int64_t pitch = folded ? 2 * tm.m : tm.m;
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
     float* M = tb.state + tm.off_M;
     const bool mb16 = tm.flags & kFlagBf16Momentum, gb16 = tm.flags & kFlagBf16Grad;
     const CAME_GLOBAL uint16_t* g16 = glob(static_cast<const uint16_t*>(tb.grad[it.tensor]));
     uint32_t sink = 0u;
     for (int i = t.wave; i < t.nrows; i += kWaves) {
-        const int64_t idx = (t.row0 + i) * tm.m + t.col;
+        const int64_t idx = (t.row0 + i) * pitch + t.col;
+        if (folded && 2 * (t.row0 + i) + t.rsel >= tm.n) continue;  // odd number of rows: no second row in the last pair
         if (with_g) {
             const CAME_GLOBAL u32x4* pg = (const CAME_GLOBAL u32x4*)(g16 + (gb16 ? idx : 2 * idx));
             u32x4 a = __builtin_nontemporal_load(pg);
@@ -991,8 +1021,9 @@ hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, 
     if (item_end <= item_begin) return hipSuccess;
     const int32_t vec_count = vec_end - vec_begin;
     const dim3 grid(item_end - item_begin + vec_count), block(kWorkgroup);
-    // two row factors per row of a tile; a whole-vector item needs 4 doubles
-    const size_t dyn = std::max(sizeof(float) * 2 * static_cast<size_t>(tile_rows), sizeof(double) * 4);
+    // two factors per row of the matrix in a tile (a folded tile holds two of them per row of
+    // its own); a whole-vector item needs 4 doubles
+    const size_t dyn = std::max(sizeof(float) * 4 * static_cast<size_t>(tile_rows), sizeof(double) * 4);
     switch (variant) {
         case 0: sweep3_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
         case 1: sweep3_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;

@@ -133,6 +133,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
                 if (RB > kMaxItems || CB > kMaxItems || RB * CB > kMaxItems) return CAME_EINVAL;
                 items += RB * CB;
                 if (!resident[t]) {
+                    // (a folded matrix has fewer tiles than this, never more)
                     const int64_t RB3 = ceil_div(d.rows, p.tile_rows3);
                     if (RB3 > kMaxItems || RB3 * CB > kMaxItems) return CAME_EINVAL;
                     items += RB3 * CB;
@@ -172,6 +173,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             tm.off_C = off; off = round_up(off + tm.m, kAlignFloats);
             ++p.n_matrices;
             if (tm.m % kLaneCols == 0) tm.flags |= kFlagAligned;
+            if (!resident[t] && tm.m % kTileCols == kTileCols / 2) tm.flags |= kFlagFolded;
             if (resident[t]) {
                 tm.flags |= kFlagResident;
                 ++p.n_resident;
@@ -246,9 +248,11 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
                 const TensorMeta& tm = p.metas[t];
                 if ((tm.flags & (kFlagVector | kFlagResident)) || variant_of(tm.flags) != v) continue;
-                const int32_t RB3 = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows3));
+                const bool folded = tm.flags & kFlagFolded;
+                const int32_t RB3 = static_cast<int32_t>(ceil_div(folded ? ceil_div(tm.n, 2) : tm.n, tm.tile_rows3));
+                const int32_t CB3 = folded ? static_cast<int32_t>(2 * tm.m / kTileCols) : tm.CB;
                 for (int32_t rb = 0; rb < RB3; ++rb)
-                    for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 4});
+                    for (int32_t cb = 0; cb < CB3; ++cb) p.items.push_back(WorkItem{t, rb, cb, folded ? 5 : 4});
             }
             g.var3_end[v] = static_cast<int32_t>(p.items.size());
         }

@@ -51,6 +51,7 @@ enum TensorFlags : int32_t {
     kFlagBf16Momentum = 8,  // M stored as bfloat16 (off_M still counts floats from the blob's start)
     kFlagMomentumOnly = 16, // vector updated by -eta M (no instability / confidence statistics)
     kFlagResident = 32,     // matrix on the on-chip path (tile_rows = kResidentRows, no finalize items)
+    kFlagFolded = 64,       // the update sweep treats the matrix as ceil(n/2) rows of 2m columns (see WorkItem)
 };
 
 // Per-tensor descriptor in device memory (scratch blob).
@@ -93,7 +94,11 @@ struct WorkItem {
     int32_t rb, cb;  // row block, column block (matrix tiles)
     int32_t kind;    // 0 = matrix tile, 1 = whole vector, 2 = chunk `rb` of a long vector,
                      // 3 = tile of a matrix on the on-chip path,
-                     // 4 = matrix tile of the update sweep (row blocks of TensorMeta.tile_rows3 rows)
+                     // 4 = matrix tile of the update sweep (row blocks of TensorMeta.tile_rows3 rows),
+                     // 5 = the same for a folded matrix: a matrix whose width is an odd multiple of 256
+                     //     (768 = 512 + 256 ...) is swept as ceil(n/2) rows of 2m columns -- row 2v followed
+                     //     by row 2v+1, which is how they lie in memory -- so that every tile is 512 columns
+                     //     wide; rb and cb count blocks of that view
 };
 
 // Vectors up to this length are updated by one workgroup in one kernel.  Longer ones are cut

@@ -154,9 +154,26 @@ int main(int argc, char** argv)
         for (int v = 0; v < kVariants; ++v)
             for (int32_t k = g.var3_begin[v]; k < g.var3_end[v]; ++k) {
                 const WorkItem& it = p.items[k];
-                if (it.tensor < g.tensor_begin || it.tensor >= g.tensor_end || it.kind != 4) return fail("update-sweep item", k, it.tensor);
+                if (it.tensor < g.tensor_begin || it.tensor >= g.tensor_end || (it.kind != 4 && it.kind != 5)) return fail("update-sweep item", k, it.tensor);
                 const TensorMeta& tm = p.metas[it.tensor];
                 if (tm.tile_rows3 < 4 || tm.tile_rows3 % 4 != 0) return fail("update-sweep tile height", it.tensor, tm.tile_rows3);
+                if ((it.kind == 5) != ((tm.flags & kFlagFolded) != 0)) return fail("update-sweep item kind", it.kind, tm.flags);
+                if (it.kind == 5) {
+                    // folded: the matrix as ceil(n/2) rows of 2m columns; aligned rows, the width an odd multiple of 256
+                    if (!(tm.flags & kFlagAligned) || (tm.flags & (kFlagVector | kFlagResident)) || variant_of(tm.flags) != v ||
+                        tm.m % kTileCols != kTileCols / 2)
+                        return fail("folded matrix", it.tensor, tm.m);
+                    const long long nv = (tm.n + 1) / 2, RB3 = (nv + tm.tile_rows3 - 1) / tm.tile_rows3, CB3 = 2 * tm.m / kTileCols;
+                    if (it.rb < 0 || it.rb >= RB3 || it.cb < 0 || it.cb >= CB3) return fail("folded item block", it.rb, it.cb);
+                    const long long v0 = static_cast<long long>(it.rb) * tm.tile_rows3, v1 = std::min<long long>(v0 + tm.tile_rows3, nv);
+                    for (long long vr = v0; vr < v1; ++vr)
+                        for (long long c0 = static_cast<long long>(it.cb) * kTileCols; c0 < static_cast<long long>(it.cb + 1) * kTileCols; c0 += kLaneCols) {
+                            const long long row = 2 * vr + (c0 >= tm.m ? 1 : 0);
+                            if (c0 < tm.m && c0 + kLaneCols > tm.m) return fail("a lane's columns straddle two rows", it.tensor, c0);
+                            if (row < tm.n) seen3[it.tensor] += kLaneCols;
+                        }
+                    continue;
+                }
                 const long long RB3 = (tm.n + tm.tile_rows3 - 1) / tm.tile_rows3;
                 if ((tm.flags & (kFlagVector | kFlagResident)) || variant_of(tm.flags) != v || it.rb < 0 || it.rb >= RB3 ||
                     it.cb < 0 || it.cb >= tm.CB)

@@ -104,11 +104,12 @@ def test_llama_full_size_sampled():
     _run(w, 2, TOL_1 * 2, check=check)
 
 
-ODD_SHAPES = [(1, 1), (1, 8), (8, 1), (3, 5), (2, 768), (5, 520), (7, 1000), (130, 24), (33, 513), (257, 1031),
-              (1030, 8), (4, 4104)]
+ODD_SHAPES = [(1, 1), (1, 8), (8, 1), (3, 5), (2, 768), (5, 768), (3, 256), (5, 520), (7, 1000), (130, 24), (33, 513),
+              (257, 1031), (1030, 8), (4, 4104)]
 
 
-NARROW_SHAPES = [(37, 768), (129, 256), (77, 8), (50, 1160), (1, 264), (2, 128), (3, 640), (261, 768)]
+NARROW_SHAPES = [(37, 768), (129, 256), (77, 8), (50, 1160), (1, 264), (2, 128), (3, 640), (261, 768), (1, 768), (2, 256),
+                 (70, 1280), (64, 768)]
 
 
 @pytest.mark.parametrize("momentum", [P.MOMENTUM_F32, P.MOMENTUM_BF16], ids=["m-f32", "m-bf16"])
@@ -117,7 +118,9 @@ NARROW_SHAPES = [(37, 768), (129, 256), (77, 8), (50, 1160), (1, 264), (2, 128),
 def test_last_column_block_of_at_most_256_columns(dtype, momentum, algo):
     """Matrices whose last column block is at most half a tile wide (768 = 512 + 256, 8, 264 = 256 + 8,
     1160 = 2 * 512 + 136 ...: the widths of BERT-base / GPT-2-small shaped layers among them), with odd
-    and even row counts and one to several row blocks, through all kernel variants."""
+    and even row counts and one to several row blocks, through all kernel variants.  Those whose width
+    is an odd multiple of 256 (256, 768, 1280) are swept by the update sweep as ceil(n/2) rows of 2m
+    columns; an odd row count leaves the last of those rows half empty."""
     w = W.Workload("narrow-tiles", NARROW_SHAPES, dtype, seed=321, steps=5, grad_kind="normal",
                    scale_range=(1e-4, 1e-1), zero_row_fraction=0.2)
     if momentum == P.MOMENTUM_BF16:

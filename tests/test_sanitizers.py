@@ -50,7 +50,8 @@ def test_planner_on_the_named_workloads(plan_driver, tmp_path, make):
 
 
 def test_planner_on_degenerate_descriptors(plan_driver, tmp_path):
-    ok = [(1, 1, 2, 0), (1, 8, 2, 1), (8, 1, 2, 0), (2, 768, 2, 0), (4, 4104, 2, 1), (1, 1, 1, 0), (16385, 1, 1, 1),
+    ok = [(1, 1, 2, 0), (1, 8, 2, 1), (8, 1, 2, 0), (2, 768, 2, 0), (5, 768, 2, 1), (33, 256, 2, 0), (1, 1280, 2, 1),
+          (4, 4104, 2, 1), (1, 1, 1, 0), (16385, 1, 1, 1),
           (10 ** 9, 1, 1, 0)]
     for tr in (0, 4, 1024):
         for res in (0, 2):
