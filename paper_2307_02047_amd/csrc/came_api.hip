@@ -291,7 +291,7 @@ int came_plan_query(const came_tensor_desc* descs, int32_t count, const came_opt
         const int rc = build_plan(descs, count, opts, &plan);
         if (rc != CAME_OK) return rc;
         int64_t tiles = 0;  // the update sweep's own cut of the same matrices is not counted again
-        for (const WorkItem& it : plan.items) tiles += it.kind != 4 && it.kind != 5;
+        for (const WorkItem& it : plan.items) tiles += it.kind != 4 && it.kind != 5;  // (kind 6 is a tile of sweeps 1 and 2)
         out[0] = plan.tile_rows;
         out[1] = kTileCols;
         out[2] = tiles;
@@ -454,6 +454,7 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
             e = timed_launch(ctx, 5, s, [&] { return launch_long_vectors(tb, g.lvec_begin, g.lvec_end, sh, fh, s); });
             if (e != hipSuccess) return failed(e);
         }
+        const int32_t lds_rows = p.any_folded ? 2 * p.tile_rows : p.tile_rows;
         bool on_chip = false;
         for (int v = 0; v < kVariants; ++v) on_chip = on_chip || g.res_end[v] > g.res_begin[v];
         if (on_chip) {
@@ -476,14 +477,14 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
         }
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, p.tile_rows, g.var_begin[v], g.var_end[v], 0, 0, sh, fh, s); });
+            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, lds_rows, g.var_begin[v], g.var_end[v], 0, 0, sh, fh, s); });
             if (e != hipSuccess) return failed(e);
         }
         e = timed_launch(ctx, 1, s, [&] { return launch_finalize1(tb, g.fin_begin, g.fin_end, fh, s); });
         if (e != hipSuccess) return failed(e);
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, p.algo, p.tile_rows, g.var_begin[v], g.var_end[v], p.reverse_sweep2, s); });
+            e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, p.algo, lds_rows, g.var_begin[v], g.var_end[v], p.reverse_sweep2, s); });
             if (e != hipSuccess) return failed(e);
         }
         e = timed_launch(ctx, 3, s, [&] { return launch_finalize2(tb, g.fin_begin, g.fin_end, fh, s); });
@@ -668,22 +669,17 @@ int came_probe_placement(came_ctx* ctx, void* const* theta_dev, const void* cons
         const int used_slot = ctx->slot;
         const bool with_g = grad_dev != nullptr;
         double bytes = 0.0;
-        for (const Group& g : p.groups)
-            for (int v = 0; v < kVariants; ++v) {
-                if (v & 2) continue;  // aligned variants only
-                for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
-                    const TensorMeta& tm = p.metas[p.items[k].tensor];
-                    const int64_t rows = std::min<int64_t>(tm.tile_rows, tm.n - int64_t(p.items[k].rb) * tm.tile_rows);
-                    const int64_t cols = std::min<int64_t>(kTileCols, tm.m - int64_t(p.items[k].cb) * kTileCols);
-                    const double mb = (tm.flags & kFlagBf16Momentum) ? 2.0 : 4.0;
-                    const double gb = (tm.flags & kFlagBf16Grad) ? 2.0 : 4.0;
-                    // sweep 3's streams: theta and M read and written (g read);
-                    // with gradients also sweep 2's: g and M read
-                    double per = 8.0 + 2.0 * mb;
-                    if (with_g) per += gb + (gb + mb);
-                    bytes += per * static_cast<double>(rows * cols);
-                }
-            }
+        // every streamed matrix with 16-byte aligned rows, all of its entries
+        for (const TensorMeta& tm : p.metas) {
+            if ((tm.flags & (kFlagVector | kFlagResident)) || !(tm.flags & kFlagAligned)) continue;
+            const double mb = (tm.flags & kFlagBf16Momentum) ? 2.0 : 4.0;
+            const double gb = (tm.flags & kFlagBf16Grad) ? 2.0 : 4.0;
+            // sweep 3's streams: theta and M read and written (g read);
+            // with gradients also sweep 2's: g and M read
+            double per = 8.0 + 2.0 * mb;
+            if (with_g) per += gb + (gb + mb);
+            bytes += per * static_cast<double>(tm.n) * static_cast<double>(tm.m);
+        }
         if (bytes == 0.0) return CAME_OK;
         const DeviceTables tb = tables_for(ctx, used_slot);
         hipEvent_t e0, e1;

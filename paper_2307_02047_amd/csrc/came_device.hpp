@@ -278,6 +278,19 @@ __device__ __forceinline__ T wave_sum_lane63(T v)
     return v;
 }
 
+// Sums over the two halves of a wave: the total of lanes 0..31 is valid in lanes 16..31, that of
+// lanes 32..63 in lanes 48..63 (the butterflies and the first row broadcast of wave_sum_lane63).
+template <class T>
+__device__ __forceinline__ T wave_half_sums(T v)
+{
+    v += dpp_get<kDppXor1>(v);
+    v += dpp_get<kDppXor2>(v);
+    v += dpp_get<kDppHalfMirror>(v);
+    v += dpp_get<kDppMirror>(v);
+    v += dpp_get<kDppBcast15>(v);
+    return v;
+}
+
 __device__ __forceinline__ double lane63_to_all(double v)
 {
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
@@ -339,7 +352,7 @@ __device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkIt
     return tile_geom(tm, it, tm.tile_rows);
 }
 
-// Tile of a folded matrix (work items of kind 5): rows and columns of the view with ceil(n/2)
+// Tile of a folded matrix (work items of kinds 5 and 6): rows and columns of the view with ceil(n/2)
 // rows of 2m columns.  `col` is the lane's first column in that view; rsel says which of the two
 // rows of the matrix it lies in (0: row 2v, 1: row 2v+1) -- a lane's 8 columns never straddle,
 // since m is a multiple of 256.  All 512 columns of the tile exist.

@@ -68,10 +68,12 @@ hipError_t launch_vectors(const DeviceTables& t, int32_t item_begin, int32_t ite
 // moment and chunk sums of u^2, then everything else).
 hipError_t launch_long_vectors(const DeviceTables& t, int32_t item_begin, int32_t item_end,
                                const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);
+// lds_rows (sweeps 1 and 2): rows of the matrix a tile can hold, which sizes the per-row buffers in
+// LDS: the plan's tile_rows, twice that when the list has folded matrices.
 // Sweep 1: row/column sums of g^2 of the matrix tiles [item_begin, item_end).  The whole-vector
 // items [vec_begin, vec_end) ride along in the same launch (their complete update, as
 // launch_vectors would do); pass an empty range for none.
-hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
+hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t lds_rows, int32_t item_begin,
                          int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
                          const FinalizeHyper& fh, hipStream_t s);
 // Finalize 1: r, c and the per-workgroup sums of r.
@@ -79,7 +81,7 @@ hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fi
                             const FinalizeHyper& h, hipStream_t s);
 // Sweep 2: row/column sums of u^2, u*M, M^2 and the per-tile sum of u^2 (Algorithm 1: the latter only).
 // reverse: take the tiles last to first (same results; see Plan::reverse_sweep2).
-hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t tile_rows,
+hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t lds_rows,
                          int32_t item_begin, int32_t item_end, bool reverse, hipStream_t s);
 // Finalize 2: kappa (Eq. 1), R, C and the per-workgroup sums of R.
 hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,

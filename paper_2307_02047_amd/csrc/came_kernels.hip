@@ -161,17 +161,77 @@ __device__ __forceinline__ int32_t xcd_item(int32_t b, int32_t n)
 #endif
 constexpr int kRows1 = CAME_ROWS1;
 
-// ALIGNED: rows start 16-byte aligned (m % 8 == 0).  FULL: the tile's 512 columns all exist.
-template <bool BF16, bool ALIGNED, bool FULL>
-__device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
-                            char* scratch, float* lds /* [4][512] */, float* rowbuf /* [tile_rows] */)
+// ALIGNED: rows start 16-byte aligned (m % 8 == 0).
+// SHAPE: kTileFull (the tile's 512 columns all exist), kTileRagged (the matrix ends inside the
+// tile), kTileFolded (tile of the ceil(n/2) x 2m view of a folded matrix, t from folded_geom).
+//
+// Folded tiles.  A matrix of width m = 512 k + 256 is swept as rows of 2m entries, row 2v of the
+// matrix followed by row 2v+1 (which is how they lie in memory), cut into 2k+1 column blocks of
+// 512: blocks 0..k-1 lie in row 2v, blocks k+1..2k in row 2v+1, and block k straddles (lanes
+// 0..31 the last 256 columns of row 2v, lanes 32..63 the first 256 of row 2v+1).  A lane always
+// holds 8 entries of one row and 8 consecutive columns of the matrix; its row and column sums go
+// where the finalize kernels expect them: column partials as if the two rows of a pair belonged
+// to two row blocks (2 rb and 2 rb + 1), row partials in slot (column block - k * [row is odd]),
+// which numbers the k+1 blocks that touch a row 0..k for even and odd rows alike.
+enum TileShape : int { kTileFull = 0, kTileRagged = 1, kTileFolded = 2 };
+
+// What a folded tile adds to the geometry (all trivial for the other shapes).
+struct FoldInfo {
+    int64_t pitch;   // elements from one row of the tile to the next: 2m (folded) or m
+    int64_t mrow0;   // first row of the matrix in the tile
+    int mrows;       // rows of the matrix in the tile
+    int64_t mcol;    // the lane's first column in the matrix
+    int k;           // index of the straddling column block
+    bool split;      // this tile is the straddling one
+};
+
+template <int SHAPE>
+__device__ __forceinline__ FoldInfo fold_info(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, int64_t lcol)
 {
+    FoldInfo f;
+    if constexpr (SHAPE == kTileFolded) {
+        f.pitch = 2 * tm.m;
+        f.mrow0 = 2 * t.row0;
+        const int64_t left = tm.n - f.mrow0;
+        f.mrows = static_cast<int>(left < 2 * t.nrows ? left : 2 * t.nrows);
+        f.mcol = lcol - t.rsel * tm.m;
+        f.k = static_cast<int>(tm.m / kTileCols);
+        f.split = it.cb == f.k;
+    } else {
+        f.pitch = tm.m; f.mrow0 = t.row0; f.mrows = t.nrows; f.mcol = lcol; f.k = 0; f.split = false;
+    }
+    return f;
+}
+
+// Element index of the lane's 8 entries in step j of its wave.  Folded, odd number of rows: the
+// lanes of the missing last row read the row before it (and their data is discarded).
+template <int SHAPE>
+__device__ __forceinline__ int64_t step_index(const TileGeom& t, const FoldInfo& f, int j, int64_t lcol)
+{
+    const int64_t off = SHAPE == kTileFolded ? (2 * (t.wave + kWaves * j) + 1 < f.mrows ? lcol : f.mcol) : lcol;
+    return (t.row0 + t.wave + kWaves * j) * f.pitch + off;
+}
+
+// The lane's row of the matrix in step j, counted from the tile's first.
+template <int SHAPE>
+__device__ __forceinline__ int step_row(const TileGeom& t, int j)
+{
+    return SHAPE == kTileFolded ? 2 * (t.wave + kWaves * j) + t.rsel : t.wave + kWaves * j;
+}
+
+template <bool BF16, bool ALIGNED, int SHAPE>
+__device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
+                            char* scratch, float* lds /* [4][512] */, float* rowbuf /* [rows of the matrix in a tile] */)
+{
+    constexpr bool FULL = SHAPE != kTileRagged;
+    constexpr bool FOLDED = SHAPE == kTileFolded;
     float* rowpart = reinterpret_cast<float*>(scratch + tm.off_rowpart);
     float* colpart = reinterpret_cast<float*>(scratch + tm.off_colpart);
     const int64_t m = tm.m;
     const bool lane_valid = t.ncol > 0;
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
+    const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
 
     float cacc[2][8];
 #pragma unroll
@@ -186,20 +246,27 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     // tensor's descriptor instead, which every workgroup keeps hot in L2.
     auto load_row = [&](int j, bool real = true) {
         return load_grad_raw<BF16, ALIGNED>(real ? g : static_cast<const void*>(&tm),
-                                            real ? (t.row0 + t.wave + kWaves * j) * m + lcol : int64_t(0), real ? lncol : kLaneCols);
+                                            real ? step_index<SHAPE>(t, f, j, lcol) : int64_t(0), real ? lncol : kLaneCols);
     };
     auto consume_row = [&](const GradRaw<BF16>& raw, int j, int slot) {
         float x[8];
         unpack<BF16>(raw, x);
+        const int i = step_row<SHAPE>(t, j);
+        const bool valid = FOLDED ? i < f.mrows : lane_valid;
         float racc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            if (ALIGNED && !FULL) x[e] = lane_valid ? x[e] : 0.f;
+            if (ALIGNED && SHAPE != kTileFull) x[e] = valid ? x[e] : 0.f;
             racc = fmaf(x[e], x[e], racc);
             cacc[slot][e] = fmaf(x[e], x[e], cacc[slot][e]);
         }
-        racc = wave_sum_lane63(racc);
-        if (t.lane == 63) rowbuf[t.wave + kWaves * j] = racc;
+        if (FOLDED && f.split) {  // two rows in this step: lanes 0..31 and lanes 32..63
+            racc = wave_half_sums(racc);
+            if ((t.lane & 31) == 31 && valid) rowbuf[i] = racc;
+        } else {
+            racc = wave_sum_lane63(racc);
+            if (t.lane == 63) rowbuf[i] = racc;
+        }
     };
 
     const WaveRows wr = wave_rows<kRows1>(t);
@@ -222,22 +289,35 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             if (k + 2 >= wr.nfull) break;
         }
     }
-    for (int j = wr.nfull * kRows1; j < wr.cnt; ++j) consume_row(load_row(j), j, j & 1);
+    for (int j = wr.nfull * kRows1; j < wr.cnt; ++j) consume_row(load_row(j), j, 0);
 
     // column sums of the tile: the two accumulator sets, then the 4 waves through LDS
 #pragma unroll
     for (int e = 0; e < 8; ++e) lds[t.wave * kTileCols + t.lane * kLaneCols + e] = cacc[0][e] + cacc[1][e];
     __syncthreads();
     for (int j = threadIdx.x; j < kTileCols; j += kWorkgroup) {
-        const int64_t cj = static_cast<int64_t>(it.cb) * kTileCols + j;
+        int64_t cj = static_cast<int64_t>(it.cb) * kTileCols + j;
+        int64_t prb = it.rb;
+        if constexpr (FOLDED) {  // the pair's second row counts as a row block of its own
+            const int second = cj >= m ? 1 : 0;
+            cj -= second * m;
+            prb = 2 * prb + second;
+        }
         if (cj < m) {
             const float v = (lds[j] + lds[kTileCols + j]) + (lds[2 * kTileCols + j] + lds[3 * kTileCols + j]);
-            colpart[static_cast<int64_t>(it.rb) * m + cj] = v;
+            colpart[prb * m + cj] = v;
         }
     }
     // row sums of the tile, coalesced: rowpart[column block][row]
-    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup)
-        rowpart[static_cast<int64_t>(it.cb) * tm.n + t.row0 + i] = rowbuf[i];
+    for (int i = threadIdx.x; i < f.mrows; i += kWorkgroup) {
+        if constexpr (FOLDED) {
+            const int odd = i & 1;  // (the tile's first row of the matrix is even)
+            if (odd ? it.cb >= f.k : it.cb <= f.k)
+                rowpart[static_cast<int64_t>(it.cb - odd * f.k) * tm.n + f.mrow0 + i] = rowbuf[i];
+        } else {
+            rowpart[static_cast<int64_t>(it.cb) * tm.n + f.mrow0 + i] = rowbuf[i];
+        }
+    }
 }
 
 // One __global__ entry per variant, each with the occupancy (waves per SIMD) its register
@@ -262,13 +342,16 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         }                                                                                           \
         const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, ntile)];                     \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
-        const TileGeom t = tile_geom(tm, it);                                                       \
+        const bool folded = ALIGNED && it.kind == 6;                                                \
+        const TileGeom t = folded ? folded_geom(tm, it, tm.tile_rows) : tile_geom(tm, it);          \
         const void* g = tb.grad[it.tensor];                    \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
-        if (!ALIGNED || full)                                                                       \
-            sweep1_tile<BF16, ALIGNED, true>(tm, it, t, g, tb.scratch, lds, rowbuf_f32);            \
+        if (folded)                                                                                 \
+            sweep1_tile<BF16, ALIGNED, ALIGNED ? kTileFolded : kTileFull>(tm, it, t, g, tb.scratch, lds, rowbuf_f32); \
+        else if (!ALIGNED || full)                                                                  \
+            sweep1_tile<BF16, ALIGNED, kTileFull>(tm, it, t, g, tb.scratch, lds, rowbuf_f32);       \
         else                                                                                        \
-            sweep1_tile<BF16, ALIGNED, false>(tm, it, t, g, tb.scratch, lds, rowbuf_f32);           \
+            sweep1_tile<BF16, ALIGNED, kTileRagged>(tm, it, t, g, tb.scratch, lds, rowbuf_f32);     \
     }
 CAME_SWEEP1_KERNEL(sweep1_bf16_kernel, true, true, CAME_WAVES1)
 CAME_SWEEP1_KERNEL(sweep1_f32_kernel, false, true, 4)
@@ -380,12 +463,16 @@ constexpr int kRows2 = CAME_ROWS2;
 // (no instability / confidence lines) needs only the total of u^2 for Eq. 1, so M is not
 // read at all and there are no column accumulators.
 // MB16: M is stored as bfloat16.
-template <bool BF16, bool ALIGNED, bool FULL, bool CAME_STATS, bool MB16>
+// SHAPE: TileShape, as in sweep 1.  TRL: rows of the matrix a tile can hold (tile_rows, twice that
+// when the list has folded matrices): the stride of the three row-sum arrays in LDS.
+template <bool BF16, bool ALIGNED, int SHAPE, bool CAME_STATS, bool MB16>
 __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
                             const float* state, char* scratch, TensorScalars* sc,
-                            double* lds /* [4][512] */, double* lds4, double* rowbuf /* [3][tile_rows] */,
-                            float* rowfac /* [tile_rows] */)
+                            double* lds /* [4][512] */, double* lds4, double* rowbuf /* [3][TRL] */,
+                            float* rowfac /* [TRL] */, int TRL)
 {
+    constexpr bool FULL = SHAPE != kTileRagged;
+    constexpr bool FOLDED = SHAPE == kTileFolded;
     const int64_t m = tm.m;
     const float* r = state + tm.off_r;
     const float* c = state + tm.off_c;
@@ -396,19 +483,22 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const bool lane_valid = t.ncol > 0;
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
-    const int TR = tm.tile_rows;
+    const int TR = TRL;
+    const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
 
     struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; };
     // real = false: the pipelined loop's last, unused request; the streaming gradient load of it
     // goes to the tensor's descriptor (hot in L2) instead of fetching the last batch again
     auto load_row = [&](int j, bool real = true) {
         Row x;
-        const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
+        const int64_t idx = step_index<SHAPE>(t, f, j, lcol);
         x.g = load_grad_raw<BF16, ALIGNED>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
         if constexpr (CAME_STATS) x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         return x;
     };
-    constexpr int U = ALIGNED ? kRows2 : 1;  // element-wise loads: one row per batch (address registers)
+    // element-wise loads: one row per batch (address registers); folded tiles likewise (their
+    // per-lane row bookkeeping costs registers that this kernel does not have to spare)
+    constexpr int U = ALIGNED && !FOLDED ? kRows2 : 1;
     const WaveRows wr = wave_rows<U>(t);
     Row A[U], B[U];
     if (wr.nfull > 0) {
@@ -423,12 +513,12 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 
     // per-row factor rsqrt(r_i / 1^T r) of the tile's rows, once, into LDS: inside the row
     // loop it is then an LDS broadcast read and no global load has to be waited for there
-    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup) rowfac[i] = rsqrtf(r[t.row0 + i]) * sqrt_sum_r;
+    for (int i = threadIdx.x; i < f.mrows; i += kWorkgroup) rowfac[i] = rsqrtf(r[f.mrow0 + i]) * sqrt_sum_r;
 
     float b[8];  // rsqrt(c_j) of this lane's columns
     {
         float cv[8];
-        unpack(load_f32_raw<ALIGNED>(c, lcol, lncol), cv);
+        unpack(load_f32_raw<ALIGNED>(c, f.mcol, lncol), cv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) b[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
     }
@@ -439,10 +529,17 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     for (int e = 0; e < 8; ++e) cP[e] = cQ[e] = cW[e] = 0.0;
 
     auto consume_row = [&](const Row& row, int j) {
-        const int i = t.wave + kWaves * j;
-        const float a = rowfac[i];  // rsqrt(r_i / 1^T r)
+        const int i = step_row<SHAPE>(t, j);
+        // (folded, odd number of rows: the lanes of the missing last row hold a copy of the row
+        // before it; a zero factor and a zeroed momentum take it out of every sum)
+        const bool row_ok = !FOLDED || i < f.mrows;
+        const float a = FOLDED ? (row_ok ? rowfac[i] : 0.f) : rowfac[i];  // rsqrt(r_i / 1^T r)
         float x[8];
         unpack<BF16>(row.g, x);
+        if constexpr (FOLDED) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = row_ok ? x[e] : 0.f;
+        }
         if constexpr (CAME_STATS) {
             float mo[8];
             unpack<MB16>(row.mo, mo);
@@ -450,14 +547,20 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 if (ALIGNED && !FULL) mo[e] = lane_valid ? mo[e] : 0.f;   // (b[e] = 0 already zeroes u)
+                if (FOLDED) mo[e] = row_ok ? mo[e] : 0.f;
                 const float uf = (x[e] * a) * b[e];  // u_ij = g_ij / sqrt(v_ij)
                 const double du = static_cast<double>(uf);
                 const double dm = static_cast<double>(mo[e]);
                 rP = fma(du, du, rP); rQ = fma(du, dm, rQ); rW = fma(dm, dm, rW);
                 cP[e] = fma(du, du, cP[e]); cQ[e] = fma(du, dm, cQ[e]); cW[e] = fma(dm, dm, cW[e]);
             }
-            rP = wave_sum_lane63(rP); rQ = wave_sum_lane63(rQ); rW = wave_sum_lane63(rW);
-            if (t.lane == 63) { rowbuf[i] = rP; rowbuf[TR + i] = rQ; rowbuf[2 * TR + i] = rW; }
+            if (FOLDED && f.split) {  // two rows in this step: lanes 0..31 and lanes 32..63
+                rP = wave_half_sums(rP); rQ = wave_half_sums(rQ); rW = wave_half_sums(rW);
+                if ((t.lane & 31) == 31 && row_ok) { rowbuf[i] = rP; rowbuf[TR + i] = rQ; rowbuf[2 * TR + i] = rW; }
+            } else {
+                rP = wave_sum_lane63(rP); rQ = wave_sum_lane63(rQ); rW = wave_sum_lane63(rW);
+                if (t.lane == 63) { rowbuf[i] = rP; rowbuf[TR + i] = rQ; rowbuf[2 * TR + i] = rW; }
+            }
         } else {
             double rP = 0.0;
 #pragma unroll
@@ -465,8 +568,13 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
                 const double du = static_cast<double>((x[e] * a) * b[e]);
                 rP = fma(du, du, rP);
             }
-            rP = wave_sum_lane63(rP);
-            if (t.lane == 63) rowbuf[i] = rP;
+            if (FOLDED && f.split) {
+                rP = wave_half_sums(rP);
+                if ((t.lane & 31) == 31 && row_ok) rowbuf[i] = rP;
+            } else {
+                rP = wave_sum_lane63(rP);
+                if (t.lane == 63) rowbuf[i] = rP;
+            }
         }
     };
 
@@ -497,10 +605,16 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             lds[t.wave * kTileCols + t.lane * kLaneCols + e] = q == 0 ? cP[e] : (q == 1 ? cQ[e] : cW[e]);
         __syncthreads();
         for (int j = threadIdx.x; j < kTileCols; j += kWorkgroup) {
-            const int64_t cj = static_cast<int64_t>(it.cb) * kTileCols + j;
+            int64_t cj = static_cast<int64_t>(it.cb) * kTileCols + j;
+            int64_t prb = it.rb;
+            if constexpr (FOLDED) {  // the pair's second row counts as a row block of its own
+                const int second = cj >= m ? 1 : 0;
+                cj -= second * m;
+                prb = 2 * prb + second;
+            }
             if (cj < m) {
                 const double v = (lds[j] + lds[kTileCols + j]) + (lds[2 * kTileCols + j] + lds[3 * kTileCols + j]);
-                colpart[(static_cast<int64_t>(it.rb) * 3 + q) * m + cj] = v;
+                colpart[(prb * 3 + q) * m + cj] = v;
             }
         }
         __syncthreads();
@@ -508,18 +622,24 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     // row sums of the tile, coalesced: rowpart[column block][statistic][row]; and the
     // tile's sum of u^2 (feeds RMS(u_t))
     double p = 0.0;
-    for (int i = threadIdx.x; i < t.nrows; i += kWorkgroup) {
+    for (int i = threadIdx.x; i < f.mrows; i += kWorkgroup) {
+        int slot = it.cb;
+        if constexpr (FOLDED) {
+            const int odd = i & 1;  // (the tile's first row of the matrix is even)
+            if (!(odd ? it.cb >= f.k : it.cb <= f.k)) continue;  // a row this tile has no entry of
+            slot = it.cb - odd * f.k;
+        }
         const double vP = rowbuf[i];
         p += vP;
         if constexpr (CAME_STATS) {
-            const int64_t base = static_cast<int64_t>(it.cb) * 3 * tm.n + t.row0 + i;
+            const int64_t base = static_cast<int64_t>(slot) * 3 * tm.n + f.mrow0 + i;
             rowpart[base] = vP;
             rowpart[base + tm.n] = rowbuf[TR + i];
             rowpart[base + 2 * tm.n] = rowbuf[2 * TR + i];
         }
     }
     p = block_sum(p, lds4);
-    if (threadIdx.x == 0) tileP[static_cast<int64_t>(it.rb) * tm.CB + it.cb] = p;
+    if (threadIdx.x == 0) tileP[static_cast<int64_t>(it.rb) * (FOLDED ? 2 * f.k + 1 : tm.CB) + it.cb] = p;
 }
 
 #ifndef CAME_WAVES2
@@ -527,7 +647,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #endif
 #define CAME_SWEEP2_KERNEL(NAME, BF16, ALIGNED, STATS, MB16, WAVES)                                             \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
-    void NAME(DeviceTables tb, int32_t item_begin, int32_t reverse)                                 \
+    void NAME(DeviceTables tb, int32_t item_begin, int32_t reverse, int32_t lds_rows)               \
     {                                                                                               \
         __shared__ double lds[kWaves * kTileCols];                                                  \
         __shared__ double lds4[4];                                                                  \
@@ -535,16 +655,20 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const int32_t ord = xcd_item(blockIdx.x, gridDim.x);                                        \
         const WorkItem it = tb.items[item_begin + (reverse ? static_cast<int32_t>(gridDim.x) - 1 - ord : ord)]; \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
-        const TileGeom t = tile_geom(tm, it);                                                       \
-        float* rowfac = reinterpret_cast<float*>(rowbuf_f64 + 3 * tm.tile_rows);                    \
+        const bool folded = ALIGNED && it.kind == 6;                                                \
+        const TileGeom t = folded ? folded_geom(tm, it, tm.tile_rows) : tile_geom(tm, it);          \
+        float* rowfac = reinterpret_cast<float*>(rowbuf_f64 + 3 * lds_rows);                        \
         const void* g = tb.grad[it.tensor];                    \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
-        if (!ALIGNED || full)                                                                       \
-            sweep2_tile<BF16, ALIGNED, true, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch,       \
-                                             tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
+        if (folded)                                                                                 \
+            sweep2_tile<BF16, ALIGNED, ALIGNED ? kTileFolded : kTileFull, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch, \
+                                             tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac, lds_rows); \
+        else if (!ALIGNED || full)                                                                  \
+            sweep2_tile<BF16, ALIGNED, kTileFull, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch,  \
+                                             tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac, lds_rows); \
         else                                                                                        \
-            sweep2_tile<BF16, ALIGNED, false, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch,      \
-                                              tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac); \
+            sweep2_tile<BF16, ALIGNED, kTileRagged, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch, \
+                                              tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac, lds_rows); \
     }
 CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, true, false, CAME_WAVES2)
 CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, true, false, 2)
@@ -653,18 +777,17 @@ constexpr int kRows3 = CAME_ROWS3;
 // with a decoupled weight decay theta_{t-1} is first scaled by h.decay = 1 - eta lambda.
 // COPY16: also write theta_t as bfloat16 to theta16 (came_step_bf16_copy).
 // MB16: M is stored as bfloat16; theta_t is formed from the unrounded M_t.
-// SHAPE: kSweep3Full (the tile's 512 columns exist), kSweep3Ragged (the matrix ends inside the
-// tile), kSweep3Folded (tile of the ceil(n/2) x 2m view of a folded matrix, t from folded_geom: a
+// SHAPE: kTileFull (the tile's 512 columns exist), kTileRagged (the matrix ends inside the
+// tile), kTileFolded (tile of the ceil(n/2) x 2m view of a folded matrix, t from folded_geom: a
 // step of the wave covers 512 consecutive entries of rows 2v, 2v+1 as they lie in memory, each
 // lane with the row and column factors of the entry it really holds).
-enum : int { kSweep3Full = 0, kSweep3Ragged = 1, kSweep3Folded = 2 };
 template <bool BF16, bool ALIGNED, int SHAPE, bool COPY16, bool MB16>
 __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
                             float* theta, void* theta16, float* state, const char* scratch,
                             const TensorScalars* sc, const SweepHyper& h, float* rowfac /* [2][2 tile_rows3] */)
 {
-    constexpr bool FULL = SHAPE != kSweep3Ragged;
-    constexpr bool FOLDED = SHAPE == kSweep3Folded;
+    constexpr bool FULL = SHAPE != kTileRagged;
+    constexpr bool FOLDED = SHAPE == kTileFolded;
     const int64_t m = tm.m;
     const int64_t pitch = FOLDED ? 2 * m : m;  // elements from one row of the tile to the next
     const int TR = 2 * tm.tile_rows3;           // room per factor array: a folded tile has two rows of the matrix per row
@@ -813,14 +936,14 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const void* g = tb.grad[it.tensor];                    \
         const TensorScalars* sc = tb.scalars + it.tensor;                                           \
         if (folded) {                                                                               \
-            if (theta16) sweep3_tile<BF16, ALIGNED, ALIGNED ? kSweep3Folded : kSweep3Full, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
-            else sweep3_tile<BF16, ALIGNED, ALIGNED ? kSweep3Folded : kSweep3Full, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            if (theta16) sweep3_tile<BF16, ALIGNED, ALIGNED ? kTileFolded : kTileFull, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, ALIGNED ? kTileFolded : kTileFull, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
         } else if (!ALIGNED || full) {                                                              \
-            if (theta16) sweep3_tile<BF16, ALIGNED, kSweep3Full, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
-            else sweep3_tile<BF16, ALIGNED, kSweep3Full, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            if (theta16) sweep3_tile<BF16, ALIGNED, kTileFull, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, kTileFull, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
         } else {                                                                                    \
-            if (theta16) sweep3_tile<BF16, ALIGNED, kSweep3Ragged, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
-            else sweep3_tile<BF16, ALIGNED, kSweep3Ragged, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            if (theta16) sweep3_tile<BF16, ALIGNED, kTileRagged, true, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
+            else sweep3_tile<BF16, ALIGNED, kTileRagged, false, MB16>(tm, it, t, g, theta, theta16, tb.state, tb.scratch, sc, h, rowfac_f32); \
         }                                                                                           \
     }
 CAME_SWEEP3_KERNEL(sweep3_bf16_kernel, true, true, false, CAME_WAVES3)
@@ -852,9 +975,9 @@ __global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTable
     const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];
     const TensorMeta& tm = tb.metas[it.tensor];
     if (!(tm.flags & kFlagAligned)) return;
-    const bool folded = it.kind == 5;
-    const TileGeom t = folded ? folded_geom(tm, it, tm.tile_rows3)
-                              : tile_geom(tm, it, it.kind == 4 ? tm.tile_rows3 : tm.tile_rows);
+    const bool folded = it.kind == 5 || it.kind == 6;
+    const int32_t tile_rows = it.kind == 4 || it.kind == 5 ? tm.tile_rows3 : tm.tile_rows;
+    const TileGeom t = folded ? folded_geom(tm, it, tile_rows) : tile_geom(tm, it, tile_rows);
     if (t.ncol == 0) return;
     const int64_t pitch = folded ? 2 * tm.m : tm.m;
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
@@ -951,14 +1074,14 @@ hipError_t launch_long_vectors(const DeviceTables& t, int32_t item_begin, int32_
     return hipGetLastError();
 }
 
-hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
+hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t lds_rows, int32_t item_begin,
                          int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
                          const FinalizeHyper& fh, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const int32_t nvec = vec_end > vec_begin ? vec_end - vec_begin : 0;
     const dim3 grid(nvec + (item_end - item_begin)), block(kWorkgroup);
-    const size_t dyn = sizeof(float) * static_cast<size_t>(tile_rows);  // row sums of one tile
+    const size_t dyn = sizeof(float) * static_cast<size_t>(lds_rows);  // row sums of one tile
     switch (variant & 3) {  // sweep 1 does not touch M
         case 0: sweep1_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
         case 1: sweep1_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
@@ -976,31 +1099,31 @@ hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fi
     return hipGetLastError();
 }
 
-hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t tile_rows,
+hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t lds_rows,
                          int32_t item_begin, int32_t item_end, bool reverse, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const dim3 grid(item_end - item_begin), block(kWorkgroup);
-    // three row statistics (double) and one row factor (float) per row of a tile
-    const size_t dyn = (sizeof(double) * 3 + sizeof(float)) * static_cast<size_t>(tile_rows);
+    // three row statistics (double) and one row factor (float) per row of the matrix in a tile
+    const size_t dyn = (sizeof(double) * 3 + sizeof(float)) * static_cast<size_t>(lds_rows);
     const int32_t rev = reverse ? 1 : 0;
     if (algo == CAME_ALGO_CAME) {
         switch (variant) {
-            case 0: sweep2_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 1: sweep2_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 2: sweep2_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 3: sweep2_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 4: sweep2_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 5: sweep2_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 6: sweep2_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            default: sweep2_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 0: sweep2_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 1: sweep2_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 2: sweep2_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 3: sweep2_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 4: sweep2_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 5: sweep2_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 6: sweep2_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            default: sweep2_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
         }
     } else {
         switch (variant & 3) {
-            case 0: sweep2_adafactor_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 1: sweep2_adafactor_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            case 2: sweep2_adafactor_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
-            default: sweep2_adafactor_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev); break;
+            case 0: sweep2_adafactor_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 1: sweep2_adafactor_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 2: sweep2_adafactor_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            default: sweep2_adafactor_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
         }
     }
     return hipGetLastError();

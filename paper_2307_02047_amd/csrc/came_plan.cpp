@@ -217,9 +217,19 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             if (tm.flags & kFlagVector) continue;
             tm.tile_rows = (tm.flags & kFlagResident) ? kResidentRows : p.tile_rows;
             tm.tile_rows3 = p.tile_rows3;
-            tm.RB = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows));
             tm.CB = static_cast<int32_t>(ceil_div(tm.m, kTileCols));
-            tm.ntiles = tm.RB * tm.CB;
+            if (tm.flags & kFlagFolded) {
+                // the view has ceil(n/2) rows of 2m columns.  The finalize kernels see every row
+                // block of it as two (the pairs' first rows, the pairs' second rows) and as many
+                // column blocks per row as the matrix really has.
+                const int32_t RBv = static_cast<int32_t>(ceil_div(ceil_div(tm.n, 2), tm.tile_rows));
+                tm.RB = 2 * RBv;
+                tm.ntiles = RBv * static_cast<int32_t>(2 * tm.m / kTileCols);
+                p.any_folded = true;
+            } else {
+                tm.RB = static_cast<int32_t>(ceil_div(tm.n, tm.tile_rows));
+                tm.ntiles = tm.RB * tm.CB;
+            }
             if (tm.flags & kFlagResident) {
                 // no finalize launch: the workgroups of the matrix reduce their own partial sums; the
                 // sums of r and of R are kept per row block
@@ -238,6 +248,12 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
             for (int32_t t = g.tensor_begin; t < g.tensor_end; ++t) {
                 const TensorMeta& tm = p.metas[t];
                 if ((tm.flags & (kFlagVector | kFlagResident)) || variant_of(tm.flags) != v) continue;
+                if (tm.flags & kFlagFolded) {
+                    const int32_t CBv = static_cast<int32_t>(2 * tm.m / kTileCols);
+                    for (int32_t rb = 0; rb < tm.RB / 2; ++rb)
+                        for (int32_t cb = 0; cb < CBv; ++cb) p.items.push_back(WorkItem{t, rb, cb, 6});
+                    continue;
+                }
                 for (int32_t rb = 0; rb < tm.RB; ++rb)
                     for (int32_t cb = 0; cb < tm.CB; ++cb) p.items.push_back(WorkItem{t, rb, cb, 0});
             }

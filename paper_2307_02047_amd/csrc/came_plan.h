@@ -51,7 +51,8 @@ enum TensorFlags : int32_t {
     kFlagBf16Momentum = 8,  // M stored as bfloat16 (off_M still counts floats from the blob's start)
     kFlagMomentumOnly = 16, // vector updated by -eta M (no instability / confidence statistics)
     kFlagResident = 32,     // matrix on the on-chip path (tile_rows = kResidentRows, no finalize items)
-    kFlagFolded = 64,       // the update sweep treats the matrix as ceil(n/2) rows of 2m columns (see WorkItem)
+    kFlagFolded = 64,       // the sweeps treat the matrix as ceil(n/2) rows of 2m columns (see WorkItem); RB then
+                            // counts 2 per row block of that view and ntiles its tiles
 };
 
 // Per-tensor descriptor in device memory (scratch blob).
@@ -98,7 +99,8 @@ struct WorkItem {
                      // 5 = the same for a folded matrix: a matrix whose width is an odd multiple of 256
                      //     (768 = 512 + 256 ...) is swept as ceil(n/2) rows of 2m columns -- row 2v followed
                      //     by row 2v+1, which is how they lie in memory -- so that every tile is 512 columns
-                     //     wide; rb and cb count blocks of that view
+                     //     wide; rb and cb count blocks of that view (row blocks of tile_rows3 rows of it),
+                     // 6 = tile of a folded matrix in sweeps 1 and 2 (row blocks of tile_rows rows of the view)
 };
 
 // Vectors up to this length are updated by one workgroup in one kernel.  Longer ones are cut
@@ -173,6 +175,7 @@ struct Plan {
     bool reverse_sweep2 = false;
     int64_t n_matrices = 0, n_vectors = 0, total_elements = 0;
     int64_t n_resident = 0, resident_elements = 0;  // matrices on the on-chip path
+    bool any_folded = false;                        // a tile of sweeps 1 and 2 may hold 2 tile_rows rows of a matrix
     int32_t resident_wait_us = 0;
     // state blob
     size_t state_bytes = 0;

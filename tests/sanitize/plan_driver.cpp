@@ -114,11 +114,19 @@ int main(int argc, char** argv)
             }
             continue;
         }
-        if (static_cast<long long>(tm.RB) * tm.tile_rows < tm.n || static_cast<long long>(tm.RB - 1) * tm.tile_rows >= tm.n)
-            return fail("row blocks", tm.RB, tm.n);
         if (static_cast<long long>(tm.CB) * kTileCols < tm.m || static_cast<long long>(tm.CB - 1) * kTileCols >= tm.m)
             return fail("column blocks", tm.CB, tm.m);
-        if (tm.ntiles != tm.RB * tm.CB) return fail("tile count", tm.ntiles, t);
+        if (tm.flags & kFlagFolded) {
+            // two "row blocks" (the pairs' first rows, the pairs' second rows) per row block of the ceil(n/2) x 2m view
+            const long long nv = (tm.n + 1) / 2;
+            if (tm.RB % 2 || static_cast<long long>(tm.RB / 2) * tm.tile_rows < nv || static_cast<long long>(tm.RB / 2 - 1) * tm.tile_rows >= nv)
+                return fail("row blocks of a folded matrix", tm.RB, tm.n);
+            if (tm.ntiles != tm.RB / 2 * (2 * tm.m / kTileCols)) return fail("tile count of a folded matrix", tm.ntiles, t);
+        } else {
+            if (static_cast<long long>(tm.RB) * tm.tile_rows < tm.n || static_cast<long long>(tm.RB - 1) * tm.tile_rows >= tm.n)
+                return fail("row blocks", tm.RB, tm.n);
+            if (tm.ntiles != tm.RB * tm.CB) return fail("tile count", tm.ntiles, t);
+        }
         if (tm.off_sync != static_cast<long long>(p.off_sync + sizeof(ResidentSync) * t)) return fail("counter slot", t, tm.off_sync);
         if (tm.flags & kFlagResident) {
             // all tiles of the matrix on the chip at once, aligned rows, Algorithm 2, no finalize items
@@ -144,8 +152,19 @@ int main(int argc, char** argv)
         for (int v = 0; v < kVariants; ++v)
             for (int32_t k = g.var_begin[v]; k < g.var_end[v]; ++k) {
                 const WorkItem& it = p.items[k];
-                if (it.tensor < g.tensor_begin || it.tensor >= g.tensor_end || it.kind != 0) return fail("tile item", k, it.tensor);
+                if (it.tensor < g.tensor_begin || it.tensor >= g.tensor_end || (it.kind != 0 && it.kind != 6)) return fail("tile item", k, it.tensor);
                 const TensorMeta& tm = p.metas[it.tensor];
+                if ((it.kind == 6) != ((tm.flags & kFlagFolded) != 0)) return fail("tile item kind", it.kind, tm.flags);
+                if (it.kind == 6) {
+                    // folded: ceil(n/2) rows of 2m columns; the finalize kernels count two row blocks per row block of that view
+                    const long long RBv = ((tm.n + 1) / 2 + tm.tile_rows - 1) / tm.tile_rows, CBv = 2 * tm.m / kTileCols;
+                    if (tm.RB != 2 * RBv || tm.ntiles != RBv * CBv || tm.CB != (tm.m + kTileCols - 1) / kTileCols)
+                        return fail("folded matrix blocks", tm.RB, tm.ntiles);
+                    if (variant_of(tm.flags) != v || it.rb < 0 || it.rb >= RBv || it.cb < 0 || it.cb >= CBv)
+                        return fail("folded tile item block", it.rb, it.cb);
+                    ++seen[it.tensor];
+                    continue;
+                }
                 if (variant_of(tm.flags) != v || it.rb < 0 || it.rb >= tm.RB || it.cb < 0 || it.cb >= tm.CB)
                     return fail("tile item block", it.rb, it.cb);
                 ++seen[it.tensor];
