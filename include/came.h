@@ -329,11 +329,11 @@ double came_algorithmic_bytes(int32_t grad_bytes, int32_t momentum_bytes, int32_
  * once -- above all the one sweep that both reads and writes (sweep 3: theta and M in
  * place) -- depends on WHERE the caller's buffers sit physically: when theta and the state
  * blob share one of the HBM's three 96 GB address regions the mixed read/write stream runs
- * at about 5.0-5.2 TB/s, when they sit in different regions at about 6.0 TB/s (pure reads
+ * at about 5.4 TB/s, when they sit in different regions at about 6.2 TB/s (pure reads
  * of one array and pure writes do not care; sweep 2's two read streams g and M gain 2.5-5 %).
  * Measured cost of not caring, state blob wherever a fresh allocator puts it (directly behind
- * the parameters and gradients): a whole step takes about 15 % longer on a
- * 6.7-billion-parameter list and 10-13 % longer on lists of 0.1-0.4 billion parameters.
+ * the parameters and gradients): a whole step takes about 10 % longer on a
+ * 6.7-billion-parameter list and 0-9 % longer on lists of 0.1-0.4 billion parameters.
  * The library owns no memory, so it can only measure: this call runs the memory traffic of
  * sweep 3 over every matrix (theta and M read and written back with their own bits; nothing
  * changes) and, when grad_dev is given, also reads g in that pass and first runs the traffic
