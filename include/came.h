@@ -354,8 +354,8 @@ int came_probe_placement(came_ctx *ctx, void *const *theta_dev, const void *cons
  * phase { sweep 1, finalize 1, sweep 2, finalize 2, sweep 3, vectors, on-chip kernel } since
  * the previous read into phase_ms[7] / phase_launches[7], and forgets them.
  * "vectors" counts only launches of their own (long 1-D parameters, groups
- * without a matrix); ordinary 1-D parameters are updated inside the sweep-1
- * launch and count there.
+ * without a matrix); ordinary 1-D parameters are updated by the first workgroups
+ * of the sweep-3 launch and count there.
  * At most 65536 launches are kept between reads; further ones go untimed.
  */
 int came_profile_enable(came_ctx *ctx, int32_t on);

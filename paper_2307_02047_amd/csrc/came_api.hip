@@ -477,7 +477,7 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
         }
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, lds_rows, g.var_begin[v], g.var_end[v], 0, 0, sh, fh, s); });
+            e = timed_launch(ctx, 0, s, [&] { return launch_sweep1(tb, v, lds_rows, g.var_begin[v], g.var_end[v], s); });
             if (e != hipSuccess) return failed(e);
         }
         e = timed_launch(ctx, 1, s, [&] { return launch_finalize1(tb, g.fin_begin, g.fin_end, fh, s); });

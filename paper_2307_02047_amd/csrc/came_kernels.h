@@ -70,12 +70,9 @@ hipError_t launch_long_vectors(const DeviceTables& t, int32_t item_begin, int32_
                                const SweepHyper& h, const FinalizeHyper& fh, hipStream_t s);
 // lds_rows (sweeps 1 and 2): rows of the matrix a tile can hold, which sizes the per-row buffers in
 // LDS: the plan's tile_rows, twice that when the list has folded matrices.
-// Sweep 1: row/column sums of g^2 of the matrix tiles [item_begin, item_end).  The whole-vector
-// items [vec_begin, vec_end) ride along in the same launch (their complete update, as
-// launch_vectors would do); pass an empty range for none.
+// Sweep 1: row/column sums of g^2 of the matrix tiles [item_begin, item_end).
 hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t lds_rows, int32_t item_begin,
-                         int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
-                         const FinalizeHyper& fh, hipStream_t s);
+                         int32_t item_end, hipStream_t s);
 // Finalize 1: r, c and the per-workgroup sums of r.
 hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);

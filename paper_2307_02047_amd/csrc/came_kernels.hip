@@ -3,15 +3,15 @@
 // One step is five grouped launches over ALL tensors of a group (the sweeps once per
 // kernel variant present: gradient dtype x aligned/unaligned rows x momentum dtype):
 //
-//   sweep 1    g            -> row/column partial sums of g^2          (r_t, c_t lines);
-//                              its last workgroups do the complete update of the 1-D
-//                              parameters, one workgroup each (a group without matrices
-//                              launches them alone; vectors too long for one workgroup
-//                              take two extra launches over chunks)
+//   sweep 1    g            -> row/column partial sums of g^2          (r_t, c_t lines)
 //   finalize 1 partials     -> r_t, c_t, sqrt(1^T r_t)
 //   sweep 2    g, M_{t-1}   -> row/column partial sums of u^2, u M, M^2 with u = g / sqrt(v_t)
 //   finalize 2 partials     -> kappa = 1/max(1, RMS(u_t)/d) (Eq. 1), R_t, C_t, sqrt(1^T R_t)
-//   sweep 3    g, M, theta  -> M_t, theta_t
+//   sweep 3    g, M, theta  -> M_t, theta_t;
+//                              its first workgroups do the complete update of the 1-D
+//                              parameters, one workgroup each (a group without matrices
+//                              launches them alone; vectors too long for one workgroup
+//                              take two extra launches over chunks)
 //
 // v_t = r c^T / (1^T r) and S_t = R C^T / (1^T R) are never materialised:
 //   1/sqrt(v_ij) = rsqrt(r_i) * sqrt(1^T r) * rsqrt(c_j)
@@ -26,7 +26,10 @@
 // The three sums cancel when u^ is close to M_{t-1}, so they are accumulated in
 // binary64 from exact products of binary32 values; finalize 2 combines them.
 //
-// Tile: 4 wave64s sweep `tile_rows` rows of a 512-column stripe; lane l owns
+// Tile: 4 wave64s sweep the rows of a 512-column stripe (sweeps 1 and 2: tile_rows of them, tall
+// tiles, because every tile costs them partial sums and a chain of dependent loads; sweep 3:
+// tile_rows3, short tiles of its own, because it forms no sums and short tiles keep what it reads
+// and writes at any one time close together); lane l owns
 // columns 8l..8l+7 (one 16-byte bf16 load, two 16-byte f32 loads), wave w rows
 // w, w+4, ...  Row sums: 8 in-lane adds, then a wave reduction.  Column sums:
 // per-lane accumulators down the tile, combined across the 4 waves in LDS and
@@ -325,22 +328,13 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #ifndef CAME_WAVES1
 #define CAME_WAVES1 5
 #endif
-// The last vec_count workgroups of a sweep-1 launch update whole 1-D parameters instead
-// (work items vec_begin...): that work is independent of the matrices and latency-bound,
-// so it hides behind the tiles instead of costing a launch of its own.
 #define CAME_SWEEP1_KERNEL(NAME, BF16, ALIGNED, WAVES)                                              \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
-    void NAME(DeviceTables tb, int32_t item_begin, int32_t vec_begin, int32_t vec_count,            \
-              SweepHyper h, FinalizeHyper fh)                                                       \
+    void NAME(DeviceTables tb, int32_t item_begin)                                                  \
     {                                                                                               \
         __shared__ __attribute__((aligned(16))) float lds[kWaves * kTileCols];                      \
         extern __shared__ float rowbuf_f32[];                                                       \
-        const int32_t ntile = static_cast<int32_t>(gridDim.x) - vec_count;                          \
-        if (static_cast<int32_t>(blockIdx.x) >= ntile) {                                            \
-            vector_item(tb, vec_begin + (blockIdx.x - ntile), h, fh, reinterpret_cast<double*>(lds)); \
-            return;                                                                                 \
-        }                                                                                           \
-        const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, ntile)];                     \
+        const WorkItem it = tb.items[item_begin + xcd_item(blockIdx.x, gridDim.x)];                 \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const bool folded = ALIGNED && it.kind == 6;                                                \
         const TileGeom t = folded ? folded_geom(tm, it, tm.tile_rows) : tile_geom(tm, it);          \
@@ -915,6 +909,10 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #ifndef CAME_WAVES3
 #define CAME_WAVES3 3
 #endif
+// The first vec_count workgroups of a sweep-3 launch update whole 1-D parameters instead (work
+// items vec_begin...): that work is independent of the matrices and latency-bound, so at the
+// front of the step's longest launch it is over long before the tiles are, instead of costing a
+// launch of its own.
 #define CAME_SWEEP3_KERNEL(NAME, BF16, ALIGNED, MB16, WAVES)                                              \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
     void NAME(DeviceTables tb, int32_t item_begin, int32_t vec_begin, int32_t vec_count,            \
@@ -1075,18 +1073,16 @@ hipError_t launch_long_vectors(const DeviceTables& t, int32_t item_begin, int32_
 }
 
 hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t lds_rows, int32_t item_begin,
-                         int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
-                         const FinalizeHyper& fh, hipStream_t s)
+                         int32_t item_end, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
-    const int32_t nvec = vec_end > vec_begin ? vec_end - vec_begin : 0;
-    const dim3 grid(nvec + (item_end - item_begin)), block(kWorkgroup);
+    const dim3 grid(item_end - item_begin), block(kWorkgroup);
     const size_t dyn = sizeof(float) * static_cast<size_t>(lds_rows);  // row sums of one tile
     switch (variant & 3) {  // sweep 1 does not touch M
-        case 0: sweep1_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
-        case 1: sweep1_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
-        case 2: sweep1_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
-        default: sweep1_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, nvec, h, fh); break;
+        case 0: sweep1_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        case 1: sweep1_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        case 2: sweep1_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
+        default: sweep1_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin); break;
     }
     return hipGetLastError();
 }

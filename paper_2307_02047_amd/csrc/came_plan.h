@@ -154,7 +154,7 @@ struct Group {
     // after matrix in list order: one launch per variant present
     int32_t res_begin[kVariants], res_end[kVariants];
     bool vectors_with_resident;  // no streaming matrix in the group: the whole-vector items ride in the
-                                 // first on-chip launch instead of the first sweep-1 launch
+                                 // first on-chip launch instead of the first sweep-3 launch
 };
 
 struct Plan {
