@@ -42,6 +42,17 @@
 #include "came_device.hpp"
 #include "came_kernels.h"
 
+// Whether the gradient loads of sweeps 1, 2, 3 are streaming (non-temporal) loads.
+#ifndef CAME_NT1
+#define CAME_NT1 true
+#endif
+#ifndef CAME_NT2
+#define CAME_NT2 true
+#endif
+#ifndef CAME_NT3
+#define CAME_NT3 true
+#endif
+
 namespace came {
 namespace {
 
@@ -248,7 +259,7 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     // (measured: 17 % more bytes fetched by sweep 1 at 80-row tiles); that request reads the
     // tensor's descriptor instead, which every workgroup keeps hot in L2.
     auto load_row = [&](int j, bool real = true) {
-        return load_grad_raw<BF16, ALIGNED>(real ? g : static_cast<const void*>(&tm),
+        return load_grad_raw<BF16, ALIGNED, CAME_NT1>(real ? g : static_cast<const void*>(&tm),
                                             real ? step_index<SHAPE>(t, f, j, lcol) : int64_t(0), real ? lncol : kLaneCols);
     };
     auto consume_row = [&](const GradRaw<BF16>& raw, int j, int slot) {
@@ -486,7 +497,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     auto load_row = [&](int j, bool real = true) {
         Row x;
         const int64_t idx = step_index<SHAPE>(t, f, j, lcol);
-        x.g = load_grad_raw<BF16, ALIGNED>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
+        x.g = load_grad_raw<BF16, ALIGNED, CAME_NT2>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
         if constexpr (CAME_STATS) x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         return x;
     };
@@ -806,7 +817,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         // (folded, odd number of rows: the lanes of the missing last row read the row before it)
         const int64_t off = FOLDED ? (2 * (t.wave + kWaves * j) + 1 < mrows ? lcol : mcol) : lcol;
         const int64_t idx = (t.row0 + t.wave + kWaves * j) * pitch + off;
-        x.g = load_grad_raw<BF16, ALIGNED>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
+        x.g = load_grad_raw<BF16, ALIGNED, CAME_NT3>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
         x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         x.th = load_f32_raw<ALIGNED>(theta, idx, lncol);
         return x;
