@@ -246,6 +246,9 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
     const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
+    // binary32 gradients, aligned rows, no overhanging lanes: split ownership (see load_pair)
+    constexpr bool SPLIT = ALIGNED && !BF16 && SHAPE != kTileRagged;
+    const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
 
     float cacc[2][8];
 #pragma unroll
@@ -259,12 +262,39 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     // (measured: 17 % more bytes fetched by sweep 1 at 80-row tiles); that request reads the
     // tensor's descriptor instead, which every workgroup keeps hot in L2.
     auto load_row = [&](int j, bool real = true) {
-        return load_grad_raw<BF16, ALIGNED, CAME_NT1>(real ? g : static_cast<const void*>(&tm),
-                                            real ? step_index<SHAPE>(t, f, j, lcol) : int64_t(0), real ? lncol : kLaneCols);
+        if constexpr (SPLIT) {
+            const SplitStep st = split_step<FOLDED>(t, sg, j, f.pitch, f.mrows, m);
+            return load_pair<BF16, CAME_NT1>(real ? g : static_cast<const void*>(&tm), real ? st.ia : int64_t(0), real ? st.ib : int64_t(4));
+        } else {
+            return load_grad_raw<BF16, ALIGNED, CAME_NT1>(real ? g : static_cast<const void*>(&tm),
+                                                real ? step_index<SHAPE>(t, f, j, lcol) : int64_t(0), real ? lncol : kLaneCols);
+        }
     };
     auto consume_row = [&](const GradRaw<BF16>& raw, int j, int slot) {
         float x[8];
         unpack<BF16>(raw, x);
+        if constexpr (SPLIT) {
+            const SplitStep st = split_step<FOLDED>(t, sg, j, f.pitch, f.mrows, m);
+            float ra = 0.f, rb = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (FOLDED) x[e] = (e < 4 ? st.oka : st.okb) ? x[e] : 0.f;
+                if (e < 4) ra = fmaf(x[e], x[e], ra); else rb = fmaf(x[e], x[e], rb);
+                cacc[slot][e] = fmaf(x[e], x[e], cacc[slot][e]);
+            }
+            if (FOLDED && f.split) {  // the two groups lie in the two rows of the pair
+                ra = wave_sum_lane63(ra);
+                rb = wave_sum_lane63(rb);
+                if (t.lane == 63) {
+                    rowbuf[st.rowa] = ra;
+                    if (st.okb) rowbuf[st.rowb] = rb;
+                }
+            } else {
+                ra = wave_sum_lane63(ra + rb);
+                if (t.lane == 63 && st.oka) rowbuf[st.rowa] = ra;
+            }
+            return;
+        }
         const int i = step_row<SHAPE>(t, j);
         const bool valid = FOLDED ? i < f.mrows : lane_valid;
         float racc = 0.f;
@@ -307,7 +337,8 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 
     // column sums of the tile: the two accumulator sets, then the 4 waves through LDS
 #pragma unroll
-    for (int e = 0; e < 8; ++e) lds[t.wave * kTileCols + t.lane * kLaneCols + e] = cacc[0][e] + cacc[1][e];
+    for (int e = 0; e < 8; ++e)
+        lds[t.wave * kTileCols + (SPLIT ? split_slot(t.lane, e) : t.lane * kLaneCols + e)] = cacc[0][e] + cacc[1][e];
     __syncthreads();
     for (int j = threadIdx.x; j < kTileCols; j += kWorkgroup) {
         int64_t cj = static_cast<int64_t>(it.cb) * kTileCols + j;
@@ -490,12 +521,21 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
     const int TR = TRL;
     const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
+    // binary32 gradients, aligned rows, no overhanging lanes: split ownership (see load_pair)
+    constexpr bool SPLIT = ALIGNED && !BF16 && SHAPE != kTileRagged;
+    const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
 
     struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; };
     // real = false: the pipelined loop's last, unused request; the streaming gradient load of it
     // goes to the tensor's descriptor (hot in L2) instead of fetching the last batch again
     auto load_row = [&](int j, bool real = true) {
         Row x;
+        if constexpr (SPLIT) {
+            const SplitStep st = split_step<FOLDED>(t, sg, j, f.pitch, f.mrows, m);
+            x.g = load_pair<BF16, CAME_NT2>(real ? g : static_cast<const void*>(&tm), real ? st.ia : int64_t(0), real ? st.ib : int64_t(4));
+            if constexpr (CAME_STATS) x.mo = load_pair<MB16, false>(M, st.ia, st.ib);
+            return x;
+        }
         const int64_t idx = step_index<SHAPE>(t, f, j, lcol);
         x.g = load_grad_raw<BF16, ALIGNED, CAME_NT2>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
         if constexpr (CAME_STATS) x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
@@ -523,9 +563,10 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     float b[8];  // rsqrt(c_j) of this lane's columns
     {
         float cv[8];
-        unpack(load_f32_raw<ALIGNED>(c, f.mcol, lncol), cv);
+        if constexpr (SPLIT) unpack(load_f32_pair(c, sg.ca, sg.cb), cv);
+        else unpack(load_f32_raw<ALIGNED>(c, f.mcol, lncol), cv);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) b[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
+        for (int e = 0; e < 8; ++e) b[e] = (SPLIT || e < t.ncol) ? rsqrtf(cv[e]) : 0.f;
     }
     __syncthreads();
 
@@ -534,6 +575,62 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     for (int e = 0; e < 8; ++e) cP[e] = cQ[e] = cW[e] = 0.0;
 
     auto consume_row = [&](const Row& row, int j) {
+        if constexpr (SPLIT) {
+            const SplitStep st = split_step<FOLDED>(t, sg, j, f.pitch, f.mrows, m);
+            // rsqrt(r_i / 1^T r) of the two groups' rows (one row unless the tile spans a pair's two rows)
+            const float aa = FOLDED ? (st.oka ? rowfac[st.rowa] : 0.f) : rowfac[st.rowa];
+            const float ab = FOLDED ? (st.okb ? rowfac[st.rowb] : 0.f) : aa;
+            float x[8];
+            unpack<BF16>(row.g, x);
+            double pa = 0.0, qa = 0.0, wa = 0.0, pb = 0.0, qb = 0.0, wb = 0.0;
+            if constexpr (CAME_STATS) {
+                float mo[8];
+                unpack<MB16>(row.mo, mo);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (FOLDED) {  // a missing row's lanes hold a copy of the row before it
+                        x[e] = (e < 4 ? st.oka : st.okb) ? x[e] : 0.f;
+                        mo[e] = (e < 4 ? st.oka : st.okb) ? mo[e] : 0.f;
+                    }
+                    const float uf = (x[e] * (e < 4 ? aa : ab)) * b[e];  // u_ij = g_ij / sqrt(v_ij)
+                    const double du = static_cast<double>(uf);
+                    const double dm = static_cast<double>(mo[e]);
+                    if (e < 4) { pa = fma(du, du, pa); qa = fma(du, dm, qa); wa = fma(dm, dm, wa); }
+                    else       { pb = fma(du, du, pb); qb = fma(du, dm, qb); wb = fma(dm, dm, wb); }
+                    cP[e] = fma(du, du, cP[e]); cQ[e] = fma(du, dm, cQ[e]); cW[e] = fma(dm, dm, cW[e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (FOLDED) x[e] = (e < 4 ? st.oka : st.okb) ? x[e] : 0.f;
+                    const double du = static_cast<double>((x[e] * (e < 4 ? aa : ab)) * b[e]);
+                    if (e < 4) pa = fma(du, du, pa); else pb = fma(du, du, pb);
+                }
+            }
+            if (FOLDED && f.split) {  // the two groups lie in the two rows of the pair
+                pa = wave_sum_lane63(pa); pb = wave_sum_lane63(pb);
+                if constexpr (CAME_STATS) {
+                    qa = wave_sum_lane63(qa); wa = wave_sum_lane63(wa);
+                    qb = wave_sum_lane63(qb); wb = wave_sum_lane63(wb);
+                }
+                if (t.lane == 63) {
+                    rowbuf[st.rowa] = pa;
+                    if (CAME_STATS) { rowbuf[TR + st.rowa] = qa; rowbuf[2 * TR + st.rowa] = wa; }
+                    if (st.okb) {
+                        rowbuf[st.rowb] = pb;
+                        if (CAME_STATS) { rowbuf[TR + st.rowb] = qb; rowbuf[2 * TR + st.rowb] = wb; }
+                    }
+                }
+            } else {
+                pa = wave_sum_lane63(pa + pb);
+                if constexpr (CAME_STATS) { qa = wave_sum_lane63(qa + qb); wa = wave_sum_lane63(wa + wb); }
+                if (t.lane == 63 && st.oka) {
+                    rowbuf[st.rowa] = pa;
+                    if (CAME_STATS) { rowbuf[TR + st.rowa] = qa; rowbuf[2 * TR + st.rowa] = wa; }
+                }
+            }
+            return;
+        }
         const int i = step_row<SHAPE>(t, j);
         // (folded, odd number of rows: the lanes of the missing last row hold a copy of the row
         // before it; a zero factor and a zeroed momentum take it out of every sum)
@@ -607,7 +704,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     for (int q = 0; q < (CAME_STATS ? 3 : 0); ++q) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            lds[t.wave * kTileCols + t.lane * kLaneCols + e] = q == 0 ? cP[e] : (q == 1 ? cQ[e] : cW[e]);
+            lds[t.wave * kTileCols + (SPLIT ? split_slot(t.lane, e) : t.lane * kLaneCols + e)] = q == 0 ? cP[e] : (q == 1 ? cQ[e] : cW[e]);
         __syncthreads();
         for (int j = threadIdx.x; j < kTileCols; j += kWorkgroup) {
             int64_t cj = static_cast<int64_t>(it.cb) * kTileCols + j;
@@ -808,12 +905,22 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int64_t mrow0 = FOLDED ? 2 * t.row0 : t.row0;
     const int mrows = FOLDED ? static_cast<int>(min(static_cast<int64_t>(2 * t.nrows), tm.n - mrow0)) : t.nrows;
     const int64_t mcol = FOLDED ? lcol - t.rsel * m : lcol;
+    // binary32 gradients, aligned rows, no overhanging lanes: split ownership (see load_pair)
+    constexpr bool SPLIT = ALIGNED && !BF16 && SHAPE != kTileRagged;
+    const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
 
     struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; F32Raw th; };
     // real = false: the pipelined loop's last, unused request; the streaming gradient load of it
     // goes to the tensor's descriptor (hot in L2) instead of fetching the last batch again
     auto load_row = [&](int j, bool real = true) {
         Row x;
+        if constexpr (SPLIT) {
+            const SplitStep st = split_step<FOLDED>(t, sg, j, pitch, mrows, m);
+            x.g = load_pair<BF16, CAME_NT3>(real ? g : static_cast<const void*>(&tm), real ? st.ia : int64_t(0), real ? st.ib : int64_t(4));
+            x.mo = load_pair<MB16, false>(M, st.ia, st.ib);
+            x.th = load_f32_pair(theta, st.ia, st.ib);
+            return x;
+        }
         // (folded, odd number of rows: the lanes of the missing last row read the row before it)
         const int64_t off = FOLDED ? (2 * (t.wave + kWaves * j) + 1 < mrows ? lcol : mcol) : lcol;
         const int64_t idx = (t.row0 + t.wave + kWaves * j) * pitch + off;
@@ -850,13 +957,15 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     float b[8], Bc[8];
     {
         float cv[8];
-        unpack(load_f32_raw<ALIGNED>(c, mcol, lncol), cv);
+        if constexpr (SPLIT) unpack(load_f32_pair(c, sg.ca, sg.cb), cv);
+        else unpack(load_f32_raw<ALIGNED>(c, mcol, lncol), cv);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) b[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
+        for (int e = 0; e < 8; ++e) b[e] = (SPLIT || e < t.ncol) ? rsqrtf(cv[e]) : 0.f;
         if (came) {
-            unpack(load_f32_raw<ALIGNED>(C, mcol, lncol), cv);
+            if constexpr (SPLIT) unpack(load_f32_pair(C, sg.ca, sg.cb), cv);
+            else unpack(load_f32_raw<ALIGNED>(C, mcol, lncol), cv);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) Bc[e] = e < t.ncol ? rsqrtf(cv[e]) : 0.f;
+            for (int e = 0; e < 8; ++e) Bc[e] = (SPLIT || e < t.ncol) ? rsqrtf(cv[e]) : 0.f;
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) Bc[e] = 1.f;
@@ -865,6 +974,31 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     __syncthreads();
 
     auto consume_row = [&](const Row& row, int j) {
+        if constexpr (SPLIT) {
+            const SplitStep st = split_step<FOLDED>(t, sg, j, pitch, mrows, m);
+            // the factors of the two groups' rows (a missing row's lanes compute on a copy and store nothing)
+            const int ra = st.oka ? st.rowa : st.rowa - 1, rb = st.okb ? st.rowb : st.rowb - 1;
+            const float aa = rowfac[ra], ab = rowfac[rb];
+            const float Aa = rowfac[TR + ra], Ab = rowfac[TR + rb];
+            float x[8], mo[8], th[8], mn[8], tn[8];
+            unpack<BF16>(row.g, x);
+            unpack<MB16>(row.mo, mo);
+            unpack(row.th, th);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float uh = (x[e] * (e < 4 ? aa : ab)) * b[e];
+                mn[e] = fmaf(h.beta1, mo[e], h.one_minus_beta1 * uh);
+                tn[e] = fmaf(th[e], h.decay, -((mn[e] * (e < 4 ? Aa : Ab)) * Bc[e]));
+            }
+            // (where the stores go: the same places the loads came from, unless the row is missing)
+            const int64_t base = (t.row0 + t.wave + kWaves * j) * pitch;
+            const int64_t ia = base + sg.va, ib = base + sg.vb;
+            if constexpr (MB16) store_bf16_pair(M, ia, ib, st.oka, st.okb, mn);
+            else store_f32_pair(M, ia, ib, st.oka, st.okb, mn);
+            store_f32_pair(theta, ia, ib, st.oka, st.okb, tn);
+            if constexpr (COPY16) store_bf16_pair(theta16, ia, ib, st.oka, st.okb, tn);
+            return;
+        }
         // i: the lane's row of the matrix, counted from the tile's first
         const int i = FOLDED ? 2 * (t.wave + kWaves * j) + t.rsel : t.wave + kWaves * j;
         const bool row_ok = !FOLDED || i < mrows;
