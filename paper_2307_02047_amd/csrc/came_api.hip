@@ -30,6 +30,7 @@ struct came_ctx {
     std::vector<const void*> cached;  // theta[count], grad[count], bf16 copy[count] of the current slot
     int last_hip = 0;
     int64_t last_step = 0;
+    int64_t steps_enqueued = 0;
     // phase timer
     bool profiling = false;
     struct Timed { hipEvent_t start, stop; int phase; };
@@ -418,9 +419,13 @@ static int check_step_arguments(const Plan& p, void* const* theta_dev, const voi
 
 // The launch sequence of one step over the plan's groups, on tables that are already in device
 // memory.  ctx (may be null) only serves the phase timer and the record of a failed HIP call.
+// odd_step: whether this is an odd-numbered call on its context (lists small against the
+// on-package cache alternate the update sweep's direction, see Plan::keep_tail_cached).
 static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, const came_hyper* hyper,
-                        double lr, hipStream_t s, int* hip_error, const ResidentCtl* rctl = nullptr)
+                        double lr, hipStream_t s, int* hip_error, const ResidentCtl* rctl = nullptr,
+                        bool odd_step = false)
 {
+    const bool reverse3 = p.keep_tail_cached && odd_step;
     auto failed = [&](hipError_t e) {
         if (hip_error) *hip_error = static_cast<int>(e);
         return hip_fail(ctx, e);
@@ -484,7 +489,7 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
         if (e != hipSuccess) return failed(e);
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
-            e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, p.algo, lds_rows, g.var_begin[v], g.var_end[v], p.reverse_sweep2, s); });
+            e = timed_launch(ctx, 2, s, [&] { return launch_sweep2(tb, v, p.algo, lds_rows, g.var_begin[v], g.var_end[v], p.reverse_sweep2, p.keep_tail_cached, s); });
             if (e != hipSuccess) return failed(e);
         }
         e = timed_launch(ctx, 3, s, [&] { return launch_finalize2(tb, g.fin_begin, g.fin_end, fh, s); });
@@ -495,7 +500,7 @@ static int enqueue_step(came_ctx* ctx, const Plan& p, const DeviceTables& tb, co
         for (int v = 0; v < kVariants; ++v) {
             if (g.var_end[v] == g.var_begin[v]) continue;
             const int32_t vb = vectors_pending ? g.vec_begin : 0, ve = vectors_pending ? g.vec_end : 0;
-            e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, p.tile_rows3, g.var3_begin[v], g.var3_end[v], vb, ve, sh, fh, s); });
+            e = timed_launch(ctx, 4, s, [&] { return launch_sweep3(tb, v, p.tile_rows3, g.var3_begin[v], g.var3_end[v], vb, ve, reverse3, sh, fh, s); });
             if (e != hipSuccess) return failed(e);
             vectors_pending = false;
         }
@@ -515,7 +520,7 @@ static int step_impl(came_ctx* ctx, void* const* theta_dev, const void* const* g
     rc = upload_pointers(ctx, theta_dev, grad_dev, theta16_dev, s);
     if (rc != CAME_OK) return rc;
     const ResidentCtl rctl = resident_ctl(ctx->plan, ctx->scratch, ctx->fail_host);
-    rc = enqueue_step(ctx, ctx->plan, tables_for(ctx, ctx->slot), hyper, lr, s, nullptr, &rctl);
+    rc = enqueue_step(ctx, ctx->plan, tables_for(ctx, ctx->slot), hyper, lr, s, nullptr, &rctl, (ctx->steps_enqueued++ & 1) != 0);
     if (rc != CAME_OK) return rc;
     ctx->last_step = step;
     return CAME_OK;
@@ -588,7 +593,7 @@ int came_step_noalloc(const came_tensor_desc* descs, int32_t count, const came_o
         e = launch_fill_zero_bytes(sp + p.off_scalars, sizeof(TensorScalars) * p.descs.size(), s);
         if (e == hipSuccess && zero_state) e = launch_fill_zero(static_cast<float*>(state_dev), p.state_bytes / sizeof(float), s);
         if (e != hipSuccess) return failed(e);
-        return enqueue_step(nullptr, p, tables_in(p, sp, static_cast<float*>(state_dev), 0), hyper, lr, s, &noalloc_last_hip);
+        return enqueue_step(nullptr, p, tables_in(p, sp, static_cast<float*>(state_dev), 0), hyper, lr, s, &noalloc_last_hip, nullptr, (step & 1) != 0);
     });
 }
 

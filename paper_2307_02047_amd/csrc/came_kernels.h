@@ -77,16 +77,18 @@ hipError_t launch_sweep1(const DeviceTables& t, int variant, int32_t lds_rows, i
 hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);
 // Sweep 2: row/column sums of u^2, u*M, M^2 and the per-tile sum of u^2 (Algorithm 1: the latter only).
-// reverse: take the tiles last to first (same results; see Plan::reverse_sweep2).
+// reverse: take the tiles last to first (same results; see Plan::reverse_sweep2).  stream_m: load
+// the momentum with streaming loads as well (see Plan::keep_tail_cached).
 hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t lds_rows,
-                         int32_t item_begin, int32_t item_end, bool reverse, hipStream_t s);
+                         int32_t item_begin, int32_t item_end, bool reverse, bool stream_m, hipStream_t s);
 // Finalize 2: kappa (Eq. 1), R, C and the per-workgroup sums of R.
 hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fin_end,
                             const FinalizeHyper& h, hipStream_t s);
 // Sweep 3: momentum and parameter update.  The launch's first vec_end - vec_begin workgroups
-// update the whole-vector items [vec_begin, vec_end) (pass 0, 0 for none).
+// update the whole-vector items [vec_begin, vec_end) (pass 0, 0 for none).  reverse: take the
+// tiles last to first (same results).
 hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
-                         int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
+                         int32_t item_end, int32_t vec_begin, int32_t vec_end, bool reverse, const SweepHyper& h,
                          const FinalizeHyper& fh, hipStream_t s);
 
 // On-chip path (came_resident.hip): the complete Algorithm-2 step of the matrices whose tiles are

@@ -501,7 +501,9 @@ constexpr int kRows2 = CAME_ROWS2;
 // MB16: M is stored as bfloat16.
 // SHAPE: TileShape, as in sweep 1.  TRL: rows of the matrix a tile can hold (tile_rows, twice that
 // when the list has folded matrices): the stride of the three row-sum arrays in LDS.
-template <bool BF16, bool ALIGNED, int SHAPE, bool CAME_STATS, bool MB16>
+// NTM: the momentum loads are streaming loads too (lists that are small against the on-package
+// cache, see Plan::keep_tail_cached).
+template <bool BF16, bool ALIGNED, int SHAPE, bool CAME_STATS, bool MB16, bool NTM>
 __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, const void* g,
                             const float* state, char* scratch, TensorScalars* sc,
                             double* lds /* [4][512] */, double* lds4, double* rowbuf /* [3][TRL] */,
@@ -533,12 +535,12 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         if constexpr (SPLIT) {
             const SplitStep st = split_step<FOLDED>(t, sg, j, f.pitch, f.mrows, m);
             x.g = load_pair<BF16, CAME_NT2>(real ? g : static_cast<const void*>(&tm), real ? st.ia : int64_t(0), real ? st.ib : int64_t(4));
-            if constexpr (CAME_STATS) x.mo = load_pair<MB16, false>(M, st.ia, st.ib);
+            if constexpr (CAME_STATS) x.mo = load_pair<MB16, NTM>(M, st.ia, st.ib);
             return x;
         }
         const int64_t idx = step_index<SHAPE>(t, f, j, lcol);
         x.g = load_grad_raw<BF16, ALIGNED, CAME_NT2>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
-        if constexpr (CAME_STATS) x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
+        if constexpr (CAME_STATS) x.mo = load_grad_raw<MB16, ALIGNED, NTM>(M, idx, lncol);
         return x;
     };
     // element-wise loads: one row per batch (address registers); folded tiles likewise (their
@@ -747,7 +749,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #ifndef CAME_WAVES2
 #define CAME_WAVES2 3
 #endif
-#define CAME_SWEEP2_KERNEL(NAME, BF16, ALIGNED, STATS, MB16, WAVES)                                             \
+#define CAME_SWEEP2_KERNEL(NAME, BF16, ALIGNED, STATS, MB16, WAVES, NTM)                                             \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
     void NAME(DeviceTables tb, int32_t item_begin, int32_t reverse, int32_t lds_rows)               \
     {                                                                                               \
@@ -763,28 +765,32 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
         const void* g = tb.grad[it.tensor];                    \
         const bool full = static_cast<int64_t>(it.cb + 1) * kTileCols <= tm.m;                      \
         if (folded)                                                                                 \
-            sweep2_tile<BF16, ALIGNED, ALIGNED ? kTileFolded : kTileFull, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch, \
+            sweep2_tile<BF16, ALIGNED, ALIGNED ? kTileFolded : kTileFull, STATS, MB16, NTM>(tm, it, t, g, tb.state, tb.scratch, \
                                              tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac, lds_rows); \
         else if (!ALIGNED || full)                                                                  \
-            sweep2_tile<BF16, ALIGNED, kTileFull, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch,  \
+            sweep2_tile<BF16, ALIGNED, kTileFull, STATS, MB16, NTM>(tm, it, t, g, tb.state, tb.scratch,  \
                                              tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac, lds_rows); \
         else                                                                                        \
-            sweep2_tile<BF16, ALIGNED, kTileRagged, STATS, MB16>(tm, it, t, g, tb.state, tb.scratch, \
+            sweep2_tile<BF16, ALIGNED, kTileRagged, STATS, MB16, NTM>(tm, it, t, g, tb.state, tb.scratch, \
                                               tb.scalars + it.tensor, lds, lds4, rowbuf_f64, rowfac, lds_rows); \
     }
-CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, true, false, CAME_WAVES2)
-CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, true, false, 2)
-CAME_SWEEP2_KERNEL(sweep2_bf16_unaligned_kernel, true, false, true, false, 3)
-CAME_SWEEP2_KERNEL(sweep2_f32_unaligned_kernel, false, false, true, false, 3)
-CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_kernel, true, true, true, true, CAME_WAVES2)
-CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_kernel, false, true, true, true, 2)
-CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_unaligned_kernel, true, false, true, true, 3)
-CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_unaligned_kernel, false, false, true, true, 3)
+CAME_SWEEP2_KERNEL(sweep2_bf16_kernel, true, true, true, false, CAME_WAVES2, false)
+CAME_SWEEP2_KERNEL(sweep2_f32_kernel, false, true, true, false, 2, false)
+CAME_SWEEP2_KERNEL(sweep2_bf16_unaligned_kernel, true, false, true, false, 3, false)
+CAME_SWEEP2_KERNEL(sweep2_f32_unaligned_kernel, false, false, true, false, 3, false)
+CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_kernel, true, true, true, true, CAME_WAVES2, false)
+CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_kernel, false, true, true, true, 2, false)
+CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_unaligned_kernel, true, false, true, true, 3, false)
+CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_unaligned_kernel, false, false, true, true, 3, false)
+CAME_SWEEP2_KERNEL(sweep2_bf16_ntm_kernel, true, true, true, false, CAME_WAVES2, true)
+CAME_SWEEP2_KERNEL(sweep2_f32_ntm_kernel, false, true, true, false, 2, true)
+CAME_SWEEP2_KERNEL(sweep2_bf16_mbf16_ntm_kernel, true, true, true, true, CAME_WAVES2, true)
+CAME_SWEEP2_KERNEL(sweep2_f32_mbf16_ntm_kernel, false, true, true, true, 2, true)
 // Algorithm 1: M is not read, so its storage type does not matter here
-CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_kernel, true, true, false, false, 8)
-CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_kernel, false, true, false, false, 8)
-CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_unaligned_kernel, true, false, false, false, 4)
-CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_unaligned_kernel, false, false, false, false, 4)
+CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_kernel, true, true, false, false, 8, false)
+CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_kernel, false, true, false, false, 8, false)
+CAME_SWEEP2_KERNEL(sweep2_adafactor_bf16_unaligned_kernel, true, false, false, false, 4, false)
+CAME_SWEEP2_KERNEL(sweep2_adafactor_f32_unaligned_kernel, false, false, false, false, 4, false)
 
 // ---------------------------------------------------------------- finalize 2
 
@@ -1061,7 +1067,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #define CAME_SWEEP3_KERNEL(NAME, BF16, ALIGNED, MB16, WAVES)                                              \
     __global__ __launch_bounds__(kWorkgroup) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))     \
     void NAME(DeviceTables tb, int32_t item_begin, int32_t vec_begin, int32_t vec_count,            \
-              SweepHyper h, FinalizeHyper fh)                                                       \
+              int32_t reverse, SweepHyper h, FinalizeHyper fh)                                      \
     {                                                                                               \
         extern __shared__ __attribute__((aligned(16))) float rowfac_f32[];                          \
         if (static_cast<int32_t>(blockIdx.x) < vec_count) {                                         \
@@ -1069,7 +1075,8 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             return;                                                                                 \
         }                                                                                           \
         const int32_t ntile = static_cast<int32_t>(gridDim.x) - vec_count;                          \
-        const WorkItem it = tb.items[item_begin + xcd_item(static_cast<int32_t>(blockIdx.x) - vec_count, ntile)]; \
+        const int32_t ord = xcd_item(static_cast<int32_t>(blockIdx.x) - vec_count, ntile);          \
+        const WorkItem it = tb.items[item_begin + (reverse ? ntile - 1 - ord : ord)];               \
         const TensorMeta& tm = tb.metas[it.tensor];                                                 \
         const bool folded = ALIGNED && it.kind == 5;                                                \
         const TileGeom t = folded ? folded_geom(tm, it, tm.tile_rows3) : tile_geom(tm, it, tm.tile_rows3); \
@@ -1241,14 +1248,21 @@ hipError_t launch_finalize1(const DeviceTables& t, int32_t fin_begin, int32_t fi
 }
 
 hipError_t launch_sweep2(const DeviceTables& t, int variant, int32_t algo, int32_t lds_rows,
-                         int32_t item_begin, int32_t item_end, bool reverse, hipStream_t s)
+                         int32_t item_begin, int32_t item_end, bool reverse, bool stream_m, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const dim3 grid(item_end - item_begin), block(kWorkgroup);
     // three row statistics (double) and one row factor (float) per row of the matrix in a tile
     const size_t dyn = (sizeof(double) * 3 + sizeof(float)) * static_cast<size_t>(lds_rows);
     const int32_t rev = reverse ? 1 : 0;
-    if (algo == CAME_ALGO_CAME) {
+    if (algo == CAME_ALGO_CAME && stream_m && !(variant & 2)) {
+        switch (variant) {
+            case 0: sweep2_bf16_ntm_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 1: sweep2_f32_ntm_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            case 4: sweep2_bf16_mbf16_ntm_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+            default: sweep2_f32_mbf16_ntm_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
+        }
+    } else if (algo == CAME_ALGO_CAME) {
         switch (variant) {
             case 0: sweep2_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
             case 1: sweep2_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, rev, lds_rows); break;
@@ -1279,24 +1293,25 @@ hipError_t launch_finalize2(const DeviceTables& t, int32_t fin_begin, int32_t fi
 }
 
 hipError_t launch_sweep3(const DeviceTables& t, int variant, int32_t tile_rows, int32_t item_begin,
-                         int32_t item_end, int32_t vec_begin, int32_t vec_end, const SweepHyper& h,
+                         int32_t item_end, int32_t vec_begin, int32_t vec_end, bool reverse, const SweepHyper& h,
                          const FinalizeHyper& fh, hipStream_t s)
 {
     if (item_end <= item_begin) return hipSuccess;
     const int32_t vec_count = vec_end - vec_begin;
+    const int32_t rev = reverse ? 1 : 0;
     const dim3 grid(item_end - item_begin + vec_count), block(kWorkgroup);
     // two factors per row of the matrix in a tile (a folded tile holds two of them per row of
     // its own); a whole-vector item needs 4 doubles
     const size_t dyn = std::max(sizeof(float) * 4 * static_cast<size_t>(tile_rows), sizeof(double) * 4);
     switch (variant) {
-        case 0: sweep3_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
-        case 1: sweep3_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
-        case 2: sweep3_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
-        case 3: sweep3_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
-        case 4: sweep3_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
-        case 5: sweep3_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
-        case 6: sweep3_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
-        default: sweep3_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, h, fh); break;
+        case 0: sweep3_bf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
+        case 1: sweep3_f32_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
+        case 2: sweep3_bf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
+        case 3: sweep3_f32_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
+        case 4: sweep3_bf16_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
+        case 5: sweep3_f32_mbf16_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
+        case 6: sweep3_bf16_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
+        default: sweep3_f32_mbf16_unaligned_kernel<<<grid, block, dyn, s>>>(t, item_begin, vec_begin, vec_count, rev, h, fh); break;
     }
     return hipGetLastError();
 }

@@ -188,6 +188,7 @@ int build_plan(const came_tensor_desc* descs, int32_t count, const came_options*
     }
     p.state_bytes = static_cast<size_t>(off) * sizeof(float);
     p.reverse_sweep2 = true;
+    p.keep_tail_cached = p.total_elements <= (int64_t(1) << 29);
 
     // ---- groups of consecutive tensors
     {

@@ -173,6 +173,16 @@ struct Plan {
     // sweep 2 10 % faster on a 109M-parameter list, 3 % on 350M-parameter lists, no difference
     // at 6.7B).
     bool reverse_sweep2 = false;
+    // Lists of which the 256 MB on-package cache holds a noticeable part (up to 2^29 parameters:
+    // at least 6 % of theta and M).  The update sweep leaves the last 256 MB it wrote dirty in that
+    // cache.  Normally sweep 2's momentum loads push them out (and sweep 2 waits for their
+    // write-back); on such a list sweep 2 loads the momentum with streaming loads, which leave
+    // them where they are, and the update sweep walks its tiles in the opposite direction from
+    // step to step, so that it begins where it ended last time: on entries that are still in
+    // the cache and are then overwritten there instead of having been written back in between.
+    // Measured: -4 % per step at 1.1e8 parameters, -1 % at 3.5e8; at 6.7e9 the streaming momentum
+    // loads alone cost sweep 2 9 %, hence the limit.  Same results either way.
+    bool keep_tail_cached = false;
     int64_t n_matrices = 0, n_vectors = 0, total_elements = 0;
     int64_t n_resident = 0, resident_elements = 0;  // matrices on the on-chip path
     bool any_folded = false;                        // a tile of sweeps 1 and 2 may hold 2 tile_rows rows of a matrix
