@@ -246,8 +246,8 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
     const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
-    // binary32 gradients, aligned rows, no overhanging lanes: split ownership (see load_pair)
-    constexpr bool SPLIT = ALIGNED && !BF16 && SHAPE != kTileRagged;
+    // aligned rows, no overhanging lanes: split ownership (see load_pair)
+    constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged;
     const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
 
     float cacc[2][8];
@@ -523,8 +523,8 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
     const int TR = TRL;
     const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
-    // binary32 gradients, aligned rows, no overhanging lanes: split ownership (see load_pair)
-    constexpr bool SPLIT = ALIGNED && !BF16 && SHAPE != kTileRagged;
+    // aligned rows, no overhanging lanes: split ownership (see load_pair)
+    constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged;
     const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
 
     struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; };
@@ -911,8 +911,8 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int64_t mrow0 = FOLDED ? 2 * t.row0 : t.row0;
     const int mrows = FOLDED ? static_cast<int>(min(static_cast<int64_t>(2 * t.nrows), tm.n - mrow0)) : t.nrows;
     const int64_t mcol = FOLDED ? lcol - t.rsel * m : lcol;
-    // binary32 gradients, aligned rows, no overhanging lanes: split ownership (see load_pair)
-    constexpr bool SPLIT = ALIGNED && !BF16 && SHAPE != kTileRagged;
+    // aligned rows, no overhanging lanes: split ownership (see load_pair)
+    constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged;
     const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
 
     struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; F32Raw th; };
