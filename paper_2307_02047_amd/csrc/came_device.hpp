@@ -343,19 +343,6 @@ __device__ __forceinline__ T wave_sum_lane63(T v)
     return v;
 }
 
-// Sums over the two halves of a wave: the total of lanes 0..31 is valid in lanes 16..31, that of
-// lanes 32..63 in lanes 48..63 (the butterflies and the first row broadcast of wave_sum_lane63).
-template <class T>
-__device__ __forceinline__ T wave_half_sums(T v)
-{
-    v += dpp_get<kDppXor1>(v);
-    v += dpp_get<kDppXor2>(v);
-    v += dpp_get<kDppHalfMirror>(v);
-    v += dpp_get<kDppMirror>(v);
-    v += dpp_get<kDppBcast15>(v);
-    return v;
-}
-
 __device__ __forceinline__ double lane63_to_all(double v)
 {
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
@@ -392,7 +379,6 @@ struct TileGeom {
     int nrows;
     int64_t col;  // first column of this lane
     int ncol;     // valid columns of this lane: 0..8
-    int rsel;     // folded tiles: which row of the pair this lane's columns lie in (0 otherwise)
 };
 
 // `tile_rows`: the height of the row blocks that it.rb counts (TensorMeta.tile_rows for the items
@@ -408,7 +394,6 @@ __device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkIt
     t.col = static_cast<int64_t>(it.cb) * kTileCols + t.lane * kLaneCols;
     const int64_t cleft = tm.m - t.col;
     t.ncol = cleft >= kLaneCols ? kLaneCols : (cleft > 0 ? static_cast<int>(cleft) : 0);
-    t.rsel = 0;
     return t;
 }
 
@@ -417,10 +402,9 @@ __device__ __forceinline__ TileGeom tile_geom(const TensorMeta& tm, const WorkIt
     return tile_geom(tm, it, tm.tile_rows);
 }
 
-// Tile of a folded matrix (work items of kinds 5 and 6): rows and columns of the view with ceil(n/2)
-// rows of 2m columns.  `col` is the lane's first column in that view; rsel says which of the two
-// rows of the matrix it lies in (0: row 2v, 1: row 2v+1) -- a lane's 8 columns never straddle,
-// since m is a multiple of 256.  All 512 columns of the tile exist.
+// Tile of a folded matrix (work items of kinds 5 and 6): row0 and nrows count rows of the view with
+// ceil(n/2) rows of 2m columns.  All 512 columns of the tile exist; which columns of the matrix a
+// lane holds is split_geom's business.
 __device__ __forceinline__ TileGeom folded_geom(const TensorMeta& tm, const WorkItem& it, int32_t tile_rows)
 {
     TileGeom t;
@@ -431,7 +415,6 @@ __device__ __forceinline__ TileGeom folded_geom(const TensorMeta& tm, const Work
     t.nrows = static_cast<int>(left < tile_rows ? left : tile_rows);
     t.col = static_cast<int64_t>(it.cb) * kTileCols + t.lane * kLaneCols;
     t.ncol = kLaneCols;
-    t.rsel = t.col >= tm.m ? 1 : 0;
     return t;
 }
 

@@ -181,12 +181,15 @@ constexpr int kRows1 = CAME_ROWS1;
 //
 // Folded tiles.  A matrix of width m = 512 k + 256 is swept as rows of 2m entries, row 2v of the
 // matrix followed by row 2v+1 (which is how they lie in memory), cut into 2k+1 column blocks of
-// 512: blocks 0..k-1 lie in row 2v, blocks k+1..2k in row 2v+1, and block k straddles (lanes
-// 0..31 the last 256 columns of row 2v, lanes 32..63 the first 256 of row 2v+1).  A lane always
-// holds 8 entries of one row and 8 consecutive columns of the matrix; its row and column sums go
-// where the finalize kernels expect them: column partials as if the two rows of a pair belonged
-// to two row blocks (2 rb and 2 rb + 1), row partials in slot (column block - k * [row is odd]),
-// which numbers the k+1 blocks that touch a row 0..k for even and odd rows alike.
+// 512: blocks 0..k-1 lie in row 2v, blocks k+1..2k in row 2v+1, and block k straddles (its first
+// 256 columns are the last 256 of row 2v, its last 256 the first 256 of row 2v+1).  Folded tiles
+// have 16-byte aligned rows and no overhanging lanes, so they always run with split ownership
+// (see load_pair): a lane's first group of 4 columns lies in the tile's first half, its second
+// group in the second half, and in the straddling block therefore in the pair's first and second
+// row -- for every lane alike.  The sums go where the finalize kernels expect them: column
+// partials as if the two rows of a pair belonged to two row blocks (2 rb and 2 rb + 1), row
+// partials in slot (column block - k * [row is odd]), which numbers the k+1 blocks that touch a
+// row 0..k for even and odd rows alike.
 enum TileShape : int { kTileFull = 0, kTileRagged = 1, kTileFolded = 2 };
 
 // What a folded tile adds to the geometry (all trivial for the other shapes).
@@ -194,13 +197,12 @@ struct FoldInfo {
     int64_t pitch;   // elements from one row of the tile to the next: 2m (folded) or m
     int64_t mrow0;   // first row of the matrix in the tile
     int mrows;       // rows of the matrix in the tile
-    int64_t mcol;    // the lane's first column in the matrix
     int k;           // index of the straddling column block
     bool split;      // this tile is the straddling one
 };
 
 template <int SHAPE>
-__device__ __forceinline__ FoldInfo fold_info(const TensorMeta& tm, const WorkItem& it, const TileGeom& t, int64_t lcol)
+__device__ __forceinline__ FoldInfo fold_info(const TensorMeta& tm, const WorkItem& it, const TileGeom& t)
 {
     FoldInfo f;
     if constexpr (SHAPE == kTileFolded) {
@@ -208,29 +210,12 @@ __device__ __forceinline__ FoldInfo fold_info(const TensorMeta& tm, const WorkIt
         f.mrow0 = 2 * t.row0;
         const int64_t left = tm.n - f.mrow0;
         f.mrows = static_cast<int>(left < 2 * t.nrows ? left : 2 * t.nrows);
-        f.mcol = lcol - t.rsel * tm.m;
         f.k = static_cast<int>(tm.m / kTileCols);
         f.split = it.cb == f.k;
     } else {
-        f.pitch = tm.m; f.mrow0 = t.row0; f.mrows = t.nrows; f.mcol = lcol; f.k = 0; f.split = false;
+        f.pitch = tm.m; f.mrow0 = t.row0; f.mrows = t.nrows; f.k = 0; f.split = false;
     }
     return f;
-}
-
-// Element index of the lane's 8 entries in step j of its wave.  Folded, odd number of rows: the
-// lanes of the missing last row read the row before it (and their data is discarded).
-template <int SHAPE>
-__device__ __forceinline__ int64_t step_index(const TileGeom& t, const FoldInfo& f, int j, int64_t lcol)
-{
-    const int64_t off = SHAPE == kTileFolded ? (2 * (t.wave + kWaves * j) + 1 < f.mrows ? lcol : f.mcol) : lcol;
-    return (t.row0 + t.wave + kWaves * j) * f.pitch + off;
-}
-
-// The lane's row of the matrix in step j, counted from the tile's first.
-template <int SHAPE>
-__device__ __forceinline__ int step_row(const TileGeom& t, int j)
-{
-    return SHAPE == kTileFolded ? 2 * (t.wave + kWaves * j) + t.rsel : t.wave + kWaves * j;
 }
 
 template <bool BF16, bool ALIGNED, int SHAPE>
@@ -245,7 +230,7 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const bool lane_valid = t.ncol > 0;
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
-    const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
+    const FoldInfo f = fold_info<SHAPE>(tm, it, t);
     // aligned rows, no overhanging lanes: split ownership (see load_pair)
     constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged;
     const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
@@ -267,7 +252,7 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             return load_pair<BF16, CAME_NT1>(real ? g : static_cast<const void*>(&tm), real ? st.ia : int64_t(0), real ? st.ib : int64_t(4));
         } else {
             return load_grad_raw<BF16, ALIGNED, CAME_NT1>(real ? g : static_cast<const void*>(&tm),
-                                                real ? step_index<SHAPE>(t, f, j, lcol) : int64_t(0), real ? lncol : kLaneCols);
+                                                real ? (t.row0 + t.wave + kWaves * j) * m + lcol : int64_t(0), real ? lncol : kLaneCols);
         }
     };
     auto consume_row = [&](const GradRaw<BF16>& raw, int j, int slot) {
@@ -295,22 +280,15 @@ __device__ void sweep1_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             }
             return;
         }
-        const int i = step_row<SHAPE>(t, j);
-        const bool valid = FOLDED ? i < f.mrows : lane_valid;
         float racc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            if (ALIGNED && SHAPE != kTileFull) x[e] = valid ? x[e] : 0.f;
+            if (ALIGNED && !FULL) x[e] = lane_valid ? x[e] : 0.f;
             racc = fmaf(x[e], x[e], racc);
             cacc[slot][e] = fmaf(x[e], x[e], cacc[slot][e]);
         }
-        if (FOLDED && f.split) {  // two rows in this step: lanes 0..31 and lanes 32..63
-            racc = wave_half_sums(racc);
-            if ((t.lane & 31) == 31 && valid) rowbuf[i] = racc;
-        } else {
-            racc = wave_sum_lane63(racc);
-            if (t.lane == 63) rowbuf[i] = racc;
-        }
+        racc = wave_sum_lane63(racc);
+        if (t.lane == 63) rowbuf[t.wave + kWaves * j] = racc;
     };
 
     const WaveRows wr = wave_rows<kRows1>(t);
@@ -522,7 +500,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int64_t lcol = ALIGNED ? load_col<FULL>(t, it.cb) : t.col;
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
     const int TR = TRL;
-    const FoldInfo f = fold_info<SHAPE>(tm, it, t, lcol);
+    const FoldInfo f = fold_info<SHAPE>(tm, it, t);
     // aligned rows, no overhanging lanes: split ownership (see load_pair)
     constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged;
     const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
@@ -538,7 +516,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             if constexpr (CAME_STATS) x.mo = load_pair<MB16, NTM>(M, st.ia, st.ib);
             return x;
         }
-        const int64_t idx = step_index<SHAPE>(t, f, j, lcol);
+        const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
         x.g = load_grad_raw<BF16, ALIGNED, CAME_NT2>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
         if constexpr (CAME_STATS) x.mo = load_grad_raw<MB16, ALIGNED, NTM>(M, idx, lncol);
         return x;
@@ -566,7 +544,7 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     {
         float cv[8];
         if constexpr (SPLIT) unpack(load_f32_pair(c, sg.ca, sg.cb), cv);
-        else unpack(load_f32_raw<ALIGNED>(c, f.mcol, lncol), cv);
+        else unpack(load_f32_raw<ALIGNED>(c, lcol, lncol), cv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) b[e] = (SPLIT || e < t.ncol) ? rsqrtf(cv[e]) : 0.f;
     }
@@ -633,17 +611,10 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             }
             return;
         }
-        const int i = step_row<SHAPE>(t, j);
-        // (folded, odd number of rows: the lanes of the missing last row hold a copy of the row
-        // before it; a zero factor and a zeroed momentum take it out of every sum)
-        const bool row_ok = !FOLDED || i < f.mrows;
-        const float a = FOLDED ? (row_ok ? rowfac[i] : 0.f) : rowfac[i];  // rsqrt(r_i / 1^T r)
+        const int i = t.wave + kWaves * j;
+        const float a = rowfac[i];  // rsqrt(r_i / 1^T r)
         float x[8];
         unpack<BF16>(row.g, x);
-        if constexpr (FOLDED) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = row_ok ? x[e] : 0.f;
-        }
         if constexpr (CAME_STATS) {
             float mo[8];
             unpack<MB16>(row.mo, mo);
@@ -651,20 +622,14 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 if (ALIGNED && !FULL) mo[e] = lane_valid ? mo[e] : 0.f;   // (b[e] = 0 already zeroes u)
-                if (FOLDED) mo[e] = row_ok ? mo[e] : 0.f;
                 const float uf = (x[e] * a) * b[e];  // u_ij = g_ij / sqrt(v_ij)
                 const double du = static_cast<double>(uf);
                 const double dm = static_cast<double>(mo[e]);
                 rP = fma(du, du, rP); rQ = fma(du, dm, rQ); rW = fma(dm, dm, rW);
                 cP[e] = fma(du, du, cP[e]); cQ[e] = fma(du, dm, cQ[e]); cW[e] = fma(dm, dm, cW[e]);
             }
-            if (FOLDED && f.split) {  // two rows in this step: lanes 0..31 and lanes 32..63
-                rP = wave_half_sums(rP); rQ = wave_half_sums(rQ); rW = wave_half_sums(rW);
-                if ((t.lane & 31) == 31 && row_ok) { rowbuf[i] = rP; rowbuf[TR + i] = rQ; rowbuf[2 * TR + i] = rW; }
-            } else {
-                rP = wave_sum_lane63(rP); rQ = wave_sum_lane63(rQ); rW = wave_sum_lane63(rW);
-                if (t.lane == 63) { rowbuf[i] = rP; rowbuf[TR + i] = rQ; rowbuf[2 * TR + i] = rW; }
-            }
+            rP = wave_sum_lane63(rP); rQ = wave_sum_lane63(rQ); rW = wave_sum_lane63(rW);
+            if (t.lane == 63) { rowbuf[i] = rP; rowbuf[TR + i] = rQ; rowbuf[2 * TR + i] = rW; }
         } else {
             double rP = 0.0;
 #pragma unroll
@@ -672,13 +637,8 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
                 const double du = static_cast<double>((x[e] * a) * b[e]);
                 rP = fma(du, du, rP);
             }
-            if (FOLDED && f.split) {
-                rP = wave_half_sums(rP);
-                if ((t.lane & 31) == 31 && row_ok) rowbuf[i] = rP;
-            } else {
-                rP = wave_sum_lane63(rP);
-                if (t.lane == 63) rowbuf[i] = rP;
-            }
+            rP = wave_sum_lane63(rP);
+            if (t.lane == 63) rowbuf[i] = rP;
         }
     };
 
@@ -910,7 +870,6 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     // folded tiles: rows of the matrix in the tile, first of them, this lane's column in the matrix
     const int64_t mrow0 = FOLDED ? 2 * t.row0 : t.row0;
     const int mrows = FOLDED ? static_cast<int>(min(static_cast<int64_t>(2 * t.nrows), tm.n - mrow0)) : t.nrows;
-    const int64_t mcol = FOLDED ? lcol - t.rsel * m : lcol;
     // aligned rows, no overhanging lanes: split ownership (see load_pair)
     constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged;
     const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
@@ -927,9 +886,7 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             x.th = load_f32_pair(theta, st.ia, st.ib);
             return x;
         }
-        // (folded, odd number of rows: the lanes of the missing last row read the row before it)
-        const int64_t off = FOLDED ? (2 * (t.wave + kWaves * j) + 1 < mrows ? lcol : mcol) : lcol;
-        const int64_t idx = (t.row0 + t.wave + kWaves * j) * pitch + off;
+        const int64_t idx = (t.row0 + t.wave + kWaves * j) * m + lcol;
         x.g = load_grad_raw<BF16, ALIGNED, CAME_NT3>(real ? g : static_cast<const void*>(&tm), real ? idx : int64_t(0), real ? lncol : kLaneCols);
         x.mo = load_mom_raw<MB16, ALIGNED>(M, idx, lncol);
         x.th = load_f32_raw<ALIGNED>(theta, idx, lncol);
@@ -964,12 +921,12 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     {
         float cv[8];
         if constexpr (SPLIT) unpack(load_f32_pair(c, sg.ca, sg.cb), cv);
-        else unpack(load_f32_raw<ALIGNED>(c, mcol, lncol), cv);
+        else unpack(load_f32_raw<ALIGNED>(c, lcol, lncol), cv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) b[e] = (SPLIT || e < t.ncol) ? rsqrtf(cv[e]) : 0.f;
         if (came) {
             if constexpr (SPLIT) unpack(load_f32_pair(C, sg.ca, sg.cb), cv);
-            else unpack(load_f32_raw<ALIGNED>(C, mcol, lncol), cv);
+            else unpack(load_f32_raw<ALIGNED>(C, lcol, lncol), cv);
 #pragma unroll
             for (int e = 0; e < 8; ++e) Bc[e] = (SPLIT || e < t.ncol) ? rsqrtf(cv[e]) : 0.f;
         } else {
@@ -1005,12 +962,9 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             if constexpr (COPY16) store_bf16_pair(theta16, ia, ib, st.oka, st.okb, tn);
             return;
         }
-        // i: the lane's row of the matrix, counted from the tile's first
-        const int i = FOLDED ? 2 * (t.wave + kWaves * j) + t.rsel : t.wave + kWaves * j;
-        const bool row_ok = !FOLDED || i < mrows;
-        const int ic = FOLDED ? (row_ok ? i : i - 1) : i;
-        const float a = rowfac[ic];
-        const float Ar = rowfac[TR + ic];
+        const int i = t.wave + kWaves * j;
+        const float a = rowfac[i];
+        const float Ar = rowfac[TR + i];
         float x[8], mo[8], th[8], mn[8], tn[8];
         unpack<BF16>(row.g, x);
         unpack<MB16>(row.mo, mo);
@@ -1021,13 +975,8 @@ __device__ void sweep3_tile(const TensorMeta& tm, const WorkItem& it, const Tile
             mn[e] = fmaf(h.beta1, mo[e], h.one_minus_beta1 * uh);
             tn[e] = fmaf(th[e], h.decay, -((mn[e] * Ar) * Bc[e]));
         }
-        const int64_t idx = (t.row0 + t.wave + kWaves * j) * pitch + t.col;
-        if constexpr (FOLDED) {
-            const int nc = row_ok ? kLaneCols : 0;
-            store_mom<MB16, true>(M, idx, nc, mn);
-            store_f32x8<true>(theta, idx, nc, tn);
-            if constexpr (COPY16) store_bf16x8<true>(theta16, idx, nc, tn);
-        } else if constexpr (ALIGNED && FULL) {
+        const int64_t idx = (t.row0 + i) * m + t.col;
+        if constexpr (ALIGNED && FULL) {
             store_mom<MB16, true>(M, idx, kLaneCols, mn);
             store_f32x8<true>(theta, idx, kLaneCols, tn);
             if constexpr (COPY16) store_bf16x8<true>(theta16, idx, kLaneCols, tn);
@@ -1128,36 +1077,62 @@ __global__ __launch_bounds__(kWorkgroup) void placement_probe_kernel(DeviceTable
     const bool folded = it.kind == 5 || it.kind == 6;
     const int32_t tile_rows = it.kind == 4 || it.kind == 5 ? tm.tile_rows3 : tm.tile_rows;
     const TileGeom t = folded ? folded_geom(tm, it, tile_rows) : tile_geom(tm, it, tile_rows);
-    if (t.ncol == 0) return;
+    // the lane's two groups of 4 columns, as the sweeps take them: split ownership unless the
+    // matrix ends inside the tile (then 8 consecutive columns, or none)
+    const bool ragged = !folded && static_cast<int64_t>(it.cb + 1) * kTileCols > tm.m;
+    if (ragged && t.ncol == 0) return;
+    const SplitGeom sg = folded ? split_geom<true>(tm, it, t) : split_geom<false>(tm, it, t);
     const int64_t pitch = folded ? 2 * tm.m : tm.m;
+    const int mrows = folded ? static_cast<int>(min(static_cast<int64_t>(2 * t.nrows), tm.n - 2 * t.row0)) : t.nrows;
     float* theta = static_cast<float*>(tb.theta[it.tensor]);
     float* M = tb.state + tm.off_M;
     const bool mb16 = tm.flags & kFlagBf16Momentum, gb16 = tm.flags & kFlagBf16Grad;
     const CAME_GLOBAL uint16_t* g16 = glob(static_cast<const uint16_t*>(tb.grad[it.tensor]));
+    CAME_GLOBAL uint16_t* m16 = glob(reinterpret_cast<uint16_t*>(M));
     uint32_t sink = 0u;
-    for (int i = t.wave; i < t.nrows; i += kWaves) {
-        const int64_t idx = (t.row0 + i) * pitch + t.col;
-        if (folded && 2 * (t.row0 + i) + t.rsel >= tm.n) continue;  // odd number of rows: no second row in the last pair
+    for (int j = 0; t.wave + kWaves * j < t.nrows; ++j) {
+        int64_t ia, ib;
+        bool oka = true, okb = true;
+        if (ragged) {
+            ia = (t.row0 + t.wave + kWaves * j) * pitch + t.col;
+            ib = ia + 4;
+        } else {
+            const SplitStep st = folded ? split_step<true>(t, sg, j, pitch, mrows, tm.m) : split_step<false>(t, sg, j, pitch, mrows, tm.m);
+            ia = st.ia; ib = st.ib; oka = st.oka; okb = st.okb;  // (a missing row's lanes read the row before it and store nothing)
+        }
         if (with_g) {
-            const CAME_GLOBAL u32x4* pg = (const CAME_GLOBAL u32x4*)(g16 + (gb16 ? idx : 2 * idx));
-            u32x4 a = __builtin_nontemporal_load(pg);
-            sink ^= a.x ^ a.y ^ a.z ^ a.w;
-            if (!gb16) {
-                a = __builtin_nontemporal_load(pg + 1);
-                sink ^= a.x ^ a.y ^ a.z ^ a.w;
+            if (gb16) {
+                const u32x2 a = __builtin_nontemporal_load((const CAME_GLOBAL u32x2*)(g16 + ia));
+                const u32x2 b = __builtin_nontemporal_load((const CAME_GLOBAL u32x2*)(g16 + ib));
+                sink ^= a.x ^ a.y ^ b.x ^ b.y;
+            } else {
+                const u32x4 a = __builtin_nontemporal_load((const CAME_GLOBAL u32x4*)(g16 + 2 * ia));
+                const u32x4 b = __builtin_nontemporal_load((const CAME_GLOBAL u32x4*)(g16 + 2 * ib));
+                sink ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w;
             }
         }
-        CAME_GLOBAL u32x4* pm = (CAME_GLOBAL u32x4*)(glob(reinterpret_cast<uint16_t*>(M)) + (mb16 ? idx : 2 * idx));
-        CAME_GLOBAL f32x4* pt = (CAME_GLOBAL f32x4*)(glob(theta) + idx);
-        u32x4 m0 = pm[0], m1 = m0;
-        if (!mb16) m1 = pm[1];
+        u32x4 m0 = {0u, 0u, 0u, 0u}, m1 = m0;
+        if (mb16) {
+            const u32x2 a = *(const CAME_GLOBAL u32x2*)(m16 + ia), b = *(const CAME_GLOBAL u32x2*)(m16 + ib);
+            m0.x = a.x; m0.y = a.y; m1.x = b.x; m1.y = b.y;
+        } else {
+            m0 = *(const CAME_GLOBAL u32x4*)(m16 + 2 * ia);
+            m1 = *(const CAME_GLOBAL u32x4*)(m16 + 2 * ib);
+        }
         if (mode == 0) {
-            f32x4 t0 = pt[0], t1 = pt[1];
+            f32x4 t0 = *(const CAME_GLOBAL f32x4*)(glob(theta) + ia), t1 = *(const CAME_GLOBAL f32x4*)(glob(theta) + ib);
             // opaque to the optimiser, so that the stores of just-loaded values are kept
             asm volatile("" : "+v"(m0), "+v"(m1), "+v"(t0), "+v"(t1));
-            pm[0] = m0;
-            if (!mb16) pm[1] = m1;
-            pt[0] = t0; pt[1] = t1;
+            if (oka) {
+                if (mb16) *(CAME_GLOBAL u32x2*)(m16 + ia) = u32x2{m0.x, m0.y};
+                else *(CAME_GLOBAL u32x4*)(m16 + 2 * ia) = m0;
+                *(CAME_GLOBAL f32x4*)(glob(theta) + ia) = t0;
+            }
+            if (okb) {
+                if (mb16) *(CAME_GLOBAL u32x2*)(m16 + ib) = u32x2{m1.x, m1.y};
+                else *(CAME_GLOBAL u32x4*)(m16 + 2 * ib) = m1;
+                *(CAME_GLOBAL f32x4*)(glob(theta) + ib) = t1;
+            }
         } else {
             sink ^= m0.x ^ m0.y ^ m0.z ^ m0.w ^ m1.x ^ m1.y ^ m1.z ^ m1.w;
         }
