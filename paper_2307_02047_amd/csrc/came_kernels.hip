@@ -501,8 +501,10 @@ __device__ void sweep2_tile(const TensorMeta& tm, const WorkItem& it, const Tile
     const int lncol = ALIGNED ? kLaneCols : t.ncol;
     const int TR = TRL;
     const FoldInfo f = fold_info<SHAPE>(tm, it, t);
-    // aligned rows, no overhanging lanes: split ownership (see load_pair)
-    constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged;
+    // aligned rows, no overhanging lanes: split ownership (see load_pair) -- except where both
+    // arrays this sweep reads are bfloat16: split ownership would turn their dense 16-byte loads
+    // into pairs of 8-byte ones (measured: sweep 2 7 % slower); folded tiles need it all the same
+    constexpr bool SPLIT = ALIGNED && SHAPE != kTileRagged && (SHAPE == kTileFolded || !(BF16 && MB16 && CAME_STATS));
     const SplitGeom sg = split_geom<FOLDED>(tm, it, t);
 
     struct Row { GradRaw<BF16> g; GradRaw<MB16> mo; };
