@@ -232,7 +232,7 @@ class CameStep:
                  vector_rule: int = VECTOR_ALGORITHM2, resident: int = RESIDENT_AUTO, resident_wait_us: int = 0,
                  tile_rows3: int = 0, place_against=None, place_against_grads=None,
                  placement_candidates: int = 8, placement_spacer_bytes: int = 16 << 30,
-                 placement_accept_ratio: float = 1.12, placement_reserve_bytes: int = 2 << 30, blobs=None):
+                 placement_accept_ratio: float = 1.04, placement_reserve_bytes: int = 2 << 30, blobs=None):
         """blobs: (state, scratch), two uint8 tensors on `device` of at least state_size()'s bytes
         at 256-byte aligned addresses, when the caller wants to place them itself; by default
         both are allocated here.
@@ -244,7 +244,7 @@ class CameStep:
         bounded by what torch.cuda.mem_get_info reports as free (a candidate is only tried if it,
         its spacers and placement_reserve_bytes fit) and stops early at the first candidate
         that is placement_accept_ratio times faster than the first one, i.e. than the place the
-        allocator chose by itself: on MI355X the read+write sweep is ~15 % faster when theta
+        allocator chose by itself: on MI355X the read+write sweep is ~10 % faster when theta
         and the state sit in different 96 GB regions of the HBM address space.  Memory is
         only allocated and measured here; nothing about the arithmetic changes."""
         import torch
