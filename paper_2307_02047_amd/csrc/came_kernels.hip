@@ -29,8 +29,9 @@
 // Tile: 4 wave64s sweep the rows of a 512-column stripe (sweeps 1 and 2: tile_rows of them, tall
 // tiles, because every tile costs them partial sums and a chain of dependent loads; sweep 3:
 // tile_rows3, short tiles of its own, because it forms no sums and short tiles keep what it reads
-// and writes at any one time close together); lane l owns
-// columns 8l..8l+7 (one 16-byte bf16 load, two 16-byte f32 loads), wave w rows
+// and writes at any one time close together); a lane owns 8 columns of the tile (rows 16-byte
+// aligned and no overhanging lane: 4l..4l+3 and 256+4l..256+4l+3, see load_pair; otherwise
+// 8l..8l+7), wave w takes rows
 // w, w+4, ...  Row sums: 8 in-lane adds, then a wave reduction.  Column sums:
 // per-lane accumulators down the tile, combined across the 4 waves in LDS and
 // written per (row block, column); the finalize kernels add the row blocks.
