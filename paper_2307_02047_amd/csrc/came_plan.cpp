@@ -17,10 +17,10 @@ constexpr int64_t kAlignFloats = 64;  // 256-byte alignment of every state array
 constexpr int64_t kMaxItems = int64_t(1) << 26;
 
 // Rows per tile of the update sweep when the caller does not choose.  Measured on lists from 1e8
-// to 6.7e9 parameters: 32 rows are fastest or within 1 % of it everywhere (16: the per-tile
-// prologue begins to show; 64 and more: the read-and-write stream pair slows down by up to 20 %
-// when theta and M lie in the same region of the address space).
-constexpr int32_t kDefaultTileRows3 = 32;
+// to 6.7e9 parameters: 16 rows (four per wave) are fastest everywhere, by 0.5 to 3 % over 32 rows;
+// at 8 and 12 rows the per-tile prologue shows (+2 to +4 %); with 64 and more the read-and-write
+// stream pair slows down by up to 20 % when theta and M lie in the same region of the address space.
+constexpr int32_t kDefaultTileRows3 = 16;
 constexpr size_t kAlignBytes = 256;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
