@@ -128,7 +128,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama_7b")
     ap.add_argument("--tile-rows", type=int, default=0, help="rows per tile of sweeps 1 and 2 (0: chosen from the list)")
-    ap.add_argument("--tile-rows3", type=int, default=0, help="rows per tile of the update sweep (0: the library's default, 16)")
+    ap.add_argument("--tile-rows3", type=int, default=0, help="rows per tile of the update sweep (0: the library's default: 16, or 32 with the bfloat16 momentum)")
     ap.add_argument("--group-elements", type=int, default=0)
     ap.add_argument("--momentum-dtype", choices=("f32", "bf16"), default="f32",
                     help="storage type of the momentum M between steps (f32: the configuration the metric is "
@@ -331,7 +331,7 @@ def main() -> int:
             "param_state_dtype": "f32",
             "momentum_dtype": args.momentum_dtype,
             "tile_rows": plan["tile_rows"],
-            "tile_rows_update_sweep": args.tile_rows3 or 16,
+            "tile_rows_update_sweep": args.tile_rows3 or (32 if args.momentum_dtype == "bf16" else 16),
             "launch_groups": plan["groups"],
             "state_placement_probe_GBs": fig["placement_probe_GBs"],
         },
