@@ -839,7 +839,7 @@ __global__ __launch_bounds__(kWorkgroup) void finalize2_kernel(DeviceTables tb, 
 // ---------------------------------------------------------------- sweep 3
 
 #ifndef CAME_ROWS3
-#define CAME_ROWS3 2
+#define CAME_ROWS3 1
 #endif
 constexpr int kRows3 = CAME_ROWS3;
 
