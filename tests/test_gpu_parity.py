@@ -261,17 +261,20 @@ def test_state_checkpoint_round_trip():
 
 def test_grouped_launch_equals_single_group():
     """Splitting the list into launch groups changes scheduling only."""
-    w = W.Workload("groups", [(256, 512), (512,), (100, 1024), (1024,), (512, 512)], W.GRAD_BF16, seed=11,
-                   steps=3, grad_kind="normal", scale_range=(1e-3, 1e-1))
+    # (a folded width, 768, and a ragged one, 520, among them: every tile shape in every group)
+    shapes = [(256, 512), (512,), (100, 1024), (1024,), (512, 512), (131, 768), (768,), (40, 520)]
+    n = len(shapes)
+    w = W.Workload("groups", shapes, W.GRAD_BF16, seed=11, steps=3, grad_kind="normal", scale_range=(1e-3, 1e-1))
     res = []
     for ge in (0, 150_000):
         gen = W.Generator(w, device="cuda:0")
-        th = [gen.theta0(i) for i in range(5)]
-        opt = P.CameStep(w.shapes, [w.grad_dtype] * 5, group_elements=ge, tile_rows=16)
+        th = [gen.theta0(i) for i in range(n)]
+        opt = P.CameStep(w.shapes, [w.grad_dtype] * n, group_elements=ge, tile_rows=16)
         for t in range(1, 4):
-            opt.step(th, [gen.grad(i, t) for i in range(5)], P.CameHyper(), 1e-3, t)
+            opt.step(th, [gen.grad(i, t) for i in range(n)], P.CameHyper(), 1e-3, t)
         torch.cuda.synchronize()
-        res.append(th + [opt.state_view(0)["R"].clone(), opt.state_view(4)["C"].clone()])
+        res.append(th + [opt.state_view(0)["R"].clone(), opt.state_view(4)["C"].clone(), opt.state_view(5)["C"].clone(),
+                         opt.state_view(5)["r"].clone()])
         opt.close()
     for x, y in zip(*res):
         assert torch.equal(x, y)
