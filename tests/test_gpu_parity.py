@@ -259,6 +259,42 @@ def test_state_checkpoint_round_trip():
     a.close(); b1.close(); b2.close()
 
 
+def test_update_sweep_direction_changes_nothing():
+    """On short lists the update sweep walks its tiles forwards on a context's 1st, 3rd, ...
+    call and backwards on the others.  Steps 2 and 3 taken by a fresh context (its 1st
+    and 2nd call) must equal steps 2 and 3 of a context that also took step 1, bit for bit."""
+    shapes = [(300, 1024), (1024,), (131, 768), (40, 520), (9, 256)]
+    n = len(shapes)
+    w = W.Workload("direction", shapes, W.GRAD_BF16, seed=14, steps=3, grad_kind="normal",
+                   scale_range=(1e-3, 1e-1))
+    gen = W.Generator(w, device="cuda:0")
+    h = P.CameHyper()
+    dt = [w.grad_dtype] * n
+    th_a = [gen.theta0(i) for i in range(n)]
+    a = P.CameStep(w.shapes, dt)
+    for t in range(1, 4):
+        a.step(th_a, [gen.grad(i, t) for i in range(n)], h, 1e-3, t)
+    th_b = [gen.theta0(i) for i in range(n)]
+    b1 = P.CameStep(w.shapes, dt)
+    b1.step(th_b, [gen.grad(i, 1) for i in range(n)], h, 1e-3, 1)
+    b2 = P.CameStep(w.shapes, dt)
+    torch.cuda.synchronize()
+    for i in range(n):
+        src, dst = b1.state_view(i), b2.state_view(i)
+        for k in "MrcRC":
+            if src[k] is not None:
+                dst[k].copy_(src[k])
+    for t in range(2, 4):
+        b2.step(th_b, [gen.grad(i, t) for i in range(n)], h, 1e-3, t)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert torch.equal(th_a[i], th_b[i])
+        for k in "MrcRC":
+            if a.state_view(i)[k] is not None:
+                assert torch.equal(a.state_view(i)[k], b2.state_view(i)[k])
+    a.close(); b1.close(); b2.close()
+
+
 def test_grouped_launch_equals_single_group():
     """Splitting the list into launch groups changes scheduling only."""
     # (a folded width, 768, and a ragged one, 520, among them: every tile shape in every group)
