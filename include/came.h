@@ -218,6 +218,10 @@ int came_init_state(came_ctx **out, const came_tensor_desc *descs, int32_t count
  * lr is the learning rate eta; step is the 1-based iteration number t, which
  * is validated (must be >= 1) and recorded but, as in Algorithm 2, never used
  * in the arithmetic.  Asynchronous on hip_stream.
+ * On lists of at most 2^29 parameters the update sweep walks its tiles forwards on a
+ * context's 1st, 3rd, ... call and backwards on the others (it then starts on the
+ * entries the previous call left in the on-package cache); that sweep forms no sums,
+ * so results do not depend on the order, bit for bit.
  * Stream capture: a call whose parameter/gradient addresses are those of the previous call
  * on this context only enqueues kernels and may be captured into a HIP graph (no memset
  * nodes).  A call with a changed address has to wait for a free slot of the pointer table
