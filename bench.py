@@ -331,7 +331,7 @@ def main() -> int:
             "param_state_dtype": "f32",
             "momentum_dtype": args.momentum_dtype,
             "tile_rows": plan["tile_rows"],
-            "tile_rows_update_sweep": args.tile_rows3 or (32 if args.momentum_dtype == "bf16" else 16),
+            "tile_rows_update_sweep": args.tile_rows3 or (16 if args.momentum_dtype == "bf16" else 12),
             "launch_groups": plan["groups"],
             "state_placement_probe_GBs": fig["placement_probe_GBs"],
         },

@@ -163,7 +163,7 @@ typedef struct {
                                 came_device_status on the context returns CAME_ETIMEOUT */
     int32_t tile_rows3;      /* rows per tile of the update sweep (M_t, theta_t), which forms no
                                 sums and so has no per-tile results to pay for: multiple of 4,
-                                4..1024; 0 = 16 (32 under CAME_MOMENTUM_BF16).  Short tiles keep the addresses that are read and
+                                4..1024; 0 = 12 (16 under CAME_MOMENTUM_BF16).  Short tiles keep the addresses that are read and
                                 written at any one time close together, which is what the memory
                                 system wants of a stream pair that reads and writes the same
                                 arrays (tall tiles: up to 20 % slower, depending on where the

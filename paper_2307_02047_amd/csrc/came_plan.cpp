@@ -17,11 +17,13 @@ constexpr int64_t kAlignFloats = 64;  // 256-byte alignment of every state array
 constexpr int64_t kMaxItems = int64_t(1) << 26;
 
 // Rows per tile of the update sweep when the caller does not choose.  Measured on lists from 1e8
-// to 6.7e9 parameters: 16 rows (four per wave) are fastest everywhere, by 0.5 to 3 % over 32 rows;
-// at 8 and 12 rows the per-tile prologue shows (+2 to +4 %); with 64 and more the read-and-write
-// stream pair slows down by up to 20 % when theta and M lie in the same region of the address space.
-// With the momentum stored as bfloat16 (fewer bytes per row) 32 rows are 1 % faster than 16.
-constexpr int32_t kDefaultTileRows3 = 16, kDefaultTileRows3Bf16Momentum = 32;
+// to 6.7e9 parameters with one row per batch: 12 rows (three per wave) are fastest or equal
+// everywhere -- over 16 rows by 0.5 % where theta and M lie in different regions of the address
+// space and by 1 to 2 % where they lie in the same one; at 8 rows the per-tile prologue shows
+// (+3 %); with 64 and more the read-and-write stream pair slows down by up to 20 % in the same
+// region.  With the momentum stored as bfloat16 (fewer bytes per row) the optimum is 16 rows
+// (2 % faster than 32, 1 % faster than 12).
+constexpr int32_t kDefaultTileRows3 = 12, kDefaultTileRows3Bf16Momentum = 16;
 constexpr size_t kAlignBytes = 256;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
